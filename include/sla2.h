@@ -1,0 +1,143 @@
+/*
+ * libsla2 - SLA2 attention forward pass on MI355X (gfx950), C ABI.
+ *
+ * The operator is  O = SLA2(Q, K, V, k%, R, alpha)  of the paper
+ * "SLA2: Sparse-Linear Attention with Learnable Routing and QAT":
+ *
+ *   O   = alpha (.) O_s + (1 - alpha) (.) O_l                      (Eq. 13)
+ *   O_s = softmax(Q K^T / sqrt(d) restricted to M = 1) V           (Eq. 14)
+ *   O_l = norm(phi(Q) phi(K)^T (.) (1 - M)) V,  phi = softmax_d    (Eq. 14)
+ *   M   = expansion of M_c = Top-k(k%, proj_q(pool Q) proj_k(pool K)^T)   (Eq. 15-16)
+ *
+ * computed block-wise as in the paper's forward algorithm (Alg. 2), with K
+ * first replaced by K - colmean(K).
+ *
+ * Conventions for every entry point
+ *   - q, k, v, out are DEVICE pointers to contiguous [B, H, N, d] tensors of
+ *     params->dtype; router_w, alpha, block_idx, lse, workspace are DEVICE
+ *     pointers; params is a HOST pointer.  All memory is owned by the caller;
+ *     the library allocates nothing, frees nothing and never synchronises.
+ *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and completes in stream order.
+ *   - Arguments are validated on the host before anything is launched.  The
+ *     return value is SLA2_OK (0) or a negative sla2_status; on an error no
+ *     kernel has been launched (except SLA2_EHIP, which reports a failed
+ *     launch).  No exceptions, no errno, no logging.
+ *   - `workspace` must hold at least sla2_workspace_bytes(params) bytes and be
+ *     256-byte aligned; its contents after a call are described by
+ *     sla2_workspace_layout() and may be read by the caller (tests do).
+ *     Calls that share a workspace must not overlap in time.
+ */
+#ifndef SLA2_H
+#define SLA2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SLA2_OK = 0,
+  SLA2_EINVAL = -1,       /* null pointer, non-positive size, topk_frac outside [0,1], bad enum */
+  SLA2_EUNSUPPORTED = -2, /* a shape / mode combination the kernels do not cover (see sla2_params) */
+  SLA2_EWORKSPACE = -3,   /* workspace null, misaligned or smaller than sla2_workspace_bytes() */
+  SLA2_EALIAS = -4,       /* out overlaps q, k or v */
+  SLA2_EHIP = -5          /* a kernel launch failed */
+} sla2_status;
+
+typedef enum { SLA2_F32 = 0, SLA2_BF16 = 1 } sla2_dtype;   /* element type of q, k, v, out */
+
+/* Precision of the sparse branch (Sec. 5 of the paper, "Quantization-aware training").
+ *   SLA2_QUANT_NONE  Q K^T and P V in the storage type with fp32 accumulation.
+ *   SLA2_QUANT_FP8   Q and the smoothed K as FP8 e4m3 (OCP; max 448) with one
+ *                    scale per b_q x d block of Q and per b_kv x d block of K:
+ *                    amax = max|x| over the block, stored value = rne(x * (448/amax)),
+ *                    dequantisation scale amax/448, both divisions in fp32;
+ *                    P rounded to e4m3 after scaling by 2^8; V kept in bf16;
+ *                    the softmax denominator uses the un-rounded P.
+ *                    Requires dtype = SLA2_BF16. */
+typedef enum { SLA2_QUANT_NONE = 0, SLA2_QUANT_FP8 = 1 } sla2_quant;
+
+#define SLA2_FLAG_NO_SMOOTH_K 1u   /* skip K <- K - colmean(K) (first step of Alg. 2) */
+
+typedef struct sla2_params {
+  int B, H, N, d;          /* batch, heads, tokens, head dim.  d in {64, 128}; N >= 1;
+                              ceil(N / block_kv) <= 2048 */
+  int block_q, block_kv;   /* b_q, b_kv of the paper: (64, 64) or (128, 64) */
+  float topk_frac;         /* k% as a fraction in [0, 1]; each query block keeps
+                              k = floor(topk_frac * T_n + 0.5) key/value blocks, T_n = ceil(N / block_kv) */
+  int dtype;               /* sla2_dtype */
+  int quant_mode;          /* sla2_quant */
+  int router_w_per_head;   /* 0: router_w is [2, d, d], shared by all heads; 1: [H, 2, d, d] */
+  int alpha_per_block;     /* 0: alpha is [H]; 1: alpha is [H, T_m], T_m = ceil(N / block_q)
+                              (Alg. 2 takes one alpha per query block) */
+  unsigned flags;          /* SLA2_FLAG_* */
+} sla2_params;
+
+/* Byte offsets, inside the workspace, of what a call leaves behind.  All are
+ * multiples of 256.  "BH" = B*H, T_m / T_n = number of query / key blocks. */
+typedef struct sla2_ws_layout {
+  size_t q_sum;     /* double [BH, T_m, d]   sum of the rows of each query block            (Eq. 15 x block size) */
+  size_t k_sum;     /* double [BH, T_n, d]   same for the raw K blocks */
+  size_t k_mean;    /* double [BH, d]        colmean(K) (zeros with SLA2_FLAG_NO_SMOOTH_K)  (Alg. 2, smoothing) */
+  size_t q_proj;    /* double [BH, T_m, d]   proj_q(pool Q) / sqrt(d)                       (Eq. 16) */
+  size_t k_proj;    /* double [BH, T_n, d]   proj_k(pool(K - colmean K)) */
+  size_t block_idx; /* int32  [BH, T_m, k]   ascending selected key/value blocks (M_c)      (Eq. 16) */
+  size_t h_total;   /* float  [BH, d, d]     sum over all key blocks of (K^phi_j)^T V_j     (Alg. 2: h) */
+  size_t z_total;   /* float  [BH, d]        sum over all key blocks of colsum(K^phi_j)     (Alg. 2: z) */
+  size_t k_stats;   /* float  [BH, N, 2]     per key token: max_c(k'_c) and 1 / sum_c exp(k'_c - max) */
+  size_t k_fp8;     /* uint8  [BH, T_n*block_kv, d]  e4m3 codes of the smoothed K (FP8 mode only; rows >= N are 0) */
+  size_t k_scale;   /* float  [BH, T_n]      dequantisation scale of each key block (FP8 mode only) */
+  size_t partial;   /* scratch for per-chunk partial sums of h and z */
+  size_t total;     /* = sla2_workspace_bytes() */
+} sla2_ws_layout;
+
+/* Pure host functions.  Return 0 / fill `out` with zeros when params is invalid. */
+size_t sla2_workspace_bytes(const sla2_params* params);
+int sla2_workspace_layout(const sla2_params* params, sla2_ws_layout* out);
+/* k of Eq. 16 for these parameters (floor(topk_frac * T_n + 0.5), clamped); negative sla2_status on error. */
+int sla2_num_selected(const sla2_params* params);
+
+/* Learnable router (Sec. 4, Eq. 15-16; router step of Alg. 2): mean-pool Q over
+ * block_q tokens and K - colmean(K) over block_kv tokens (a ragged last block is
+ * averaged over the tokens it has), project with router_w = [Wq | Wk] (each
+ * [d_in, d_out] row-major fp32, proj(x) = x W, no bias), score
+ * R = proj_q(Qbar) proj_k(Kbar)^T / sqrt(d) and keep, per query block, the k
+ * largest scores; equal scores go to the lower block index.  The row softmax of
+ * Alg. 2 is omitted: it does not change a row-wise top-k.  All arithmetic is
+ * fp64 so that the selection matches an fp64 reference up to summation order.
+ * block_idx: int32 [B, H, T_m, k], each row ascending.  With k = 0 nothing is written. */
+int sla2_router(const sla2_params* params, const void* q, const void* k, const float* router_w,
+                int32_t* block_idx, void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* The whole forward pass (Alg. 2; Eq. 13-16): router as above, then for every
+ * query block the sparse branch over its selected key/value blocks in ascending
+ * order (online softmax), the linear branch over the others - formed as the
+ * per-head total of h_j, z_j minus the selected blocks - and the alpha mix.
+ * alpha values are used as given (the caller keeps them in [0,1]).  A query
+ * block with no selected block has O_s = 0; one with every block selected has
+ * O_l = 0.
+ * out:               [B, H, N, d] of params->dtype.
+ * block_idx_or_null: if non-null receives the mask as in sla2_router.
+ * lse_or_null:       if non-null receives float [B, H, N]: L = m + log l of the
+ *                    sparse branch (the L_i of Alg. 2), -inf when k = 0. */
+int sla2_forward(const sla2_params* params, const void* q, const void* k, const void* v,
+                 const float* router_w, const float* alpha, void* out,
+                 int32_t* block_idx_or_null, float* lse_or_null,
+                 void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Dense attention softmax(Q K^T / sqrt(d)) V with the same tile machinery: the
+ * comparator the paper measures speed-ups against (Sec. 8.1: "C = 4 N^2 d").
+ * Uses B, H, N, d, dtype of params (dtype must be SLA2_BF16); needs no workspace. */
+int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, const void* v,
+                       void* out, void* hip_stream);
+
+const char* sla2_strerror(int status);
+int sla2_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLA2_H */

@@ -1,0 +1,59 @@
+// Shared declarations of the SLA2 HIP kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/sla2.h"
+
+namespace sla2 {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) double f64x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+constexpr int kWave = 64;
+constexpr int kMaxKeyBlocks = 2048;   // router keeps a whole score row in registers
+constexpr float kE4M3Max = 448.0f;
+constexpr float kLog2e = 1.4426950408889634f;
+
+// Host-side description of one call, derived from sla2_params.
+struct Shape {
+  int B, H, N, d, bq, bk;
+  int BH, Tm, Tn, k;
+  bool bf16, fp8, smooth, w_per_head, alpha_per_block;
+  // kv precompute: each workgroup reduces `blocks_per_chunk` key blocks; `chunks` per head
+  int blocks_per_chunk, chunks;
+};
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
+  return __builtin_bit_cast(float, (uint32_t)b << 16);
+}
+// round to nearest even; inputs are finite
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float load_elem(const float* p, size_t i) { return p[i]; }
+__device__ __forceinline__ float load_elem(const uint16_t* p, size_t i) { return bf16_bits_to_f32(p[i]); }
+__device__ __forceinline__ void store_elem(float* p, size_t i, float v) { p[i] = v; }
+__device__ __forceinline__ void store_elem(uint16_t* p, size_t i, float v) { p[i] = f32_to_bf16_bits(v); }
+
+// ---- launchers (one per kernel file); all enqueue on `stream` and return hipGetLastError() ----
+hipError_t launch_block_sums(const Shape& s, const void* q, const void* k, double* q_sum, double* k_sum, hipStream_t stream);
+hipError_t launch_col_mean(const Shape& s, const double* k_sum, double* k_mean, hipStream_t stream);
+hipError_t launch_project(const Shape& s, const double* q_sum, const double* k_sum, const double* k_mean,
+                          const float* router_w, double* q_proj, double* k_proj, hipStream_t stream);
+hipError_t launch_router_topk(const Shape& s, const double* q_proj, const double* k_proj, int32_t* block_idx,
+                              hipStream_t stream);
+hipError_t launch_kv_state_f32(const Shape& s, const float* k, const float* v, const double* k_mean, float* k_stats,
+                               float* partial, float* h_total, float* z_total, hipStream_t stream);
+hipError_t launch_attn_f32(const Shape& s, const float* q, const float* k, const float* v, const double* k_mean,
+                           const float* k_stats, const float* h_total, const float* z_total, const int32_t* block_idx,
+                           const float* alpha, float* out, float* lse, hipStream_t stream);
+
+}  // namespace sla2

@@ -1,0 +1,205 @@
+// Host side of libsla2: argument validation, workspace carve-up, kernel launches.
+// Declarations and their contracts are in include/sla2.h.
+#include <math.h>
+#include <string.h>
+
+#include "common.h"
+
+namespace sla2 {
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+// Validate everything that does not need pointers and derive the block counts.
+static int make_shape(const sla2_params* p, Shape* s) {
+  if (!p) return SLA2_EINVAL;
+  if (p->B < 1 || p->H < 1 || p->N < 1) return SLA2_EINVAL;
+  if (!(p->topk_frac >= 0.0f && p->topk_frac <= 1.0f)) return SLA2_EINVAL;   // also rejects NaN
+  if (p->dtype != SLA2_F32 && p->dtype != SLA2_BF16) return SLA2_EINVAL;
+  if (p->quant_mode != SLA2_QUANT_NONE && p->quant_mode != SLA2_QUANT_FP8) return SLA2_EINVAL;
+  if (p->router_w_per_head != 0 && p->router_w_per_head != 1) return SLA2_EINVAL;
+  if (p->alpha_per_block != 0 && p->alpha_per_block != 1) return SLA2_EINVAL;
+  if (p->flags & ~SLA2_FLAG_NO_SMOOTH_K) return SLA2_EINVAL;
+  if (p->d != 64 && p->d != 128) return SLA2_EUNSUPPORTED;
+  if (!((p->block_q == 64 || p->block_q == 128) && p->block_kv == 64)) return SLA2_EUNSUPPORTED;
+  if (p->quant_mode == SLA2_QUANT_FP8 && p->dtype != SLA2_BF16) return SLA2_EUNSUPPORTED;
+  if ((long long)p->B * p->H > 65535) return SLA2_EUNSUPPORTED;
+  s->B = p->B; s->H = p->H; s->N = p->N; s->d = p->d; s->bq = p->block_q; s->bk = p->block_kv;
+  s->BH = p->B * p->H;
+  s->Tm = (p->N + p->block_q - 1) / p->block_q;
+  s->Tn = (p->N + p->block_kv - 1) / p->block_kv;
+  if (s->Tn > kMaxKeyBlocks) return SLA2_EUNSUPPORTED;
+  int k = (int)floor((double)p->topk_frac * (double)s->Tn + 0.5);
+  s->k = k < 0 ? 0 : (k > s->Tn ? s->Tn : k);
+  s->bf16 = p->dtype == SLA2_BF16;
+  s->fp8 = p->quant_mode == SLA2_QUANT_FP8;
+  s->smooth = !(p->flags & SLA2_FLAG_NO_SMOOTH_K);
+  s->w_per_head = p->router_w_per_head != 0;
+  s->alpha_per_block = p->alpha_per_block != 0;
+  // key blocks per kv-precompute workgroup: aim at ~512 workgroups, at most 32 blocks each
+  long long total_blocks = (long long)s->BH * s->Tn;
+  int bpc = (int)((total_blocks + 511) / 512);
+  if (bpc < 1) bpc = 1;
+  if (bpc > 32) bpc = 32;
+  s->blocks_per_chunk = bpc;
+  s->chunks = (s->Tn + bpc - 1) / bpc;
+  return SLA2_OK;
+}
+
+static void make_layout(const Shape& s, sla2_ws_layout* L) {
+  size_t off = 0, BH = (size_t)s.BH, d = (size_t)s.d;
+  auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+  L->q_sum = take(BH * s.Tm * d * sizeof(double));
+  L->k_sum = take(BH * s.Tn * d * sizeof(double));
+  L->k_mean = take(BH * d * sizeof(double));
+  L->q_proj = take(BH * s.Tm * d * sizeof(double));
+  L->k_proj = take(BH * s.Tn * d * sizeof(double));
+  L->block_idx = take(BH * s.Tm * (size_t)(s.k > 0 ? s.k : 1) * sizeof(int32_t));
+  L->h_total = take(BH * d * d * sizeof(float));
+  L->z_total = take(BH * d * sizeof(float));
+  L->k_stats = take(BH * (size_t)s.N * 2 * sizeof(float));
+  L->k_fp8 = take(s.fp8 ? BH * (size_t)s.Tn * s.bk * d : 0);
+  L->k_scale = take(s.fp8 ? BH * (size_t)s.Tn * sizeof(float) : 0);
+  L->partial = take(BH * (size_t)s.chunks * (d * d + d) * sizeof(float));
+  L->total = off;
+}
+
+static bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
+  uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
+  return x < y + nb && y < x + na;
+}
+
+static int check_workspace(const sla2_ws_layout& L, const void* ws, size_t bytes) {
+  if (!ws || ((uintptr_t)ws & 255) || bytes < L.total) return SLA2_EWORKSPACE;
+  return SLA2_OK;
+}
+
+template <class T>
+static T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
+
+// pool -> colmean -> project -> scores + top-k.  Leaves the index lists in the workspace.
+static int run_router(const Shape& s, const sla2_ws_layout& L, const void* q, const void* k, const float* router_w,
+                      void* ws, hipStream_t st) {
+  double* q_sum = at<double>(ws, L.q_sum);
+  double* k_sum = at<double>(ws, L.k_sum);
+  double* k_mean = at<double>(ws, L.k_mean);
+  double* q_proj = at<double>(ws, L.q_proj);
+  double* k_proj = at<double>(ws, L.k_proj);
+  if (launch_block_sums(s, q, k, q_sum, k_sum, st) != hipSuccess) return SLA2_EHIP;
+  if (launch_col_mean(s, k_sum, k_mean, st) != hipSuccess) return SLA2_EHIP;
+  if (s.k > 0) {
+    if (launch_project(s, q_sum, k_sum, k_mean, router_w, q_proj, k_proj, st) != hipSuccess) return SLA2_EHIP;
+    if (launch_router_topk(s, q_proj, k_proj, at<int32_t>(ws, L.block_idx), st) != hipSuccess) return SLA2_EHIP;
+  }
+  return SLA2_OK;
+}
+
+}  // namespace sla2
+
+using namespace sla2;
+
+extern "C" {
+
+size_t sla2_workspace_bytes(const sla2_params* params) {
+  Shape s; sla2_ws_layout L;
+  if (make_shape(params, &s) != SLA2_OK) return 0;
+  make_layout(s, &L);
+  return L.total;
+}
+
+int sla2_workspace_layout(const sla2_params* params, sla2_ws_layout* out) {
+  if (!out) return SLA2_EINVAL;
+  memset(out, 0, sizeof(*out));
+  Shape s;
+  int rc = make_shape(params, &s);
+  if (rc != SLA2_OK) return rc;
+  make_layout(s, out);
+  return SLA2_OK;
+}
+
+int sla2_num_selected(const sla2_params* params) {
+  Shape s;
+  int rc = make_shape(params, &s);
+  return rc != SLA2_OK ? rc : s.k;
+}
+
+int sla2_router(const sla2_params* params, const void* q, const void* k, const float* router_w, int32_t* block_idx,
+                void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Shape s; sla2_ws_layout L;
+  int rc = make_shape(params, &s);
+  if (rc != SLA2_OK) return rc;
+  if (!q || !k || !router_w || (!block_idx && s.k > 0)) return SLA2_EINVAL;
+  make_layout(s, &L);
+  if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = run_router(s, L, q, k, router_w, workspace, st)) != SLA2_OK) return rc;
+  if (s.k > 0) {
+    size_t bytes = (size_t)s.BH * s.Tm * s.k * sizeof(int32_t);
+    if (hipMemcpyAsync(block_idx, at<int32_t>(workspace, L.block_idx), bytes, hipMemcpyDeviceToDevice, st) != hipSuccess)
+      return SLA2_EHIP;
+  }
+  return SLA2_OK;
+}
+
+int sla2_forward(const sla2_params* params, const void* q, const void* k, const void* v, const float* router_w,
+                 const float* alpha, void* out, int32_t* block_idx_or_null, float* lse_or_null, void* workspace,
+                 size_t workspace_bytes, void* hip_stream) {
+  Shape s; sla2_ws_layout L;
+  int rc = make_shape(params, &s);
+  if (rc != SLA2_OK) return rc;
+  if (!q || !k || !v || !router_w || !alpha || !out) return SLA2_EINVAL;
+  size_t tensor_bytes = (size_t)s.BH * s.N * s.d * (s.bf16 ? 2 : 4);
+  if (overlaps(out, tensor_bytes, q, tensor_bytes) || overlaps(out, tensor_bytes, k, tensor_bytes) ||
+      overlaps(out, tensor_bytes, v, tensor_bytes))
+    return SLA2_EALIAS;
+  make_layout(s, &L);
+  if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  if ((rc = run_router(s, L, q, k, router_w, workspace, st)) != SLA2_OK) return rc;
+  int32_t* idx = at<int32_t>(workspace, L.block_idx);
+  if (block_idx_or_null && s.k > 0) {
+    size_t bytes = (size_t)s.BH * s.Tm * s.k * sizeof(int32_t);
+    if (hipMemcpyAsync(block_idx_or_null, idx, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return SLA2_EHIP;
+  }
+  const double* k_mean = at<double>(workspace, L.k_mean);
+  float* k_stats = at<float>(workspace, L.k_stats);
+  float* h_total = at<float>(workspace, L.h_total);
+  float* z_total = at<float>(workspace, L.z_total);
+  float* partial = at<float>(workspace, L.partial);
+  if (!s.bf16) {
+    if (launch_kv_state_f32(s, (const float*)k, (const float*)v, k_mean, k_stats, partial, h_total, z_total, st) !=
+        hipSuccess)
+      return SLA2_EHIP;
+    if (launch_attn_f32(s, (const float*)q, (const float*)k, (const float*)v, k_mean, k_stats, h_total, z_total, idx,
+                        alpha, (float*)out, lse_or_null, st) != hipSuccess)
+      return SLA2_EHIP;
+    return SLA2_OK;
+  }
+  return SLA2_EUNSUPPORTED;
+}
+
+int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, const void* v, void* out,
+                       void* hip_stream) {
+  Shape s;
+  int rc = make_shape(params, &s);
+  if (rc != SLA2_OK) return rc;
+  if (!q || !k || !v || !out) return SLA2_EINVAL;
+  if (!s.bf16) return SLA2_EUNSUPPORTED;
+  (void)hip_stream;
+  return SLA2_EUNSUPPORTED;
+}
+
+const char* sla2_strerror(int status) {
+  switch (status) {
+    case SLA2_OK: return "ok";
+    case SLA2_EINVAL: return "invalid argument";
+    case SLA2_EUNSUPPORTED: return "unsupported shape or mode";
+    case SLA2_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case SLA2_EALIAS: return "out overlaps an input";
+    case SLA2_EHIP: return "kernel launch failed";
+    default: return "unknown status";
+  }
+}
+
+int sla2_version(void) { return 1; }
+
+}  // extern "C"

@@ -1,0 +1,53 @@
+"""Shared plumbing of the GPU parity tests: run the oracle per head, compare
+masks under the tie rule, error metrics."""
+import numpy as np
+
+import sla2_oracle as O
+from paper_2602_12675_amd import workloads as W
+
+TIE_WINDOW = 1e-6     # router scores closer than this to the k-th largest may go either way
+
+
+def oracle_heads(inp: W.Inputs, quant=None, smooth=True, alpha=None, heads=None, q_blocks=None,
+                 topk_frac=None):
+    """Oracle results for the chosen (b, h) pairs: dict (b, h) -> forward_head dict."""
+    w = inp.workload
+    quant = {"none": O.QUANT_NONE, "fp8": O.QUANT_FP8}[w.quant] if quant is None else quant
+    Wq = inp.router_w[0].astype(np.float64)
+    Wk = inp.router_w[1].astype(np.float64)
+    alpha = inp.alpha if alpha is None else alpha
+    res = {}
+    pairs = heads if heads is not None else [(b, h) for b in range(w.B) for h in range(w.H)]
+    for (b, h) in pairs:
+        res[(b, h)] = O.forward_head(inp.values("q", b, h), inp.values("k", b, h), inp.values("v", b, h),
+                                     Wq, Wk, alpha[h], w.topk_frac if topk_frac is None else topk_frac,
+                                     w.block_q, w.block_kv, quant=quant, smooth=smooth, q_blocks=q_blocks)
+    return res
+
+
+def check_mask(gpu_idx: np.ndarray, R: np.ndarray, oracle_sel: np.ndarray):
+    """gpu_idx, oracle_sel: [T_m, k]; R: [T_m, T_n] oracle scores.  Every row of
+    the GPU list must be k distinct ascending in-range indices, and may differ
+    from the oracle's only on entries whose oracle score lies within
+    TIE_WINDOW of the oracle's k-th largest score of that row.
+    Returns the number of rows that differ (all inside the tie window)."""
+    T_m, T_n = R.shape
+    k = oracle_sel.shape[1]
+    assert gpu_idx.shape == (T_m, k)
+    differing = 0
+    for i in range(T_m):
+        g = gpu_idx[i]
+        assert np.all(g[1:] > g[:-1]) if k > 1 else True, "row %d not strictly ascending" % i
+        assert k == 0 or (g[0] >= 0 and g[-1] < T_n)
+        if np.array_equal(g, oracle_sel[i]):
+            continue
+        differing += 1
+        kth = np.sort(R[i])[::-1][k - 1]
+        sym = np.setxor1d(g, oracle_sel[i])
+        assert np.all(np.abs(R[i, sym] - kth) <= TIE_WINDOW), \
+            "row %d differs outside the tie window: %s" % (i, sym)
+    return differing
+
+
+def rel_l2(a, b):
+    return float(np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-30))

@@ -1,0 +1,104 @@
+"""Host-side checks of the C ABI: the library loads, exports every symbol the
+header declares, and rejects bad arguments before touching a device.  No
+compute call is made here (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def api():
+    lib = os.path.join(ROOT, "paper_2602_12675_amd", "libsla2.so")
+    if not os.path.exists(lib):
+        from paper_2602_12675_amd.build import build_library
+        build_library(verbose=False)
+    from paper_2602_12675_amd import api
+    return api
+
+
+def header_functions():
+    src = open(os.path.join(ROOT, "include", "sla2.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(sla2_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_every_declared_symbol_is_exported(api):
+    names = header_functions()
+    assert set(names) == set(api.EXPORTS)
+    lib = ctypes.CDLL(api.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert api.sla2_version() >= 1
+
+
+def test_struct_sizes_match_header(api):
+    assert ctypes.sizeof(api.Params) == 12 * 4
+    assert ctypes.sizeof(api.WsLayout) == 13 * ctypes.sizeof(ctypes.c_size_t)
+
+
+def test_num_selected_and_workspace(api):
+    p = api.make_params(1, 12, 32760, 128, 128, 64, 0.03)
+    assert api.sla2_num_selected(p) == 15
+    p.topk_frac = 0.05
+    assert api.sla2_num_selected(p) == 26
+    p = api.make_params(1, 40, 75600, 128, 128, 64, 0.03)
+    assert api.sla2_num_selected(p) == 35
+    p = api.make_params(1, 2, 1024, 64, 64, 64, 0.125, dtype=api.SLA2_F32)
+    assert api.sla2_num_selected(p) == 2
+    L = api.sla2_workspace_layout(p)
+    assert L.total == api.sla2_workspace_bytes(p) > 0
+    offs = [getattr(L, n) for n, _ in api.WsLayout._fields_]
+    assert all(o % 256 == 0 for o in offs)
+    assert offs == sorted(offs)
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(d=96), "EUNSUPPORTED"), (dict(block_q=32), "EUNSUPPORTED"), (dict(block_kv=128), "EUNSUPPORTED"),
+    (dict(topk_frac=1.5), "EINVAL"), (dict(topk_frac=-0.1), "EINVAL"), (dict(topk_frac=float("nan")), "EINVAL"),
+    (dict(N=0), "EINVAL"), (dict(B=0), "EINVAL"), (dict(dtype=7), "EINVAL"), (dict(quant_mode=3), "EINVAL"),
+    (dict(flags=8), "EINVAL"), (dict(N=64 * 2048 + 1), "EUNSUPPORTED"),
+    (dict(dtype=0, quant_mode=1), "EUNSUPPORTED"),
+])
+def test_bad_parameters_are_rejected_on_the_host(api, kw, status):
+    base = dict(B=1, H=2, N=1024, d=64, block_q=64, block_kv=64, topk_frac=0.125, dtype=api.SLA2_BF16)
+    base.update(kw)
+    p = api.make_params(**base)
+    assert api.sla2_workspace_bytes(p) == 0
+    # pointers are never dereferenced on the host: dummy non-null addresses are enough
+    rc = api.sla2_forward(p, 256, 256, 256, 256, 256, 4096, workspace=None, check=False)
+    assert rc == getattr(api, "SLA2_" + status)
+    assert api.sla2_strerror(rc) != "unknown status"
+
+
+def test_null_alias_and_workspace_errors(api):
+    p = api.make_params(1, 2, 1024, 64, 64, 64, 0.125, dtype=api.SLA2_F32)
+    need = api.sla2_workspace_bytes(p)
+    lib = ctypes.CDLL(api.LIB_PATH)
+    lib.sla2_forward.restype = ctypes.c_int
+    vp = ctypes.c_void_p
+    lib.sla2_forward.argtypes = [ctypes.POINTER(api.Params)] + [vp] * 9 + [ctypes.c_size_t, vp]
+    tensor = 1 * 2 * 1024 * 64 * 4
+    q, k, v, out = 1 << 20, 2 << 20, 3 << 20, 4 << 20
+    ws = 16 << 20
+    ok_args = [q, k, v, 256, 512, out, None, None, ws, need, None]
+
+    def call(args):
+        return lib.sla2_forward(ctypes.byref(p), *args)
+    a = list(ok_args); a[0] = None
+    assert call(a) == api.SLA2_EINVAL
+    a = list(ok_args); a[5] = None
+    assert call(a) == api.SLA2_EINVAL
+    a = list(ok_args); a[5] = q + tensor - 4           # out overlaps the end of q
+    assert call(a) == api.SLA2_EALIAS
+    a = list(ok_args); a[5] = v
+    assert call(a) == api.SLA2_EALIAS
+    a = list(ok_args); a[8] = None
+    assert call(a) == api.SLA2_EWORKSPACE
+    a = list(ok_args); a[9] = need - 1
+    assert call(a) == api.SLA2_EWORKSPACE
+    a = list(ok_args); a[8] = ws + 8                   # misaligned
+    assert call(a) == api.SLA2_EWORKSPACE
