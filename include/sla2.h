@@ -87,7 +87,7 @@ typedef struct sla2_ws_layout {
   size_t block_idx; /* int32  [BH, T_m, k]   ascending selected key/value blocks (M_c)      (Eq. 16) */
   size_t h_total;   /* float  [BH, d, d]     sum over all key blocks of (K^phi_j)^T V_j     (Alg. 2: h) */
   size_t z_total;   /* float  [BH, d]        sum over all key blocks of colsum(K^phi_j)     (Alg. 2: z) */
-  size_t k_stats;   /* float  [BH, N, 2]     per key token: max_c(k'_c) and 1 / sum_c exp(k'_c - max) */
+  size_t k_stats;   /* float  [BH, N]        per key token: lnZ = log sum_c exp(k'_c), k' = k - colmean(K); K^phi = exp(k' - lnZ) */
   size_t k_fp8;     /* uint8  [BH, T_n*block_kv, d]  e4m3 codes of the smoothed K (FP8 mode only; rows >= N are 0) */
   size_t k_scale;   /* float  [BH, T_n]      dequantisation scale of each key block (FP8 mode only) */
   size_t partial;   /* scratch for per-chunk partial sums of h and z */

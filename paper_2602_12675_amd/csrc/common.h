@@ -56,4 +56,15 @@ hipError_t launch_attn_f32(const Shape& s, const float* q, const float* k, const
                            const float* k_stats, const float* h_total, const float* z_total, const int32_t* block_idx,
                            const float* alpha, float* out, float* lse, hipStream_t stream);
 
+hipError_t launch_kv_total(const Shape& s, const float* partial, float* h_total, float* z_total, hipStream_t stream);
+hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_t* v, const double* k_mean,
+                                float* k_stats, float* partial, float* h_total, float* z_total, uint8_t* k_fp8,
+                                float* k_scale, hipStream_t stream);
+hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                            const double* k_mean, const float* k_stats, const float* h_total, const float* z_total,
+                            const int32_t* block_idx, const float* alpha, uint16_t* out, float* lse,
+                            hipStream_t stream);
+hipError_t launch_dense_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
+                             hipStream_t stream);
+
 }  // namespace sla2

@@ -56,7 +56,7 @@ static void make_layout(const Shape& s, sla2_ws_layout* L) {
   L->block_idx = take(BH * s.Tm * (size_t)(s.k > 0 ? s.k : 1) * sizeof(int32_t));
   L->h_total = take(BH * d * d * sizeof(float));
   L->z_total = take(BH * d * sizeof(float));
-  L->k_stats = take(BH * (size_t)s.N * 2 * sizeof(float));
+  L->k_stats = take(BH * (size_t)s.N * sizeof(float));
   L->k_fp8 = take(s.fp8 ? BH * (size_t)s.Tn * s.bk * d : 0);
   L->k_scale = take(s.fp8 ? BH * (size_t)s.Tn * sizeof(float) : 0);
   L->partial = take(BH * (size_t)s.chunks * (d * d + d) * sizeof(float));
@@ -174,7 +174,14 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
       return SLA2_EHIP;
     return SLA2_OK;
   }
-  return SLA2_EUNSUPPORTED;
+  if (s.fp8) return SLA2_EUNSUPPORTED;
+  if (launch_kv_state_bf16(s, (const uint16_t*)k, (const uint16_t*)v, k_mean, k_stats, partial, h_total, z_total,
+                           at<uint8_t>(workspace, L.k_fp8), at<float>(workspace, L.k_scale), st) != hipSuccess)
+    return SLA2_EHIP;
+  if (launch_attn_bf16(s, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, k_mean, k_stats, h_total,
+                       z_total, idx, alpha, (uint16_t*)out, lse_or_null, st) != hipSuccess)
+    return SLA2_EHIP;
+  return SLA2_OK;
 }
 
 int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, const void* v, void* out,
@@ -184,8 +191,14 @@ int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, 
   if (rc != SLA2_OK) return rc;
   if (!q || !k || !v || !out) return SLA2_EINVAL;
   if (!s.bf16) return SLA2_EUNSUPPORTED;
-  (void)hip_stream;
-  return SLA2_EUNSUPPORTED;
+  size_t tensor_bytes = (size_t)s.BH * s.N * s.d * 2;
+  if (overlaps(out, tensor_bytes, q, tensor_bytes) || overlaps(out, tensor_bytes, k, tensor_bytes) ||
+      overlaps(out, tensor_bytes, v, tensor_bytes))
+    return SLA2_EALIAS;
+  if (launch_dense_bf16(s, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)out,
+                        (hipStream_t)hip_stream) != hipSuccess)
+    return SLA2_EHIP;
+  return SLA2_OK;
 }
 
 const char* sla2_strerror(int status) {

@@ -13,7 +13,7 @@ constexpr int kRowsF32 = 64;      // query rows per workgroup in the fp32 attent
 
 // ---------------------------------------------------------------------------------------------
 // kv_state_f32: for a chunk of key blocks of one head
-//   k' = k - colmean(K);  stats[token] = (max_c k'_c, 1 / sum_c exp(k'_c - max));
+//   k' = k - colmean(K);  stats[token] = lnZ = log sum_c exp(k'_c);
 //   K^phi = softmax_d(k');  partial h += (K^phi_j)^T V_j,  partial z += colsum(K^phi_j)
 // (Alg. 2: K^phi, h, z).  Tokens past N contribute nothing.
 // ---------------------------------------------------------------------------------------------
@@ -66,10 +66,7 @@ __global__ __launch_bounds__(256) void kv_state_f32_kernel(const float* __restri
       const float inv = 1.f / sum;
       const bool ok = t < valid;
       for (int c = sub; c < D; c += 4) ks[t * LD + c] = ok ? ks[t * LD + c] * inv : 0.f;
-      if (ok && sub == 0) {
-        k_stats[((size_t)bh * N + t0 + t) * 2] = m;
-        k_stats[((size_t)bh * N + t0 + t) * 2 + 1] = inv;
-      }
+      if (ok && sub == 0) k_stats[(size_t)bh * N + t0 + t] = m + __logf(sum);
     }
     __syncthreads();
     for (int t = 0; t < kBK; t++) {
@@ -141,7 +138,7 @@ hipError_t launch_kv_state_f32(const Shape& s, const float* k, const float* v, c
 // attn_f32: one workgroup per 64 query rows of query block i.
 //   sparse branch  : for j in sel(i), ascending: S = Q_i K'_j^T / sqrt(d), online softmax, O += P V_j
 //   linear branch  : H_i = H_total - sum_{j in sel(i)} h_j (h_j rebuilt from the staged tiles and the
-//                    per-token softmax statistics), Z_i likewise; O_l = Q^phi H_i / (Q^phi Z_i)
+//                    per-token log-partition lnZ), Z_i likewise; O_l = Q^phi H_i / (Q^phi Z_i)
 //   mix            : out = alpha O_s / l + (1 - alpha) O_l                                   (Eq. 13)
 // ---------------------------------------------------------------------------------------------
 template <int D>
@@ -258,10 +255,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
     for (int idx = tid; idx < kBK * D; idx += 256) {
       int t = idx / D, c = idx % D;
       float kp = 0.f;
-      if (t < valid) {
-        float mt = k_stats[((size_t)bh * N + t0 + t) * 2], inv = k_stats[((size_t)bh * N + t0 + t) * 2 + 1];
-        kp = __expf(ks[t * LD + c] - mt) * inv;
-      }
+      if (t < valid) kp = __expf(ks[t * LD + c] - k_stats[(size_t)bh * N + t0 + t]);
       ks[t * LD + c] = kp;
     }
     // O = diag(corr) O + P V

@@ -1,0 +1,563 @@
+// bf16 / FP8 path of the SLA2 forward pass on the gfx950 matrix cores (Alg. 2 of the paper).
+//
+//   kv_state_bf16   per key token lnZ_t = log sum_c exp(k'_tc), k' = k - colmean(K); per-chunk partial
+//                   sums of h_j = (K^phi_j)^T V_j and z_j = colsum(K^phi_j); in FP8 mode also the e4m3
+//                   codes of k' with one scale per key block (Sec. 5).
+//   attn_mfma       one workgroup per query block i:
+//                     sparse branch over the selected key/value blocks, ascending (online softmax);
+//                     the h_j, z_j of exactly those blocks rebuilt from the staged tiles and lnZ,
+//                     H_i = H_total - sum_sel h_j, Z_i likewise  (complement of the M_c[i,j] = 0 sum);
+//                     O_l = Q^phi H_i / (Q^phi Z_i);  out = alpha O_s + (1 - alpha) O_l     (Eq. 13)
+//                   The same kernel with the block list replaced by 0..T_n-1 and the linear branch
+//                   compiled out is the dense attention comparator.
+//
+// All products run as v_mfma_f32_32x32x16_bf16 (FP8 mode: Q K^T as v_mfma_f32_32x32x16_fp8_fp8) with
+// fp32 accumulation.  Scores are kept transposed (S^T = K Q^T) so that one lane owns one query row:
+// row maxima and sums are in-lane reductions plus one exchange between the two lane halves, and
+// the probabilities go back into the next product as its B operand without leaving registers.
+#include "mfma_tiles.h"
+
+namespace sla2 {
+
+__device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32); }   // partner lane of the other half
+
+__device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// How the (D/32)^2 32x32 tiles of the d x d state h are spread over NW waves: wave w owns
+// kMtw x kNtw tiles starting at (mt0, nt0).
+template <int D, int NW> struct HSplit {
+  static constexpr int kMt = D / 32;
+  static constexpr int kPerWave = kMt * kMt / NW;
+  static constexpr int kMtw = kPerWave > kMt ? kPerWave / kMt : 1;
+  static constexpr int kNtw = kPerWave / kMtw;
+  static_assert(kPerWave >= 1 && kMtw * kNtw == kPerWave, "unsupported split");
+  __device__ static int mt0(int w) { return (w * kPerWave) / kMt; }
+  __device__ static int nt0(int w) { return (w * kPerWave) % kMt; }
+};
+
+// =============================================================================================
+// kv_state_bf16
+// =============================================================================================
+template <int D, bool FP8>
+__global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __restrict__ k,
+                                                            const uint16_t* __restrict__ v,
+                                                            const double* __restrict__ k_mean,
+                                                            float* __restrict__ k_stats, float* __restrict__ partial,
+                                                            uint8_t* __restrict__ k_fp8, float* __restrict__ k_scale,
+                                                            int N, int Tn, int chunks, int blocks_per_chunk) {
+  constexpr int LD = TileGeom<D>::kLd;
+  typedef HSplit<D, 4> HS;
+  __shared__ __attribute__((aligned(16))) uint16_t ktile[kTileTokens * LD];
+  __shared__ __attribute__((aligned(16))) uint16_t vtile[kTileTokens * LD];
+  __shared__ __attribute__((aligned(16))) float lnz2[kTileTokens];
+  __shared__ float mu_s[D];
+  __shared__ float red[4];
+  const int bh = blockIdx.x / chunks, chunk = blockIdx.x % chunks;
+  const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave, g = lane / 32;
+  const uint16_t* kh = k + (size_t)bh * N * D;
+  const uint16_t* vh = v + (size_t)bh * N * D;
+  const int j0 = chunk * blocks_per_chunk, j1 = min(Tn, j0 + blocks_per_chunk);
+  const int mt0 = HS::mt0(w), nt0 = HS::nt0(w);
+
+  if (tid < D) mu_s[tid] = (float)k_mean[(size_t)bh * D + tid];
+  __syncthreads();
+  float mu2[HS::kMtw];
+#pragma unroll
+  for (int a = 0; a < HS::kMtw; a++) mu2[a] = mu_s[32 * (mt0 + a) + lane % 32] * kLog2e;
+
+  f32x16 hacc[HS::kMtw][HS::kNtw];
+  float zsum[HS::kMtw];
+#pragma unroll
+  for (int a = 0; a < HS::kMtw; a++) {
+    zsum[a] = 0.f;
+#pragma unroll
+    for (int b = 0; b < HS::kNtw; b++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) hacc[a][b][e] = 0.f;
+  }
+
+  TileRegs<D, 256> kr, vr;
+  if (j0 < j1) {
+    const int valid = min(kTileTokens, N - j0 * kTileTokens);
+    kr.load(kh + (size_t)j0 * kTileTokens * D, valid, tid);
+    vr.load(vh + (size_t)j0 * kTileTokens * D, valid, tid);
+  }
+  for (int j = j0; j < j1; j++) {
+    const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
+    __syncthreads();                                   // previous tile fully consumed
+    kr.store(ktile, tid);
+    vr.store(vtile, tid);
+    if (j + 1 < j1) {
+      const int nvalid = min(kTileTokens, N - (j + 1) * kTileTokens);
+      kr.load(kh + (size_t)(j + 1) * kTileTokens * D, nvalid, tid);
+      vr.load(vh + (size_t)(j + 1) * kTileTokens * D, nvalid, tid);
+    }
+    __syncthreads();
+    {  // per-token log-partition of softmax_d(k'), 4 threads per token
+      const int t = tid / 4, sub = tid % 4;
+      float x[D / 4];
+      float m = -INFINITY, amax = 0.f;
+#pragma unroll
+      for (int i = 0; i < D / 32; i++) {
+        const int c0 = 8 * (sub + 4 * i);
+        uint4 u = *reinterpret_cast<const uint4*>(ktile + t * LD + c0);
+        uint32_t wds[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int e = 0; e < 4; e++) {
+          x[8 * i + 2 * e] = __builtin_bit_cast(float, wds[e] << 16) - mu_s[c0 + 2 * e];
+          x[8 * i + 2 * e + 1] = __builtin_bit_cast(float, wds[e] & 0xFFFF0000u) - mu_s[c0 + 2 * e + 1];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < D / 4; i++) { m = fmaxf(m, x[i]); amax = fmaxf(amax, fabsf(x[i])); }
+      m = fmaxf(m, __shfl_xor(m, 1));
+      m = fmaxf(m, __shfl_xor(m, 2));
+      float sum = 0.f;
+#pragma unroll
+      for (int i = 0; i < D / 4; i++) sum += fast_exp2((x[i] - m) * kLog2e);
+      sum += __shfl_xor(sum, 1);
+      sum += __shfl_xor(sum, 2);
+      const float lnz = m + __log2f(sum) * 0.6931471805599453f;
+      const bool ok = t < valid;
+      if (sub == 0) {
+        lnz2[t] = ok ? lnz * kLog2e : INFINITY;
+        if (ok) k_stats[(size_t)bh * N + t0 + t] = lnz;
+      }
+      if (FP8) {
+        // one scale per key block: amax over the block's existing tokens (Sec. 5; see sla2.h)
+        if (!ok) amax = 0.f;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+        if (lane == 0) red[w] = amax;
+        __syncthreads();
+        amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+        const float inv = amax > 0.f ? kE4M3Max / amax : 1.f;
+        if (tid == 0) k_scale[(size_t)bh * Tn + j] = amax > 0.f ? amax / kE4M3Max : 1.f;
+        uint8_t* dst = k_fp8 + (((size_t)bh * Tn + j) * kTileTokens + t) * D;
+#pragma unroll
+        for (int i = 0; i < D / 32; i++) {
+          const int c0 = 8 * (sub + 4 * i);
+          int lo = 0, hi = 0;
+          if (ok) {
+            float y[8];
+#pragma unroll
+            for (int e = 0; e < 8; e++) y[e] = fminf(fmaxf(x[8 * i + e] * inv, -kE4M3Max), kE4M3Max);
+            lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], lo, false);
+            lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], lo, true);
+            hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], hi, false);
+            hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], hi, true);
+          }
+          *reinterpret_cast<int2*>(dst + c0) = make_int2(lo, hi);
+        }
+      }
+    }
+    __syncthreads();
+    // h += K^phi^T V on the matrix cores, z += colsum(K^phi)
+#pragma unroll
+    for (int ks = 0; ks < kTileTokens / 16; ks++) {
+      bf16x8 kf[HS::kMtw];
+#pragma unroll
+      for (int a = 0; a < HS::kMtw; a++)
+        kf[a] = kphi_fragment<LD>(ktile, lnz2, mu2[a], ks, 32 * (mt0 + a), lane, zsum[a]);
+#pragma unroll
+      for (int b = 0; b < HS::kNtw; b++) {
+        bf16x8 vf = v_fragment<LD>(vtile, ks, 32 * (nt0 + b), lane);
+#pragma unroll
+        for (int a = 0; a < HS::kMtw; a++) hacc[a][b] = mfma_bf16(kf[a], vf, hacc[a][b]);
+      }
+    }
+  }
+  float* ph = partial + (size_t)blockIdx.x * (D * D + D);
+#pragma unroll
+  for (int a = 0; a < HS::kMtw; a++) {
+#pragma unroll
+    for (int b = 0; b < HS::kNtw; b++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        const int c = 32 * (mt0 + a) + 8 * (e / 4) + 4 * g + e % 4;
+        ph[c * D + 32 * (nt0 + b) + lane % 32] = hacc[a][b][e];
+      }
+    const float z = zsum[a] + xhalf(zsum[a]);
+    if (g == 0 && nt0 == 0) ph[D * D + 32 * (mt0 + a) + lane] = z;
+  }
+}
+
+hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_t* v, const double* k_mean,
+                                float* k_stats, float* partial, float* h_total, float* z_total, uint8_t* k_fp8,
+                                float* k_scale, hipStream_t stream) {
+  dim3 grid((unsigned)(s.BH * s.chunks));
+#define SLA2_KV(DD, F8)                                                                                        \
+  kv_state_bf16_kernel<DD, F8><<<grid, 256, 0, stream>>>(k, v, k_mean, k_stats, partial, k_fp8, k_scale, s.N, \
+                                                         s.Tn, s.chunks, s.blocks_per_chunk)
+  if (s.d == 128) { if (s.fp8) SLA2_KV(128, true); else SLA2_KV(128, false); }
+  else            { if (s.fp8) SLA2_KV(64, true);  else SLA2_KV(64, false); }
+#undef SLA2_KV
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  return launch_kv_total(s, partial, h_total, z_total, stream);
+}
+
+// =============================================================================================
+// attn_mfma
+// =============================================================================================
+constexpr int kXcds = 8;
+
+template <int D, int BQ> struct AttnSmem {
+  static constexpr int kLd = TileGeom<D>::kLd;
+  static constexpr int kTileBytes = kTileTokens * kLd * 2;
+  // two K and two V tiles during the loop; H_i^T [D][kLd] and the output tile [BQ][kLd] afterwards
+  static constexpr int kLoopBytes = 4 * kTileBytes;
+  static constexpr int kEpiBytes = (D + BQ) * kLd * 2;
+  static constexpr int kTiles = kLoopBytes > kEpiBytes ? kLoopBytes : kEpiBytes;
+  static constexpr int kLnzOff = kTiles;                       // float [2][64]
+  static constexpr int kZsOff = kLnzOff + 2 * kTileTokens * 4; // float [D]
+  static constexpr int kBytes = kZsOff + D * 4;
+};
+
+template <int D, int BQ, bool DENSE>
+__global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const double* __restrict__ k_mean, const float* __restrict__ k_stats, const float* __restrict__ h_total,
+    const float* __restrict__ z_total, const int32_t* __restrict__ block_idx, const float* __restrict__ alpha,
+    uint16_t* __restrict__ out, float* __restrict__ lse, int H, int N, int Tm, int Tn, int ksel, int alpha_per_block,
+    int total_blocks) {
+  constexpr int NW = BQ / 32, NT = NW * kWave;
+  constexpr int LD = TileGeom<D>::kLd;
+  constexpr int KS = D / 16;            // contraction steps over the head dimension
+  constexpr int ET = D / 32;            // 32-wide tiles over the head dimension
+  typedef HSplit<D, NW> HS;
+  typedef AttnSmem<D, BQ> SM;
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  uint16_t* tiles = reinterpret_cast<uint16_t*>(smem);
+  float* lnz_s = reinterpret_cast<float*>(smem + SM::kLnzOff);
+  float* zs = reinterpret_cast<float*>(smem + SM::kZsOff);
+  auto ktile = [&](int buf) { return tiles + (2 * buf) * kTileTokens * LD; };
+  auto vtile = [&](int buf) { return tiles + (2 * buf + 1) * kTileTokens * LD; };
+
+  // consecutive query blocks of a head share key/value tiles: keep them on one XCD (workgroups are
+  // dealt round-robin to the 8 XCDs, each with its own L2)
+  const int per_xcd = (total_blocks + kXcds - 1) / kXcds;
+  const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  if (logical >= total_blocks) return;
+  const int bh = logical / Tm, i = logical % Tm, h = bh % H;
+  const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave, g = lane / 32;
+  const int row0 = i * BQ;
+  const int rows_valid = min(BQ, N - row0);
+  const uint16_t* qh = q + (size_t)bh * N * D;
+  const uint16_t* kh = k + (size_t)bh * N * D;
+  const uint16_t* vh = v + (size_t)bh * N * D;
+  const float* stats = DENSE ? nullptr : k_stats + (size_t)bh * N;
+  const int32_t* sel = DENSE ? nullptr : block_idx + ((size_t)bh * Tm + i) * ksel;
+  const int ntiles = DENSE ? Tn : ksel;
+  const int mt0 = HS::mt0(w), nt0 = HS::nt0(w);
+
+  // Q fragments (B operand of S^T = K Q^T): lane <- Q[row0 + 32 w + l%32][16 ks + 8 g + 0..7]
+  bf16x8 qf[KS];
+  {
+    const int r = 32 * w + lane % 32;
+    const bool ok = r < rows_valid;
+    const uint16_t* src = qh + (size_t)(row0 + (ok ? r : 0)) * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      uint4 u = ok ? *reinterpret_cast<const uint4*>(src + 16 * ks) : make_uint4(0, 0, 0, 0);
+      qf[ks] = __builtin_bit_cast(bf16x8, u);
+    }
+  }
+  float mu2[HS::kMtw];
+#pragma unroll
+  for (int a = 0; a < HS::kMtw; a++)
+    mu2[a] = DENSE ? 0.f : (float)k_mean[(size_t)bh * D + 32 * (mt0 + a) + lane % 32] * kLog2e;
+
+  f32x16 oacc[ET];
+#pragma unroll
+  for (int et = 0; et < ET; et++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) oacc[et][e] = 0.f;
+  f32x16 hacc[HS::kMtw][HS::kNtw];
+  float zsum[HS::kMtw];
+#pragma unroll
+  for (int a = 0; a < HS::kMtw; a++) {
+    zsum[a] = 0.f;
+#pragma unroll
+    for (int b = 0; b < HS::kNtw; b++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) hacc[a][b][e] = 0.f;
+  }
+  float m_run = -INFINITY, l_run = 0.f;              // running max (log2 domain) and sum of this lane's query row
+  const float c1 = kLog2e * rsqrtf((float)D);        // scores are used as S * log2(e) / sqrt(d)
+
+  TileRegs<D, NT> kr, vr;
+  float lnz_r = 0.f;
+  auto tile_of = [&](int s) { return DENSE ? s : sel[s]; };
+  auto issue = [&](int s) {
+    const int t0 = tile_of(s) * kTileTokens, valid = min(kTileTokens, N - t0);
+    kr.load(kh + (size_t)t0 * D, valid, tid);
+    vr.load(vh + (size_t)t0 * D, valid, tid);
+    if (!DENSE && tid < kTileTokens) lnz_r = tid < valid ? stats[t0 + tid] * kLog2e : INFINITY;
+  };
+  auto commit = [&](int buf) {
+    kr.store(ktile(buf), tid);
+    vr.store(vtile(buf), tid);
+    if (!DENSE && tid < kTileTokens) lnz_s[buf * kTileTokens + tid] = lnz_r;
+  };
+  if (ntiles > 0) { issue(0); commit(0); }
+  __syncthreads();
+
+  for (int s = 0; s < ntiles; s++) {
+    const int buf = s & 1;
+    const int valid = min(kTileTokens, N - tile_of(s) * kTileTokens);
+    if (s + 1 < ntiles) issue(s + 1);
+    const uint16_t* kt = ktile(buf);
+    const uint16_t* vt = vtile(buf);
+
+    // ---- S^T = K Q^T (keys x query rows), two 32-key halves ----
+    f32x16 sacc[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) sacc[mt][e] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int mt = 0; mt < 2; mt++) {
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(kt + (32 * mt + lane % 32) * LD + 16 * ks + 8 * g);
+        sacc[mt] = mfma_bf16(a, qf[ks], sacc[mt]);
+      }
+    // ---- online softmax of this lane's query row over the 64 keys ----
+    if (valid < kTileTokens) {
+#pragma unroll
+      for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+        for (int e = 0; e < 16; e++)
+          if (32 * mt + 8 * (e / 4) + 4 * g + e % 4 >= valid) sacc[mt][e] = -INFINITY;
+    }
+    float mx = -INFINITY;
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) mx = fmaxf(mx, sacc[mt][e]);
+    mx = fmaxf(mx, xhalf(mx)) * c1;
+    const float m_new = fmaxf(m_run, mx);            // finite: a tile holds at least one key
+    float rs = 0.f;
+    bf16x8 pf[4];                                    // P^T fragments, token order
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        const float p = fast_exp2(sacc[mt][e] * c1 - m_new);
+        rs += p;
+        pf[2 * mt + e / 8][e % 8] = (__bf16)p;
+      }
+    rs += xhalf(rs);
+    const float corr = fast_exp2(m_run - m_new);     // 0 on the first tile
+    l_run = l_run * corr + rs;
+    m_run = m_new;
+#pragma unroll
+    for (int et = 0; et < ET; et++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) oacc[et][e] *= corr;
+
+    // ---- O^T += V^T P^T, and the d x d state of this block: h += K^phi^T V ----
+    const float* lnz2 = lnz_s + buf * kTileTokens;
+#pragma unroll
+    for (int ks = 0; ks < kTileTokens / 16; ks++) {
+      bf16x8 kf[HS::kMtw];
+      if (!DENSE) {
+#pragma unroll
+        for (int a = 0; a < HS::kMtw; a++)
+          kf[a] = kphi_fragment<LD>(kt, lnz2, mu2[a], ks, 32 * (mt0 + a), lane, zsum[a]);
+      }
+      if constexpr (HS::kNtw == ET) {                // every V fragment feeds both products
+#pragma unroll
+        for (int et = 0; et < ET; et++) {
+          bf16x8 vf = v_fragment<LD>(vt, ks, 32 * et, lane);
+          oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
+          if (!DENSE) {
+#pragma unroll
+            for (int a = 0; a < HS::kMtw; a++) hacc[a][et] = mfma_bf16(kf[a], vf, hacc[a][et]);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int et = 0; et < ET; et++) {
+          bf16x8 vf = v_fragment<LD>(vt, ks, 32 * et, lane);
+          oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
+        }
+        if (!DENSE) {
+#pragma unroll
+          for (int b = 0; b < HS::kNtw; b++) {
+            bf16x8 vf = v_fragment<LD>(vt, ks, 32 * (nt0 + b), lane);
+#pragma unroll
+            for (int a = 0; a < HS::kMtw; a++) hacc[a][b] = mfma_bf16(kf[a], vf, hacc[a][b]);
+          }
+        }
+      }
+    }
+    if (s + 1 < ntiles) commit(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ================= epilogue =================
+  const float inv_l = l_run > 0.f ? 1.f / l_run : 0.f;
+  const int qrow = 32 * w + lane % 32;               // this lane's query row inside the block
+  if (lse != nullptr) {
+    // Alg. 2 defines L on the smoothed keys; the products above used the raw K, whose scores are
+    // larger by q . colmean(K) / sqrt(d) in every column of a row (which the softmax cancels)
+    float qmu = 0.f;
+    if (!DENSE) {
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+        for (int e = 0; e < 8; e++) qmu += (float)qf[ks][e] * (float)k_mean[(size_t)bh * D + 16 * ks + 8 * g + e];
+      qmu += xhalf(qmu);
+    }
+    if (g == 0 && qrow < rows_valid)
+      lse[(size_t)bh * N + row0 + qrow] =
+          l_run > 0.f ? (m_run + __log2f(l_run)) * 0.6931471805599453f - qmu * rsqrtf((float)D) : -INFINITY;
+  }
+
+  uint16_t* ht = tiles;                              // H_i^T as bf16 [e][c], row stride LD
+  uint16_t* os = tiles + D * LD;                     // output tile [BQ][LD]
+  f32x16 lacc[ET];
+  float inv_den = 0.f;
+  if (!DENSE) {
+    const float* htot = h_total + (size_t)bh * D * D;
+#pragma unroll
+    for (int a = 0; a < HS::kMtw; a++) {
+#pragma unroll
+      for (int b = 0; b < HS::kNtw; b++) {
+        const int e_col = 32 * (nt0 + b) + lane % 32;
+#pragma unroll
+        for (int v4 = 0; v4 < 4; v4++) {
+          const int c0 = 32 * (mt0 + a) + 8 * v4 + 4 * g;
+          bf16x4 pk;
+#pragma unroll
+          for (int r = 0; r < 4; r++) pk[r] = (__bf16)(htot[(c0 + r) * D + e_col] - hacc[a][b][4 * v4 + r]);
+          *reinterpret_cast<bf16x4*>(ht + e_col * LD + c0) = pk;
+        }
+      }
+      const float z = zsum[a] + xhalf(zsum[a]);
+      if (g == 0 && nt0 == 0) {
+        const int c = 32 * (mt0 + a) + lane;
+        zs[c] = z_total[(size_t)bh * D + c] - z;
+      }
+    }
+    // Q^phi = softmax_d(Q) of this lane's row, kept as fragments
+    float qx[KS][8];
+    float qm = -INFINITY;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        qx[ks][e] = (float)qf[ks][e];
+        qm = fmaxf(qm, qx[ks][e]);
+      }
+    qm = fmaxf(qm, xhalf(qm));
+    float qs = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        qx[ks][e] = fast_exp2((qx[ks][e] - qm) * kLog2e);
+        qs += qx[ks][e];
+      }
+    qs += xhalf(qs);
+    const float qinv = 1.f / qs;
+    __syncthreads();                                 // H_i^T and Z_i visible
+    float den = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      const f32x4 z0 = *reinterpret_cast<const f32x4*>(zs + 16 * ks + 8 * g);
+      const f32x4 z1 = *reinterpret_cast<const f32x4*>(zs + 16 * ks + 8 * g + 4);
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        qx[ks][e] *= qinv;
+        den += qx[ks][e] * (e < 4 ? z0[e] : z1[e - 4]);
+        qf[ks][e] = (__bf16)qx[ks][e];
+      }
+    }
+    den += xhalf(den);
+    inv_den = ksel >= Tn ? 0.f : 1.f / den;          // every block selected: nothing left for the linear branch
+    // O_l^T = H_i^T Q^phi^T
+#pragma unroll
+    for (int et = 0; et < ET; et++) {
+#pragma unroll
+      for (int e = 0; e < 16; e++) lacc[et][e] = 0.f;
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++) {
+        bf16x8 a = *reinterpret_cast<const bf16x8*>(ht + (32 * et + lane % 32) * LD + 16 * ks + 8 * g);
+        lacc[et] = mfma_bf16(a, qf[ks], lacc[et]);
+      }
+    }
+  }
+  // ---- mix (Eq. 13), transpose through LDS, coalesced store ----
+  const float al = DENSE ? 1.f : alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
+  const float ws = al * inv_l, wl = (1.f - al) * inv_den;
+#pragma unroll
+  for (int et = 0; et < ET; et++)
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      bf16x4 pk;
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        float o = ws * oacc[et][4 * v4 + r];
+        if (!DENSE) o += wl * lacc[et][4 * v4 + r];
+        pk[r] = (__bf16)o;
+      }
+      *reinterpret_cast<bf16x4*>(os + qrow * LD + 32 * et + 8 * v4 + 4 * g) = pk;
+    }
+  __syncthreads();
+  uint16_t* oh = out + ((size_t)bh * N + row0) * D;
+  for (int idx = tid; idx < BQ * (D / 8); idx += NT) {
+    const int r = idx / (D / 8), ch = idx % (D / 8);
+    if (r < rows_valid) *reinterpret_cast<uint4*>(oh + (size_t)r * D + 8 * ch) = *reinterpret_cast<const uint4*>(os + r * LD + 8 * ch);
+  }
+}
+
+template <int D, int BQ, bool DENSE>
+static hipError_t launch_attn_t(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                                const double* k_mean, const float* k_stats, const float* h_total, const float* z_total,
+                                const int32_t* block_idx, const float* alpha, uint16_t* out, float* lse,
+                                hipStream_t stream) {
+  constexpr int smem = AttnSmem<D, BQ>::kBytes;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<D, BQ, DENSE>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int Tm = (s.N + BQ - 1) / BQ;
+  const int total = s.BH * Tm;
+  const int grid = ((total + kXcds - 1) / kXcds) * kXcds;
+  attn_mfma_kernel<D, BQ, DENSE><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(
+      q, k, v, k_mean, k_stats, h_total, z_total, block_idx, alpha, out, lse, s.H, s.N, Tm, s.Tn, s.k,
+      s.alpha_per_block ? 1 : 0, total);
+  return hipGetLastError();
+}
+
+hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                            const double* k_mean, const float* k_stats, const float* h_total, const float* z_total,
+                            const int32_t* block_idx, const float* alpha, uint16_t* out, float* lse,
+                            hipStream_t stream) {
+#define SLA2_ATTN(DD, QQ) \
+  return launch_attn_t<DD, QQ, false>(s, q, k, v, k_mean, k_stats, h_total, z_total, block_idx, alpha, out, lse, stream)
+  if (s.d == 128 && s.bq == 128) SLA2_ATTN(128, 128);
+  if (s.d == 128 && s.bq == 64) SLA2_ATTN(128, 64);
+  if (s.d == 64 && s.bq == 128) SLA2_ATTN(64, 128);
+  SLA2_ATTN(64, 64);
+#undef SLA2_ATTN
+}
+
+hipError_t launch_dense_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
+                             hipStream_t stream) {
+  if (s.d == 128)
+    return launch_attn_t<128, 128, true>(s, q, k, v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, out, nullptr,
+                                         stream);
+  return launch_attn_t<64, 128, true>(s, q, k, v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, out, nullptr,
+                                      stream);
+}
+
+}  // namespace sla2

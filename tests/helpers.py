@@ -51,3 +51,33 @@ def check_mask(gpu_idx: np.ndarray, R: np.ndarray, oracle_sel: np.ndarray):
 
 def rel_l2(a, b):
     return float(np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def run_forward(api, torch, inp, flags=0, alpha=None, alpha_per_block=0, want_lse=True):
+    w = inp.workload
+    dt = api.SLA2_BF16 if w.dtype == "bf16" else api.SLA2_F32
+    qm = api.SLA2_QUANT_FP8 if w.quant == "fp8" else api.SLA2_QUANT_NONE
+    p = api.make_params(w.B, w.H, w.N, w.d, w.block_q, w.block_kv, w.topk_frac, dtype=dt, quant_mode=qm,
+                        alpha_per_block=alpha_per_block, flags=flags)
+    q, k, v = (api.to_device(a, dt) for a in (inp.q, inp.k, inp.v))
+    rw = torch.from_numpy(inp.router_w).cuda()
+    al = torch.from_numpy(np.ascontiguousarray(inp.alpha if alpha is None else alpha, dtype=np.float32)).cuda()
+    ws = api.alloc_workspace(p)
+    kk = api.sla2_num_selected(p)
+    out = torch.full_like(q, float("nan"))
+    idx = torch.full((w.B, w.H, w.T_m, max(kk, 1)), -1, dtype=torch.int32, device="cuda")
+    lse = torch.full((w.B, w.H, w.N), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
+    api.sla2_forward(p, q, k, v, rw, al, out, block_idx=idx, lse=lse, workspace=ws)
+    torch.cuda.synchronize()
+    return dict(p=p, ws=ws, out=out.float().cpu().numpy(), idx=idx.cpu().numpy()[..., :kk],
+                lse=None if lse is None else lse.cpu().numpy(), k=kk)
+
+
+def run_dense(api, torch, inp):
+    w = inp.workload
+    p = api.make_params(w.B, w.H, w.N, w.d, w.block_q, w.block_kv, 1.0, dtype=api.SLA2_BF16)
+    q, k, v = (api.to_device(a, api.SLA2_BF16) for a in (inp.q, inp.k, inp.v))
+    out = torch.full_like(q, float("nan"))
+    api.sla2_dense_forward(p, q, k, v, out)
+    torch.cuda.synchronize()
+    return out.float().cpu().numpy()

@@ -4,32 +4,12 @@ import numpy as np
 import pytest
 
 import sla2_oracle as O
-from helpers import check_mask, oracle_heads
+from helpers import check_mask, oracle_heads, run_forward
 from paper_2602_12675_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
 
 F32_MAX_ABS = 2e-3
-
-
-def run_forward(api, torch, inp, flags=0, alpha=None, alpha_per_block=0, want_lse=True):
-    w = inp.workload
-    dt = api.SLA2_BF16 if w.dtype == "bf16" else api.SLA2_F32
-    qm = api.SLA2_QUANT_FP8 if w.quant == "fp8" else api.SLA2_QUANT_NONE
-    p = api.make_params(w.B, w.H, w.N, w.d, w.block_q, w.block_kv, w.topk_frac, dtype=dt, quant_mode=qm,
-                        alpha_per_block=alpha_per_block, flags=flags)
-    q, k, v = (api.to_device(a, dt) for a in (inp.q, inp.k, inp.v))
-    rw = torch.from_numpy(inp.router_w).cuda()
-    al = torch.from_numpy(np.ascontiguousarray(inp.alpha if alpha is None else alpha, dtype=np.float32)).cuda()
-    ws = api.alloc_workspace(p)
-    kk = api.sla2_num_selected(p)
-    out = torch.full_like(q, float("nan"))
-    idx = torch.full((w.B, w.H, w.T_m, max(kk, 1)), -1, dtype=torch.int32, device="cuda")
-    lse = torch.full((w.B, w.H, w.N), float("nan"), dtype=torch.float32, device="cuda") if want_lse else None
-    api.sla2_forward(p, q, k, v, rw, al, out, block_idx=idx, lse=lse, workspace=ws)
-    torch.cuda.synchronize()
-    return dict(p=p, ws=ws, out=out.float().cpu().numpy(), idx=idx.cpu().numpy()[..., :kk],
-                lse=None if lse is None else lse.cpu().numpy(), k=kk)
 
 
 CASES = [
