@@ -1,0 +1,182 @@
+#!/usr/bin/env python3
+"""Benchmark of the SLA2 forward pass on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--quant fp8|none]
+
+One "step" is one sla2_forward call (router -> kv state -> fused sparse + linear +
+mix) on a synthetic Wan2.1-1.3B-shaped input set (B=1, H=12, N=32760, d=128,
+b_q=128, b_kv=64, 3 % of the key blocks kept = 97 % sparsity) that is already
+resident in HBM.  Prints ONE JSON line: dense-equivalent TFLOP/s (4 N^2 d H B / t,
+the paper's C/t), ms per call, the roofline entry of the dominant kernel measured
+live with HIP events, the per-kernel breakdown, the in-build dense bf16 attention
+on the same inputs, and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+for p in (ROOT, os.path.join(ROOT, "oracle")):
+    if p not in sys.path:
+        sys.path.insert(0, p)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0}
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="wan1.3b-97-fp8")
+    ap.add_argument("--quant", choices=["fp8", "none"], default=None, help="override the workload's sparse-branch precision")
+    ap.add_argument("--topk", type=float, default=None, help="override the kept fraction of key blocks")
+    ap.add_argument("--input-sets", type=int, default=3, help="independent input copies rotated between calls")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-heads", type=int, default=6, help="heads of the workload the oracle is timed on")
+    return ap.parse_args()
+
+
+def cpu_baseline(inp, heads):
+    """The oracle as it stands, timed on `heads` full heads of the workload."""
+    import sla2_oracle as O
+    import numpy as np
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    w = inp.workload
+    quant = O.QUANT_FP8 if w.quant == "fp8" else O.QUANT_NONE
+    Wq, Wk = inp.router_w[0].astype(np.float64), inp.router_w[1].astype(np.float64)
+    t0 = time.perf_counter()
+    for h in range(heads):
+        O.forward_head(inp.values("q", 0, h), inp.values("k", 0, h), inp.values("v", 0, h), Wq, Wk,
+                       float(inp.alpha[h]), w.topk_frac, w.block_q, w.block_kv, quant=quant)
+    dt = time.perf_counter() - t0
+    flops = 4.0 * w.N * w.N * w.d * heads
+    return {"value": flops / dt / 1e12, "unit": "TFLOP/s (dense-equivalent)", "cores": int(cores), "kind": "oracle",
+            "sample": "%d of %d heads of the same workload, all query blocks, %.1f s; ms per full call extrapolated: %.0f"
+                      % (heads, w.B * w.H, dt, dt / heads * w.B * w.H * 1e3)}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
+              "--gpus %d is not supported - value is the throughput of a single MI355X" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    from paper_2602_12675_amd import api, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    torch.cuda.set_device(0)
+    w = W.CONFIGS[args.workload]
+    if args.quant is not None:
+        w = w.replace(quant=args.quant)
+    if args.topk is not None:
+        w = w.replace(topk_frac=args.topk)
+    inp = W.generate(w)
+    dt = api.SLA2_BF16 if w.dtype == "bf16" else api.SLA2_F32
+    qm = api.SLA2_QUANT_FP8 if w.quant == "fp8" else api.SLA2_QUANT_NONE
+    p = api.make_params(w.B, w.H, w.N, w.d, w.block_q, w.block_kv, w.topk_frac, dtype=dt, quant_mode=qm)
+    ksel = api.sla2_num_selected(p)
+    sets = []
+    for s in range(max(1, args.input_sets)):
+        q, k, v = (api.to_device(a, dt) for a in (inp.q, inp.k, inp.v))
+        sets.append((q, k, v, torch.empty_like(q)))
+    rw = torch.from_numpy(inp.router_w).cuda()
+    al = torch.from_numpy(inp.alpha).cuda()
+    ws = api.alloc_workspace(p)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        q, k, v, out = sets[i % len(sets)]
+        api.sla2_forward(p, q, k, v, rw, al, out, workspace=ws, stream=stream)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    # timed region: only the dominant kernel carries event pairs (2 event records per step)
+    api.sla2_profile_begin(["attn"], args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    prof = api.sla2_profile_end()
+    ms_per_step = elapsed / args.steps * 1e3
+    dense_flops = 4.0 * w.N * w.N * w.d * w.H * w.B
+    value = dense_flops / (ms_per_step * 1e-3) / 1e12
+
+    # per-kernel breakdown in a second, untimed-for-value pass
+    api.sla2_profile_begin(list(api.STAGES[:7]), args.steps)
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    stages = {name: ms / n for name, (ms, n) in api.sla2_profile_end().items()}
+
+    BH, esz = w.B * w.H, (2 if w.dtype == "bf16" else 4)
+    tile_iters = BH * w.T_m * ksel
+    attn_flops = tile_iters * 4.0 * w.block_q * w.block_kv * w.d + BH * w.T_m * 2.0 * w.block_q * w.d * w.d
+    attn_ms = prof["attn"][0] / prof["attn"][1]
+    mm = "fp8" if w.quant == "fp8" else "bf16"
+    achieved = attn_flops / (attn_ms * 1e-3) / 1e12
+    roofline = {"kernel": "attn_mfma (sparse + linear branch + mix)", "bound": "mfma", "achieved": round(achieved, 2),
+                "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS["bf16"], 4),
+                "traffic": None, "ms": round(attn_ms, 4),
+                "algorithmic_flops": attn_flops,
+                "note": "peak = dense bf16 MFMA; P V and the linear branch run in bf16 (in fp8 mode only Q K^T is fp8)"}
+    qk_bytes = 2.0 * BH * w.N * w.d * esz
+    hbm = {}
+    if "block_sums" in stages:
+        gbs = qk_bytes / (stages["block_sums"] * 1e-3) / 1e9
+        hbm["block_sums"] = {"GB/s": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4), "bytes": qk_bytes}
+    if "kv_state" in stages:
+        b = qk_bytes + (BH * w.T_n * w.block_kv * w.d if w.quant == "fp8" else 0)
+        gbs = b / (stages["kv_state"] * 1e-3) / 1e9
+        hbm["kv_state"] = {"GB/s": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4), "bytes": b}
+
+    line = {
+        "metric": "SLA2 forward, dense-equivalent throughput 4*N^2*d*H*B / t",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": mm, "data": "synthetic",
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "block_q": w.block_q,
+                   "block_kv": w.block_kv, "topk_frac": w.topk_frac, "k": ksel, "T_n": w.T_n,
+                   "sparsity": round(1.0 - ksel / w.T_n, 4), "quant": w.quant, "input_sets": len(sets)},
+        "roofline": roofline,
+        "stage_ms": {k_: round(v_, 4) for k_, v_ in stages.items()},
+        "hbm_kernels": hbm,
+    }
+    if not args.no_dense and w.dtype == "bf16":
+        q, k, v, out = sets[0]
+        api.sla2_dense_forward(p, q, k, v, out, stream=stream)
+        torch.cuda.synchronize()
+        reps = 3
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            api.sla2_dense_forward(p, q, k, v, out, stream=stream)
+        torch.cuda.synchronize()
+        dense_ms = (time.perf_counter() - t0) / reps * 1e3
+        line["dense_bf16"] = {"ms": round(dense_ms, 3), "TFLOP/s": round(dense_flops / (dense_ms * 1e-3) / 1e12, 1),
+                              "frac_of_mfma_peak": round(dense_flops / (dense_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4)}
+        line["speedup_vs_dense_bf16"] = round(dense_ms / ms_per_step, 2)
+    line["paper_context"] = "paper: 97 % sparsity, 18.6x attention speed-up over FlashAttn2 on an RTX5090 (other hardware; not a target)"
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(inp, max(1, min(args.cpu_heads, w.H)))
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

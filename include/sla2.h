@@ -88,6 +88,10 @@ typedef struct sla2_ws_layout {
   size_t h_total;   /* float  [BH, d, d]     sum over all key blocks of (K^phi_j)^T V_j     (Alg. 2: h) */
   size_t z_total;   /* float  [BH, d]        sum over all key blocks of colsum(K^phi_j)     (Alg. 2: z) */
   size_t k_stats;   /* float  [BH, N]        per key token: lnZ = log sum_c exp(k'_c), k' = k - colmean(K); K^phi = exp(k' - lnZ) */
+  size_t k_phi;     /* bf16   [BH, T_n, d/32, 4, 64, 8]  K^phi = softmax_d(K - colmean K) of each key block as matrix-core
+                                                        operand fragments (bf16 path only): lane l of fragment (mt, ks)
+                                                        holds channel 32 mt + l%32, tokens 16 ks + 8 (i/4) + 4 (l/32) + i%4, i = 0..7 */
+  size_t z_blocks;  /* float  [BH, T_n, d]   z_j = colsum(K^phi_j) per key block (bf16 path only)        (Alg. 2: z) */
   size_t k_fp8;     /* uint8  [BH, T_n*block_kv, d]  e4m3 codes of the smoothed K (FP8 mode only; rows >= N are 0) */
   size_t k_scale;   /* float  [BH, T_n]      dequantisation scale of each key block (FP8 mode only) */
   size_t partial;   /* scratch for per-chunk partial sums of h and z */
@@ -133,6 +137,29 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
  * Uses B, H, N, d, dtype of params (dtype must be SLA2_BF16); needs no workspace. */
 int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, const void* v,
                        void* out, void* hip_stream);
+
+/* Per-kernel timing for benchmarks (not part of the operator; host-side state, not thread-safe).
+ * The forward pass is a fixed sequence of kernels ("stages").  Between sla2_profile_begin and
+ * sla2_profile_end every launch of a stage whose bit is set in stage_mask is bracketed by two
+ * hipEventRecord calls on the caller's stream, for at most max_calls calls of sla2_forward /
+ * sla2_router / sla2_dense_forward; the events are created in sla2_profile_begin, so the
+ * calls in between still allocate nothing.  sla2_profile_end synchronises on the recorded
+ * events, adds up the elapsed milliseconds and the number of launches per stage into the two
+ * HOST arrays (each SLA2_STAGE_COUNT long) and destroys the events.
+ * Returns SLA2_OK, SLA2_EINVAL (bad arguments / begin without end) or SLA2_EHIP. */
+typedef enum {
+  SLA2_STAGE_BLOCK_SUMS = 0,  /* pooling sums of Q and K blocks            (Eq. 15) */
+  SLA2_STAGE_COL_MEAN = 1,    /* colmean(K)                                (Alg. 2, smoothing) */
+  SLA2_STAGE_PROJECT = 2,     /* proj_q, proj_k                            (Eq. 16) */
+  SLA2_STAGE_TOPK = 3,        /* scores + row-wise top-k                   (Eq. 16) */
+  SLA2_STAGE_KV_STATE = 4,    /* lnZ, partial h and z, FP8 codes of K      (Alg. 2: K^phi, h, z) */
+  SLA2_STAGE_KV_TOTAL = 5,    /* per-head totals of h and z */
+  SLA2_STAGE_ATTN = 6,        /* sparse + linear branch + mix              (Alg. 2 block loop, Eq. 13) */
+  SLA2_STAGE_DENSE = 7,       /* dense attention comparator */
+  SLA2_STAGE_COUNT = 8
+} sla2_stage;
+int sla2_profile_begin(unsigned stage_mask, int max_calls);
+int sla2_profile_end(double* stage_ms, int* stage_launches);
 
 const char* sla2_strerror(int status);
 int sla2_version(void);

@@ -21,7 +21,10 @@ SLA2_FLAG_NO_SMOOTH_K = 1
 SLA2_OK, SLA2_EINVAL, SLA2_EUNSUPPORTED, SLA2_EWORKSPACE, SLA2_EALIAS, SLA2_EHIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("sla2_workspace_bytes", "sla2_workspace_layout", "sla2_num_selected", "sla2_router",
-           "sla2_forward", "sla2_dense_forward", "sla2_strerror", "sla2_version")
+           "sla2_forward", "sla2_dense_forward", "sla2_profile_begin", "sla2_profile_end",
+           "sla2_strerror", "sla2_version")
+
+STAGES = ("block_sums", "col_mean", "project", "topk", "kv_state", "kv_total", "attn", "dense")   # sla2_stage
 
 
 class Params(ctypes.Structure):
@@ -36,7 +39,7 @@ class WsLayout(ctypes.Structure):
     """struct sla2_ws_layout"""
     _fields_ = [(n, ctypes.c_size_t) for n in
                 ("q_sum", "k_sum", "k_mean", "q_proj", "k_proj", "block_idx", "h_total", "z_total",
-                 "k_stats", "k_fp8", "k_scale", "partial", "total")]
+                 "k_stats", "k_phi", "z_blocks", "k_fp8", "k_scale", "partial", "total")]
 
 
 if not os.path.exists(LIB_PATH):
@@ -56,6 +59,10 @@ _lib.sla2_forward.restype = ctypes.c_int
 _lib.sla2_forward.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.sla2_dense_forward.restype = ctypes.c_int
 _lib.sla2_dense_forward.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp]
+_lib.sla2_profile_begin.restype = ctypes.c_int
+_lib.sla2_profile_begin.argtypes = [ctypes.c_uint, ctypes.c_int]
+_lib.sla2_profile_end.restype = ctypes.c_int
+_lib.sla2_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
 _lib.sla2_strerror.restype = ctypes.c_char_p
 _lib.sla2_strerror.argtypes = [ctypes.c_int]
 _lib.sla2_version.restype = ctypes.c_int
@@ -139,6 +146,26 @@ def sla2_dense_forward(params, q, k, v, out, stream=None, check=True) -> int:
     if check and rc != SLA2_OK:
         raise Sla2Error(rc)
     return rc
+
+
+def sla2_profile_begin(stages, max_calls: int) -> None:
+    """stages: iterable of names from STAGES."""
+    mask = 0
+    for name in stages:
+        mask |= 1 << STAGES.index(name)
+    rc = _lib.sla2_profile_begin(mask, max_calls)
+    if rc != SLA2_OK:
+        raise Sla2Error(rc)
+
+
+def sla2_profile_end() -> dict:
+    """-> {stage name: (total ms, launches)} for the stages that ran."""
+    ms = (ctypes.c_double * len(STAGES))()
+    n = (ctypes.c_int * len(STAGES))()
+    rc = _lib.sla2_profile_end(ms, n)
+    if rc != SLA2_OK:
+        raise Sla2Error(rc)
+    return {STAGES[i]: (ms[i], n[i]) for i in range(len(STAGES)) if n[i]}
 
 
 # ---- plumbing helpers for tests and the benchmark (no arithmetic) ------------------------------

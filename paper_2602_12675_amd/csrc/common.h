@@ -51,17 +51,18 @@ hipError_t launch_project(const Shape& s, const double* q_sum, const double* k_s
 hipError_t launch_router_topk(const Shape& s, const double* q_proj, const double* k_proj, int32_t* block_idx,
                               hipStream_t stream);
 hipError_t launch_kv_state_f32(const Shape& s, const float* k, const float* v, const double* k_mean, float* k_stats,
-                               float* partial, float* h_total, float* z_total, hipStream_t stream);
+                               float* partial, hipStream_t stream);
 hipError_t launch_attn_f32(const Shape& s, const float* q, const float* k, const float* v, const double* k_mean,
                            const float* k_stats, const float* h_total, const float* z_total, const int32_t* block_idx,
                            const float* alpha, float* out, float* lse, hipStream_t stream);
 
 hipError_t launch_kv_total(const Shape& s, const float* partial, float* h_total, float* z_total, hipStream_t stream);
 hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_t* v, const double* k_mean,
-                                float* k_stats, float* partial, float* h_total, float* z_total, uint8_t* k_fp8,
+                                float* k_stats, float* partial, uint16_t* k_phi, float* z_blocks, uint8_t* k_fp8,
                                 float* k_scale, hipStream_t stream);
 hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v,
-                            const double* k_mean, const float* k_stats, const float* h_total, const float* z_total,
+                            const double* k_mean, const uint16_t* k_phi, const float* z_blocks, const uint8_t* k_fp8,
+                            const float* k_scale, const float* h_total, const float* z_total,
                             const int32_t* block_idx, const float* alpha, uint16_t* out, float* lse,
                             hipStream_t stream);
 hipError_t launch_dense_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,

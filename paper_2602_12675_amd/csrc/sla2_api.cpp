@@ -3,6 +3,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <vector>
+
 #include "common.h"
 
 namespace sla2 {
@@ -57,6 +59,8 @@ static void make_layout(const Shape& s, sla2_ws_layout* L) {
   L->h_total = take(BH * d * d * sizeof(float));
   L->z_total = take(BH * d * sizeof(float));
   L->k_stats = take(BH * (size_t)s.N * sizeof(float));
+  L->k_phi = take(s.bf16 ? BH * (size_t)s.Tn * s.bk * d * 2 : 0);
+  L->z_blocks = take(s.bf16 ? BH * (size_t)s.Tn * d * sizeof(float) : 0);
   L->k_fp8 = take(s.fp8 ? BH * (size_t)s.Tn * s.bk * d : 0);
   L->k_scale = take(s.fp8 ? BH * (size_t)s.Tn * sizeof(float) : 0);
   L->partial = take(BH * (size_t)s.chunks * (d * d + d) * sizeof(float));
@@ -76,6 +80,35 @@ static int check_workspace(const sla2_ws_layout& L, const void* ws, size_t bytes
 template <class T>
 static T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
 
+// ---- optional per-stage event timing (see sla2_profile_begin in sla2.h) ----
+struct Profiler {
+  bool active = false;
+  unsigned mask = 0;
+  int max_calls = 0, calls = 0;
+  std::vector<hipEvent_t> pool;                   // created in begin(); two per (call, stage)
+  struct Rec { int stage; hipEvent_t a, b; };
+  std::vector<Rec> recs;                          // capacity reserved in begin()
+  size_t next = 0;
+};
+static Profiler g_prof;
+
+// Brackets one launch with events when profiling asks for it.
+struct StageTimer {
+  hipStream_t st; int stage; bool on = false; hipEvent_t a, b;
+  StageTimer(int stage_, hipStream_t st_) : st(st_), stage(stage_) {
+    Profiler& p = g_prof;
+    if (p.active && (p.mask >> stage & 1u) && p.calls <= p.max_calls && p.next + 2 <= p.pool.size() &&
+        p.recs.size() < p.recs.capacity()) {
+      a = p.pool[p.next++]; b = p.pool[p.next++];
+      on = hipEventRecord(a, st) == hipSuccess;
+    }
+  }
+  ~StageTimer() {
+    if (on && hipEventRecord(b, st) == hipSuccess) g_prof.recs.push_back({stage, a, b});
+  }
+};
+#define SLA2_STAGE(stage, call) ([&]() { StageTimer t_(stage, st); return (call); }())
+
 // pool -> colmean -> project -> scores + top-k.  Leaves the index lists in the workspace.
 static int run_router(const Shape& s, const sla2_ws_layout& L, const void* q, const void* k, const float* router_w,
                       void* ws, hipStream_t st) {
@@ -84,11 +117,15 @@ static int run_router(const Shape& s, const sla2_ws_layout& L, const void* q, co
   double* k_mean = at<double>(ws, L.k_mean);
   double* q_proj = at<double>(ws, L.q_proj);
   double* k_proj = at<double>(ws, L.k_proj);
-  if (launch_block_sums(s, q, k, q_sum, k_sum, st) != hipSuccess) return SLA2_EHIP;
-  if (launch_col_mean(s, k_sum, k_mean, st) != hipSuccess) return SLA2_EHIP;
+  if (SLA2_STAGE(SLA2_STAGE_BLOCK_SUMS, launch_block_sums(s, q, k, q_sum, k_sum, st)) != hipSuccess) return SLA2_EHIP;
+  if (SLA2_STAGE(SLA2_STAGE_COL_MEAN, launch_col_mean(s, k_sum, k_mean, st)) != hipSuccess) return SLA2_EHIP;
   if (s.k > 0) {
-    if (launch_project(s, q_sum, k_sum, k_mean, router_w, q_proj, k_proj, st) != hipSuccess) return SLA2_EHIP;
-    if (launch_router_topk(s, q_proj, k_proj, at<int32_t>(ws, L.block_idx), st) != hipSuccess) return SLA2_EHIP;
+    if (SLA2_STAGE(SLA2_STAGE_PROJECT, launch_project(s, q_sum, k_sum, k_mean, router_w, q_proj, k_proj, st)) !=
+        hipSuccess)
+      return SLA2_EHIP;
+    if (SLA2_STAGE(SLA2_STAGE_TOPK, launch_router_topk(s, q_proj, k_proj, at<int32_t>(ws, L.block_idx), st)) !=
+        hipSuccess)
+      return SLA2_EHIP;
   }
   return SLA2_OK;
 }
@@ -131,6 +168,7 @@ int sla2_router(const sla2_params* params, const void* q, const void* k, const f
   make_layout(s, &L);
   if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
+  g_prof.calls++;
   if ((rc = run_router(s, L, q, k, router_w, workspace, st)) != SLA2_OK) return rc;
   if (s.k > 0) {
     size_t bytes = (size_t)s.BH * s.Tm * s.k * sizeof(int32_t);
@@ -154,6 +192,7 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
   make_layout(s, &L);
   if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
+  g_prof.calls++;
   if ((rc = run_router(s, L, q, k, router_w, workspace, st)) != SLA2_OK) return rc;
   int32_t* idx = at<int32_t>(workspace, L.block_idx);
   if (block_idx_or_null && s.k > 0) {
@@ -166,20 +205,31 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
   float* z_total = at<float>(workspace, L.z_total);
   float* partial = at<float>(workspace, L.partial);
   if (!s.bf16) {
-    if (launch_kv_state_f32(s, (const float*)k, (const float*)v, k_mean, k_stats, partial, h_total, z_total, st) !=
-        hipSuccess)
+    if (SLA2_STAGE(SLA2_STAGE_KV_STATE, launch_kv_state_f32(s, (const float*)k, (const float*)v, k_mean, k_stats,
+                                                            partial, st)) != hipSuccess)
       return SLA2_EHIP;
-    if (launch_attn_f32(s, (const float*)q, (const float*)k, (const float*)v, k_mean, k_stats, h_total, z_total, idx,
-                        alpha, (float*)out, lse_or_null, st) != hipSuccess)
+    if (SLA2_STAGE(SLA2_STAGE_KV_TOTAL, launch_kv_total(s, partial, h_total, z_total, st)) != hipSuccess)
+      return SLA2_EHIP;
+    if (SLA2_STAGE(SLA2_STAGE_ATTN,
+                   launch_attn_f32(s, (const float*)q, (const float*)k, (const float*)v, k_mean, k_stats, h_total,
+                                   z_total, idx, alpha, (float*)out, lse_or_null, st)) != hipSuccess)
       return SLA2_EHIP;
     return SLA2_OK;
   }
-  if (s.fp8) return SLA2_EUNSUPPORTED;
-  if (launch_kv_state_bf16(s, (const uint16_t*)k, (const uint16_t*)v, k_mean, k_stats, partial, h_total, z_total,
-                           at<uint8_t>(workspace, L.k_fp8), at<float>(workspace, L.k_scale), st) != hipSuccess)
+  uint16_t* k_phi = at<uint16_t>(workspace, L.k_phi);
+  float* z_blocks = at<float>(workspace, L.z_blocks);
+  uint8_t* k_fp8 = at<uint8_t>(workspace, L.k_fp8);
+  float* k_scale = at<float>(workspace, L.k_scale);
+  if (SLA2_STAGE(SLA2_STAGE_KV_STATE,
+                 launch_kv_state_bf16(s, (const uint16_t*)k, (const uint16_t*)v, k_mean, k_stats, partial, k_phi,
+                                      z_blocks, k_fp8, k_scale, st)) != hipSuccess)
     return SLA2_EHIP;
-  if (launch_attn_bf16(s, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, k_mean, k_stats, h_total,
-                       z_total, idx, alpha, (uint16_t*)out, lse_or_null, st) != hipSuccess)
+  if (SLA2_STAGE(SLA2_STAGE_KV_TOTAL, launch_kv_total(s, partial, h_total, z_total, st)) != hipSuccess)
+    return SLA2_EHIP;
+  if (SLA2_STAGE(SLA2_STAGE_ATTN,
+                 launch_attn_bf16(s, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, k_mean, k_phi,
+                                  z_blocks, k_fp8, k_scale, h_total, z_total, idx, alpha, (uint16_t*)out,
+                                  lse_or_null, st)) != hipSuccess)
     return SLA2_EHIP;
   return SLA2_OK;
 }
@@ -195,10 +245,47 @@ int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, 
   if (overlaps(out, tensor_bytes, q, tensor_bytes) || overlaps(out, tensor_bytes, k, tensor_bytes) ||
       overlaps(out, tensor_bytes, v, tensor_bytes))
     return SLA2_EALIAS;
-  if (launch_dense_bf16(s, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, (uint16_t*)out,
-                        (hipStream_t)hip_stream) != hipSuccess)
+  hipStream_t st = (hipStream_t)hip_stream;
+  g_prof.calls++;
+  if (SLA2_STAGE(SLA2_STAGE_DENSE, launch_dense_bf16(s, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v,
+                                                     (uint16_t*)out, st)) != hipSuccess)
     return SLA2_EHIP;
   return SLA2_OK;
+}
+
+int sla2_profile_begin(unsigned stage_mask, int max_calls) {
+  Profiler& p = g_prof;
+  if (p.active || max_calls < 1 || max_calls > 100000 || (stage_mask >> SLA2_STAGE_COUNT)) return SLA2_EINVAL;
+  int per_call = __builtin_popcount(stage_mask);
+  if (per_call == 0) return SLA2_EINVAL;
+  size_t n = (size_t)2 * per_call * max_calls;
+  p.pool.assign(n, nullptr);
+  for (size_t i = 0; i < n; i++)
+    if (hipEventCreate(&p.pool[i]) != hipSuccess) {
+      for (size_t j = 0; j < i; j++) (void)hipEventDestroy(p.pool[j]);
+      p.pool.clear();
+      return SLA2_EHIP;
+    }
+  p.recs.clear();
+  p.recs.reserve(n / 2);
+  p.next = 0; p.calls = 0; p.max_calls = max_calls; p.mask = stage_mask; p.active = true;
+  return SLA2_OK;
+}
+
+int sla2_profile_end(double* stage_ms, int* stage_launches) {
+  Profiler& p = g_prof;
+  if (!p.active || !stage_ms || !stage_launches) return SLA2_EINVAL;
+  int rc = SLA2_OK;
+  for (int i = 0; i < SLA2_STAGE_COUNT; i++) { stage_ms[i] = 0.0; stage_launches[i] = 0; }
+  for (const Profiler::Rec& r : p.recs) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.b) != hipSuccess || hipEventElapsedTime(&ms, r.a, r.b) != hipSuccess) { rc = SLA2_EHIP; continue; }
+    stage_ms[r.stage] += ms;
+    stage_launches[r.stage]++;
+  }
+  for (hipEvent_t e : p.pool) (void)hipEventDestroy(e);
+  p.pool.clear(); p.recs.clear(); p.active = false;
+  return rc;
 }
 
 const char* sla2_strerror(int status) {

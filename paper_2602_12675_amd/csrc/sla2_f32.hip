@@ -113,7 +113,7 @@ hipError_t launch_kv_total(const Shape& s, const float* partial, float* h_total,
 }
 
 hipError_t launch_kv_state_f32(const Shape& s, const float* k, const float* v, const double* k_mean, float* k_stats,
-                               float* partial, float* h_total, float* z_total, hipStream_t stream) {
+                               float* partial, hipStream_t stream) {
   dim3 grid((unsigned)(s.BH * s.chunks));
   const size_t smem = (size_t)2 * kBK * (s.d + 1) * sizeof(float);
   static bool configured = false;
@@ -129,9 +129,7 @@ hipError_t launch_kv_state_f32(const Shape& s, const float* k, const float* v, c
   else
     kv_state_f32_kernel<64><<<grid, 256, smem, stream>>>(k, v, k_mean, k_stats, partial, s.N, s.Tn, s.chunks,
                                                          s.blocks_per_chunk);
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  return launch_kv_total(s, partial, h_total, z_total, stream);
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------

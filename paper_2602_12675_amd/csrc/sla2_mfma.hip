@@ -1,13 +1,16 @@
 // bf16 / FP8 path of the SLA2 forward pass on the gfx950 matrix cores (Alg. 2 of the paper).
 //
-//   kv_state_bf16   per key token lnZ_t = log sum_c exp(k'_tc), k' = k - colmean(K); per-chunk partial
-//                   sums of h_j = (K^phi_j)^T V_j and z_j = colsum(K^phi_j); in FP8 mode also the e4m3
-//                   codes of k' with one scale per key block (Sec. 5).
+//   kv_state_bf16   per key block j of a head: K^phi_j = softmax_d(K_j - colmean K), written out as bf16
+//                   MFMA operand fragments; z_j = colsum(K^phi_j); per-chunk partial sums of
+//                   h_j = (K^phi_j)^T V_j and z_j (reduced to the per-head totals by kv_total); in FP8
+//                   mode also the e4m3 codes of K - colmean K with one scale per key block (Sec. 5).
 //   attn_mfma       one workgroup per query block i:
 //                     sparse branch over the selected key/value blocks, ascending (online softmax);
-//                     the h_j, z_j of exactly those blocks rebuilt from the staged tiles and lnZ,
-//                     H_i = H_total - sum_sel h_j, Z_i likewise  (complement of the M_c[i,j] = 0 sum);
-//                     O_l = Q^phi H_i / (Q^phi Z_i);  out = alpha O_s + (1 - alpha) O_l     (Eq. 13)
+//                     the d x d state of exactly those blocks, sum_sel (K^phi_j)^T V_j, from the stored
+//                     K^phi fragments and the V tile that is already staged for P V;
+//                     H_i = H_total - that sum, Z_i = Z_total - sum_sel z_j  (complement of the
+//                     M_c[i,j] = 0 sum of Alg. 2);  O_l = Q^phi H_i / (Q^phi Z_i);
+//                     out = alpha O_s + (1 - alpha) O_l                                     (Eq. 13)
 //                   The same kernel with the block list replaced by 0..T_n-1 and the linear branch
 //                   compiled out is the dense attention comparator.
 //
@@ -37,6 +40,15 @@ template <int D, int NW> struct HSplit {
   __device__ static int nt0(int w) { return (w * kPerWave) % kMt; }
 };
 
+// K^phi of one key block is stored as the A-operand fragments of the product K^phi^T V:
+// [block][mt = channel tile][ks = 16-token step][lane][8 bf16], lane l holding channel 32 mt + l % 32
+// and the 8 tokens of (ks, l / 32) in token order - 1 KB per fragment, read back with one
+// coalesced 16-byte load per lane and no LDS traffic.
+template <int D>
+__device__ __forceinline__ size_t kphi_offset(size_t block, int mt, int ks, int lane) {
+  return (((block * (D / 32) + mt) * (kTileTokens / 16) + ks) * kWave + lane) * 8;
+}
+
 // =============================================================================================
 // kv_state_bf16
 // =============================================================================================
@@ -45,6 +57,7 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
                                                             const uint16_t* __restrict__ v,
                                                             const double* __restrict__ k_mean,
                                                             float* __restrict__ k_stats, float* __restrict__ partial,
+                                                            uint16_t* __restrict__ k_phi, float* __restrict__ z_blocks,
                                                             uint8_t* __restrict__ k_fp8, float* __restrict__ k_scale,
                                                             int N, int Tn, int chunks, int blocks_per_chunk) {
   constexpr int LD = TileGeom<D>::kLd;
@@ -68,10 +81,10 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
   for (int a = 0; a < HS::kMtw; a++) mu2[a] = mu_s[32 * (mt0 + a) + lane % 32] * kLog2e;
 
   f32x16 hacc[HS::kMtw][HS::kNtw];
-  float zsum[HS::kMtw];
+  float zacc[HS::kMtw];
 #pragma unroll
   for (int a = 0; a < HS::kMtw; a++) {
-    zsum[a] = 0.f;
+    zacc[a] = 0.f;
 #pragma unroll
     for (int b = 0; b < HS::kNtw; b++)
 #pragma unroll
@@ -154,19 +167,31 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
       }
     }
     __syncthreads();
-    // h += K^phi^T V on the matrix cores, z += colsum(K^phi)
+    // K^phi fragments (kept for the attention kernel), h += K^phi^T V on the matrix cores, z_j
+    float zsum[HS::kMtw];
+#pragma unroll
+    for (int a = 0; a < HS::kMtw; a++) zsum[a] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < kTileTokens / 16; ks++) {
       bf16x8 kf[HS::kMtw];
 #pragma unroll
-      for (int a = 0; a < HS::kMtw; a++)
+      for (int a = 0; a < HS::kMtw; a++) {
         kf[a] = kphi_fragment<LD>(ktile, lnz2, mu2[a], ks, 32 * (mt0 + a), lane, zsum[a]);
+        if (nt0 == 0)
+          *reinterpret_cast<bf16x8*>(k_phi + kphi_offset<D>((size_t)bh * Tn + j, mt0 + a, ks, lane)) = kf[a];
+      }
 #pragma unroll
       for (int b = 0; b < HS::kNtw; b++) {
         bf16x8 vf = v_fragment<LD>(vtile, ks, 32 * (nt0 + b), lane);
 #pragma unroll
         for (int a = 0; a < HS::kMtw; a++) hacc[a][b] = mfma_bf16(kf[a], vf, hacc[a][b]);
       }
+    }
+#pragma unroll
+    for (int a = 0; a < HS::kMtw; a++) {
+      const float z = zsum[a] + xhalf(zsum[a]);
+      zacc[a] += z;
+      if (g == 0 && nt0 == 0) z_blocks[((size_t)bh * Tn + j) * D + 32 * (mt0 + a) + lane] = z;
     }
   }
   float* ph = partial + (size_t)blockIdx.x * (D * D + D);
@@ -179,62 +204,93 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
         const int c = 32 * (mt0 + a) + 8 * (e / 4) + 4 * g + e % 4;
         ph[c * D + 32 * (nt0 + b) + lane % 32] = hacc[a][b][e];
       }
-    const float z = zsum[a] + xhalf(zsum[a]);
-    if (g == 0 && nt0 == 0) ph[D * D + 32 * (mt0 + a) + lane] = z;
+    if (g == 0 && nt0 == 0) ph[D * D + 32 * (mt0 + a) + lane] = zacc[a];
   }
 }
 
 hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_t* v, const double* k_mean,
-                                float* k_stats, float* partial, float* h_total, float* z_total, uint8_t* k_fp8,
+                                float* k_stats, float* partial, uint16_t* k_phi, float* z_blocks, uint8_t* k_fp8,
                                 float* k_scale, hipStream_t stream) {
   dim3 grid((unsigned)(s.BH * s.chunks));
 #define SLA2_KV(DD, F8)                                                                                        \
-  kv_state_bf16_kernel<DD, F8><<<grid, 256, 0, stream>>>(k, v, k_mean, k_stats, partial, k_fp8, k_scale, s.N, \
-                                                         s.Tn, s.chunks, s.blocks_per_chunk)
+  kv_state_bf16_kernel<DD, F8><<<grid, 256, 0, stream>>>(k, v, k_mean, k_stats, partial, k_phi, z_blocks, k_fp8, \
+                                                         k_scale, s.N, s.Tn, s.chunks, s.blocks_per_chunk)
   if (s.d == 128) { if (s.fp8) SLA2_KV(128, true); else SLA2_KV(128, false); }
   else            { if (s.fp8) SLA2_KV(64, true);  else SLA2_KV(64, false); }
 #undef SLA2_KV
-  hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  return launch_kv_total(s, partial, h_total, z_total, stream);
+  return hipGetLastError();
 }
 
 // =============================================================================================
 // attn_mfma
 // =============================================================================================
 constexpr int kXcds = 8;
+enum AttnMode { kSparseBf16 = 0, kSparseFp8 = 1, kDenseBf16 = 2 };
 
-template <int D, int BQ> struct AttnSmem {
+__device__ __forceinline__ f32x16 mfma_fp8(long a, long b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, b, c, 0, 0, 0);
+}
+
+// LDS carve-up.  Loop: two buffers, each one K tile (bf16 [64][D+8], or e4m3 [64][D+8 bytes]) and one
+// V tile (bf16 [64][D+8]).  Epilogue: H_i^T as bf16 [D][D+8] and the output tile [BQ][D+8].
+template <int D, int BQ, bool FP8> struct AttnSmem {
   static constexpr int kLd = TileGeom<D>::kLd;
-  static constexpr int kTileBytes = kTileTokens * kLd * 2;
-  // two K and two V tiles during the loop; H_i^T [D][kLd] and the output tile [BQ][kLd] afterwards
-  static constexpr int kLoopBytes = 4 * kTileBytes;
+  static constexpr int kLdK8 = D + 8;                               // bytes per row of an e4m3 K tile
+  static constexpr int kVBytes = kTileTokens * kLd * 2;
+  static constexpr int kKBytes = FP8 ? kTileTokens * kLdK8 : kVBytes;
+  static constexpr int kBufBytes = kKBytes + kVBytes;
+  static constexpr int kLoopBytes = 2 * kBufBytes;
   static constexpr int kEpiBytes = (D + BQ) * kLd * 2;
   static constexpr int kTiles = kLoopBytes > kEpiBytes ? kLoopBytes : kEpiBytes;
-  static constexpr int kLnzOff = kTiles;                       // float [2][64]
-  static constexpr int kZsOff = kLnzOff + 2 * kTileTokens * 4; // float [D]
-  static constexpr int kBytes = kZsOff + D * 4;
+  static constexpr int kZsOff = kTiles;                             // float [D]: Z_i
+  static constexpr int kRedOff = kZsOff + D * 4;                    // float [4]: block-wide max
+  static constexpr int kBytes = kRedOff + 16;
 };
 
-template <int D, int BQ, bool DENSE>
+// 16-byte global loads of one 64 x D e4m3 tile; 8-byte LDS stores (rows are 8-byte aligned only)
+template <int D, int NT>
+struct TileRegs8 {
+  static constexpr int kChunks = D / 16;
+  static constexpr int kLoads = kTileTokens * kChunks / NT;
+  uint4 r[kLoads];
+  __device__ __forceinline__ void load(const uint8_t* src, int tid) {   // rows past the end are stored as zeros
+#pragma unroll
+    for (int i = 0; i < kLoads; i++) {
+      int idx = tid + NT * i;
+      r[i] = *reinterpret_cast<const uint4*>(src + (size_t)(idx / kChunks) * D + 16 * (idx % kChunks));
+    }
+  }
+  __device__ __forceinline__ void store(uint8_t* tile, int tid) const {
+#pragma unroll
+    for (int i = 0; i < kLoads; i++) {
+      int idx = tid + NT * i;
+      uint2* dst = reinterpret_cast<uint2*>(tile + (idx / kChunks) * (D + 8) + 16 * (idx % kChunks));
+      dst[0] = make_uint2(r[i].x, r[i].y);
+      dst[1] = make_uint2(r[i].z, r[i].w);
+    }
+  }
+};
+
+template <int D, int BQ, int MODE>
 __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const double* __restrict__ k_mean, const float* __restrict__ k_stats, const float* __restrict__ h_total,
+    const double* __restrict__ k_mean, const uint16_t* __restrict__ k_phi, const float* __restrict__ z_blocks,
+    const uint8_t* __restrict__ k_fp8, const float* __restrict__ k_scale, const float* __restrict__ h_total,
     const float* __restrict__ z_total, const int32_t* __restrict__ block_idx, const float* __restrict__ alpha,
     uint16_t* __restrict__ out, float* __restrict__ lse, int H, int N, int Tm, int Tn, int ksel, int alpha_per_block,
     int total_blocks) {
+  constexpr bool DENSE = MODE == kDenseBf16, FP8 = MODE == kSparseFp8;
   constexpr int NW = BQ / 32, NT = NW * kWave;
   constexpr int LD = TileGeom<D>::kLd;
   constexpr int KS = D / 16;            // contraction steps over the head dimension
   constexpr int ET = D / 32;            // 32-wide tiles over the head dimension
   typedef HSplit<D, NW> HS;
-  typedef AttnSmem<D, BQ> SM;
+  typedef AttnSmem<D, BQ, FP8> SM;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-  uint16_t* tiles = reinterpret_cast<uint16_t*>(smem);
-  float* lnz_s = reinterpret_cast<float*>(smem + SM::kLnzOff);
   float* zs = reinterpret_cast<float*>(smem + SM::kZsOff);
-  auto ktile = [&](int buf) { return tiles + (2 * buf) * kTileTokens * LD; };
-  auto vtile = [&](int buf) { return tiles + (2 * buf + 1) * kTileTokens * LD; };
+  float* red = reinterpret_cast<float*>(smem + SM::kRedOff);
+  auto kbuf = [&](int buf) { return smem + buf * SM::kBufBytes; };
+  auto vbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + buf * SM::kBufBytes + SM::kKBytes); };
 
   // consecutive query blocks of a head share key/value tiles: keep them on one XCD (workgroups are
   // dealt round-robin to the 8 XCDs, each with its own L2)
@@ -248,10 +304,10 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
   const uint16_t* qh = q + (size_t)bh * N * D;
   const uint16_t* kh = k + (size_t)bh * N * D;
   const uint16_t* vh = v + (size_t)bh * N * D;
-  const float* stats = DENSE ? nullptr : k_stats + (size_t)bh * N;
   const int32_t* sel = DENSE ? nullptr : block_idx + ((size_t)bh * Tm + i) * ksel;
   const int ntiles = DENSE ? Tn : ksel;
   const int mt0 = HS::mt0(w), nt0 = HS::nt0(w);
+  const size_t blk0 = (size_t)bh * Tn;   // first key block of this head in the per-block arrays
 
   // Q fragments (B operand of S^T = K Q^T): lane <- Q[row0 + 32 w + l%32][16 ks + 8 g + 0..7]
   bf16x8 qf[KS];
@@ -265,10 +321,37 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
       qf[ks] = __builtin_bit_cast(bf16x8, u);
     }
   }
-  float mu2[HS::kMtw];
+  // FP8: quant(Q_i) with one scale for the whole query block (Sec. 5)
+  long qf8[FP8 ? KS : 1];
+  float s_q = 1.f;
+  if constexpr (FP8) {
+    float amax = 0.f;
 #pragma unroll
-  for (int a = 0; a < HS::kMtw; a++)
-    mu2[a] = DENSE ? 0.f : (float)k_mean[(size_t)bh * D + 32 * (mt0 + a) + lane % 32] * kLog2e;
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int e = 0; e < 8; e++) amax = fmaxf(amax, fabsf((float)qf[ks][e]));
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
+    if (lane == 0) red[w] = amax;
+    __syncthreads();
+    amax = red[0];
+#pragma unroll
+    for (int x = 1; x < NW; x++) amax = fmaxf(amax, red[x]);
+    const float inv = amax > 0.f ? kE4M3Max / amax : 1.f;
+    s_q = amax > 0.f ? amax / kE4M3Max : 1.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      float y[8];
+#pragma unroll
+      for (int e = 0; e < 8; e++) y[e] = fminf(fmaxf((float)qf[ks][e] * inv, -kE4M3Max), kE4M3Max);
+      int lo = 0, hi = 0;
+      lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], lo, false);
+      lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], lo, true);
+      hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], hi, false);
+      hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], hi, true);
+      qf8[ks] = (long)(((unsigned long)(unsigned)hi << 32) | (unsigned)lo);
+    }
+  }
 
   f32x16 oacc[ET];
 #pragma unroll
@@ -276,41 +359,73 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
 #pragma unroll
     for (int e = 0; e < 16; e++) oacc[et][e] = 0.f;
   f32x16 hacc[HS::kMtw][HS::kNtw];
-  float zsum[HS::kMtw];
+  float zsel[HS::kMtw];
 #pragma unroll
   for (int a = 0; a < HS::kMtw; a++) {
-    zsum[a] = 0.f;
+    zsel[a] = 0.f;
 #pragma unroll
     for (int b = 0; b < HS::kNtw; b++)
 #pragma unroll
       for (int e = 0; e < 16; e++) hacc[a][b][e] = 0.f;
   }
-  float m_run = -INFINITY, l_run = 0.f;              // running max (log2 domain) and sum of this lane's query row
-  const float c1 = kLog2e * rsqrtf((float)D);        // scores are used as S * log2(e) / sqrt(d)
+  // running max and sum of this lane's query row, in the log2 domain.  In FP8 mode P is carried
+  // scaled by 2^8 (the rounding grid of P, see sla2.h): the factor cancels in O / l.
+  float m_run = -INFINITY, l_run = 0.f;
+  constexpr float kPShift = FP8 ? 8.f : 0.f;
+  const float c0 = kLog2e * rsqrtf((float)D);        // scores are used as S * log2(e) / sqrt(d)
 
-  TileRegs<D, NT> kr, vr;
-  float lnz_r = 0.f;
+  // ---- tile prefetch state ----
+  TileRegs<D, NT> vr;
+  TileRegs<D, NT> kr;          // bf16 K tile (unused in FP8 mode)
+  TileRegs8<D, NT> kr8;        // e4m3 K tile (FP8 mode)
+  bf16x8 kphi_r[DENSE ? 1 : HS::kMtw][kTileTokens / 16];
+  float zj_r[DENSE ? 1 : HS::kMtw];
+  float sk_r = 1.f;
   auto tile_of = [&](int s) { return DENSE ? s : sel[s]; };
   auto issue = [&](int s) {
-    const int t0 = tile_of(s) * kTileTokens, valid = min(kTileTokens, N - t0);
-    kr.load(kh + (size_t)t0 * D, valid, tid);
+    const int j = tile_of(s);
+    const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
+    if constexpr (FP8) {
+      kr8.load(k_fp8 + (blk0 + j) * kTileTokens * D, tid);
+      sk_r = k_scale[blk0 + j];
+    } else {
+      kr.load(kh + (size_t)t0 * D, valid, tid);
+    }
     vr.load(vh + (size_t)t0 * D, valid, tid);
-    if (!DENSE && tid < kTileTokens) lnz_r = tid < valid ? stats[t0 + tid] * kLog2e : INFINITY;
+    if constexpr (!DENSE) {
+#pragma unroll
+      for (int a = 0; a < HS::kMtw; a++) {
+#pragma unroll
+        for (int ks = 0; ks < kTileTokens / 16; ks++)
+          kphi_r[a][ks] = *reinterpret_cast<const bf16x8*>(k_phi + kphi_offset<D>(blk0 + j, mt0 + a, ks, lane));
+        zj_r[a] = z_blocks[(blk0 + j) * D + 32 * (mt0 + a) + lane % 32];
+      }
+    }
   };
   auto commit = [&](int buf) {
-    kr.store(ktile(buf), tid);
-    vr.store(vtile(buf), tid);
-    if (!DENSE && tid < kTileTokens) lnz_s[buf * kTileTokens + tid] = lnz_r;
+    if constexpr (FP8) kr8.store(kbuf(buf), tid);
+    else kr.store(reinterpret_cast<uint16_t*>(kbuf(buf)), tid);
+    vr.store(vbuf(buf), tid);
   };
+  bf16x8 kphi_c[DENSE ? 1 : HS::kMtw][kTileTokens / 16];   // fragments of the tile being computed
+  float sk_c = 1.f;
   if (ntiles > 0) { issue(0); commit(0); }
   __syncthreads();
 
   for (int s = 0; s < ntiles; s++) {
     const int buf = s & 1;
     const int valid = min(kTileTokens, N - tile_of(s) * kTileTokens);
+    if constexpr (!DENSE) {
+#pragma unroll
+      for (int a = 0; a < HS::kMtw; a++) {
+#pragma unroll
+        for (int ks = 0; ks < kTileTokens / 16; ks++) kphi_c[a][ks] = kphi_r[a][ks];
+        zsel[a] += zj_r[a];
+      }
+    }
+    sk_c = sk_r;
     if (s + 1 < ntiles) issue(s + 1);
-    const uint16_t* kt = ktile(buf);
-    const uint16_t* vt = vtile(buf);
+    const uint16_t* vt = vbuf(buf);
 
     // ---- S^T = K Q^T (keys x query rows), two 32-key halves ----
     f32x16 sacc[2];
@@ -318,14 +433,27 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
     for (int mt = 0; mt < 2; mt++)
 #pragma unroll
       for (int e = 0; e < 16; e++) sacc[mt][e] = 0.f;
+    if constexpr (FP8) {
+      const uint8_t* kt = kbuf(buf);
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++)
+      for (int ks = 0; ks < KS; ks++)
 #pragma unroll
-      for (int mt = 0; mt < 2; mt++) {
-        bf16x8 a = *reinterpret_cast<const bf16x8*>(kt + (32 * mt + lane % 32) * LD + 16 * ks + 8 * g);
-        sacc[mt] = mfma_bf16(a, qf[ks], sacc[mt]);
-      }
+        for (int mt = 0; mt < 2; mt++) {
+          long a = *reinterpret_cast<const long*>(kt + (32 * mt + lane % 32) * SM::kLdK8 + 16 * ks + 8 * g);
+          sacc[mt] = mfma_fp8(a, qf8[ks], sacc[mt]);
+        }
+    } else {
+      const uint16_t* kt = reinterpret_cast<const uint16_t*>(kbuf(buf));
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+        for (int mt = 0; mt < 2; mt++) {
+          bf16x8 a = *reinterpret_cast<const bf16x8*>(kt + (32 * mt + lane % 32) * LD + 16 * ks + 8 * g);
+          sacc[mt] = mfma_bf16(a, qf[ks], sacc[mt]);
+        }
+    }
     // ---- online softmax of this lane's query row over the 64 keys ----
+    const float c1 = FP8 ? c0 * s_q * sk_c : c0;     // dequantisation folded into the score scale
     if (valid < kTileTokens) {
 #pragma unroll
       for (int mt = 0; mt < 2; mt++)
@@ -340,15 +468,26 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
       for (int e = 0; e < 16; e++) mx = fmaxf(mx, sacc[mt][e]);
     mx = fmaxf(mx, xhalf(mx)) * c1;
     const float m_new = fmaxf(m_run, mx);            // finite: a tile holds at least one key
+    const float m_off = m_new - kPShift;
     float rs = 0.f;
     bf16x8 pf[4];                                    // P^T fragments, token order
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
 #pragma unroll
-      for (int e = 0; e < 16; e++) {
-        const float p = fast_exp2(sacc[mt][e] * c1 - m_new);
-        rs += p;
-        pf[2 * mt + e / 8][e % 8] = (__bf16)p;
+      for (int e = 0; e < 16; e += 2) {
+        const float p0 = fast_exp2(sacc[mt][e] * c1 - m_off);
+        const float p1 = fast_exp2(sacc[mt][e + 1] * c1 - m_off);
+        rs += p0 + p1;                               // the denominator keeps the un-rounded P
+        if constexpr (FP8) {
+          const int codes = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, 0, false);       // quant(P): e4m3 grid
+          typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+          const bf16x2 pq = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes, 1.0f, false);
+          pf[2 * mt + e / 8][e % 8] = pq[0];
+          pf[2 * mt + e / 8][e % 8 + 1] = pq[1];
+        } else {
+          pf[2 * mt + e / 8][e % 8] = (__bf16)p0;
+          pf[2 * mt + e / 8][e % 8 + 1] = (__bf16)p1;
+        }
       }
     rs += xhalf(rs);
     const float corr = fast_exp2(m_run - m_new);     // 0 on the first tile
@@ -360,23 +499,16 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
       for (int e = 0; e < 16; e++) oacc[et][e] *= corr;
 
     // ---- O^T += V^T P^T, and the d x d state of this block: h += K^phi^T V ----
-    const float* lnz2 = lnz_s + buf * kTileTokens;
 #pragma unroll
     for (int ks = 0; ks < kTileTokens / 16; ks++) {
-      bf16x8 kf[HS::kMtw];
-      if (!DENSE) {
-#pragma unroll
-        for (int a = 0; a < HS::kMtw; a++)
-          kf[a] = kphi_fragment<LD>(kt, lnz2, mu2[a], ks, 32 * (mt0 + a), lane, zsum[a]);
-      }
-      if constexpr (HS::kNtw == ET) {                // every V fragment feeds both products
+      if constexpr (HS::kNtw == ET || DENSE) {       // every V fragment feeds both products
 #pragma unroll
         for (int et = 0; et < ET; et++) {
           bf16x8 vf = v_fragment<LD>(vt, ks, 32 * et, lane);
           oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
-          if (!DENSE) {
+          if constexpr (!DENSE) {
 #pragma unroll
-            for (int a = 0; a < HS::kMtw; a++) hacc[a][et] = mfma_bf16(kf[a], vf, hacc[a][et]);
+            for (int a = 0; a < HS::kMtw; a++) hacc[a][et] = mfma_bf16(kphi_c[a][ks], vf, hacc[a][et]);
           }
         }
       } else {
@@ -385,13 +517,11 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
           bf16x8 vf = v_fragment<LD>(vt, ks, 32 * et, lane);
           oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
         }
-        if (!DENSE) {
 #pragma unroll
-          for (int b = 0; b < HS::kNtw; b++) {
-            bf16x8 vf = v_fragment<LD>(vt, ks, 32 * (nt0 + b), lane);
+        for (int b = 0; b < HS::kNtw; b++) {
+          bf16x8 vf = v_fragment<LD>(vt, ks, 32 * (nt0 + b), lane);
 #pragma unroll
-            for (int a = 0; a < HS::kMtw; a++) hacc[a][b] = mfma_bf16(kf[a], vf, hacc[a][b]);
-          }
+          for (int a = 0; a < HS::kMtw; a++) hacc[a][b] = mfma_bf16(kphi_c[a][ks], vf, hacc[a][b]);
         }
       }
     }
@@ -403,10 +533,11 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
   const float inv_l = l_run > 0.f ? 1.f / l_run : 0.f;
   const int qrow = 32 * w + lane % 32;               // this lane's query row inside the block
   if (lse != nullptr) {
-    // Alg. 2 defines L on the smoothed keys; the products above used the raw K, whose scores are
-    // larger by q . colmean(K) / sqrt(d) in every column of a row (which the softmax cancels)
+    // Alg. 2 defines L on the smoothed keys.  The bf16 products above use the raw K, whose scores
+    // are larger by q . colmean(K) / sqrt(d) in every column of a row (the softmax cancels it);
+    // the FP8 codes are those of the smoothed K already.
     float qmu = 0.f;
-    if (!DENSE) {
+    if (!DENSE && !FP8) {
 #pragma unroll
       for (int ks = 0; ks < KS; ks++)
 #pragma unroll
@@ -415,14 +546,14 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
     }
     if (g == 0 && qrow < rows_valid)
       lse[(size_t)bh * N + row0 + qrow] =
-          l_run > 0.f ? (m_run + __log2f(l_run)) * 0.6931471805599453f - qmu * rsqrtf((float)D) : -INFINITY;
+          l_run > 0.f ? (m_run - kPShift + __log2f(l_run)) * 0.6931471805599453f - qmu * rsqrtf((float)D) : -INFINITY;
   }
 
-  uint16_t* ht = tiles;                              // H_i^T as bf16 [e][c], row stride LD
-  uint16_t* os = tiles + D * LD;                     // output tile [BQ][LD]
+  uint16_t* ht = reinterpret_cast<uint16_t*>(smem);  // H_i^T as bf16 [e][c], row stride LD
+  uint16_t* os = ht + D * LD;                        // output tile [BQ][LD]
   f32x16 lacc[ET];
   float inv_den = 0.f;
-  if (!DENSE) {
+  if constexpr (!DENSE) {
     const float* htot = h_total + (size_t)bh * D * D;
 #pragma unroll
     for (int a = 0; a < HS::kMtw; a++) {
@@ -431,17 +562,16 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
         const int e_col = 32 * (nt0 + b) + lane % 32;
 #pragma unroll
         for (int v4 = 0; v4 < 4; v4++) {
-          const int c0 = 32 * (mt0 + a) + 8 * v4 + 4 * g;
+          const int cc = 32 * (mt0 + a) + 8 * v4 + 4 * g;
           bf16x4 pk;
 #pragma unroll
-          for (int r = 0; r < 4; r++) pk[r] = (__bf16)(htot[(c0 + r) * D + e_col] - hacc[a][b][4 * v4 + r]);
-          *reinterpret_cast<bf16x4*>(ht + e_col * LD + c0) = pk;
+          for (int r = 0; r < 4; r++) pk[r] = (__bf16)(htot[(cc + r) * D + e_col] - hacc[a][b][4 * v4 + r]);
+          *reinterpret_cast<bf16x4*>(ht + e_col * LD + cc) = pk;
         }
       }
-      const float z = zsum[a] + xhalf(zsum[a]);
       if (g == 0 && nt0 == 0) {
         const int c = 32 * (mt0 + a) + lane;
-        zs[c] = z_total[(size_t)bh * D + c] - z;
+        zs[c] = z_total[(size_t)bh * D + c] - zsel[a];
       }
     }
     // Q^phi = softmax_d(Q) of this lane's row, kept as fragments
@@ -503,7 +633,7 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
 #pragma unroll
       for (int r = 0; r < 4; r++) {
         float o = ws * oacc[et][4 * v4 + r];
-        if (!DENSE) o += wl * lacc[et][4 * v4 + r];
+        if constexpr (!DENSE) o += wl * lacc[et][4 * v4 + r];
         pk[r] = (__bf16)o;
       }
       *reinterpret_cast<bf16x4*>(os + qrow * LD + 32 * et + 8 * v4 + 4 * g) = pk;
@@ -516,15 +646,25 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
   }
 }
 
-template <int D, int BQ, bool DENSE>
-static hipError_t launch_attn_t(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v,
-                                const double* k_mean, const float* k_stats, const float* h_total, const float* z_total,
-                                const int32_t* block_idx, const float* alpha, uint16_t* out, float* lse,
-                                hipStream_t stream) {
-  constexpr int smem = AttnSmem<D, BQ>::kBytes;
+struct AttnArgs {
+  const uint16_t *q, *k, *v;
+  const double* k_mean;
+  const uint16_t* k_phi;
+  const float* z_blocks;
+  const uint8_t* k_fp8;
+  const float *k_scale, *h_total, *z_total;
+  const int32_t* block_idx;
+  const float* alpha;
+  uint16_t* out;
+  float* lse;
+};
+
+template <int D, int BQ, int MODE>
+static hipError_t launch_attn_t(const Shape& s, const AttnArgs& a, hipStream_t stream) {
+  constexpr int smem = AttnSmem<D, BQ, MODE == kSparseFp8>::kBytes;
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<D, BQ, DENSE>,
+    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<D, BQ, MODE>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
     configured = true;
@@ -532,18 +672,21 @@ static hipError_t launch_attn_t(const Shape& s, const uint16_t* q, const uint16_
   const int Tm = (s.N + BQ - 1) / BQ;
   const int total = s.BH * Tm;
   const int grid = ((total + kXcds - 1) / kXcds) * kXcds;
-  attn_mfma_kernel<D, BQ, DENSE><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(
-      q, k, v, k_mean, k_stats, h_total, z_total, block_idx, alpha, out, lse, s.H, s.N, Tm, s.Tn, s.k,
-      s.alpha_per_block ? 1 : 0, total);
+  attn_mfma_kernel<D, BQ, MODE><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(
+      a.q, a.k, a.v, a.k_mean, a.k_phi, a.z_blocks, a.k_fp8, a.k_scale, a.h_total, a.z_total, a.block_idx, a.alpha,
+      a.out, a.lse, s.H, s.N, Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0, total);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v,
-                            const double* k_mean, const float* k_stats, const float* h_total, const float* z_total,
+                            const double* k_mean, const uint16_t* k_phi, const float* z_blocks, const uint8_t* k_fp8,
+                            const float* k_scale, const float* h_total, const float* z_total,
                             const int32_t* block_idx, const float* alpha, uint16_t* out, float* lse,
                             hipStream_t stream) {
-#define SLA2_ATTN(DD, QQ) \
-  return launch_attn_t<DD, QQ, false>(s, q, k, v, k_mean, k_stats, h_total, z_total, block_idx, alpha, out, lse, stream)
+  AttnArgs a{q, k, v, k_mean, k_phi, z_blocks, k_fp8, k_scale, h_total, z_total, block_idx, alpha, out, lse};
+#define SLA2_ATTN(DD, QQ)                                                  \
+  return s.fp8 ? launch_attn_t<DD, QQ, kSparseFp8>(s, a, stream)           \
+               : launch_attn_t<DD, QQ, kSparseBf16>(s, a, stream)
   if (s.d == 128 && s.bq == 128) SLA2_ATTN(128, 128);
   if (s.d == 128 && s.bq == 64) SLA2_ATTN(128, 64);
   if (s.d == 64 && s.bq == 128) SLA2_ATTN(64, 128);
@@ -553,11 +696,9 @@ hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k
 
 hipError_t launch_dense_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
                              hipStream_t stream) {
-  if (s.d == 128)
-    return launch_attn_t<128, 128, true>(s, q, k, v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, out, nullptr,
-                                         stream);
-  return launch_attn_t<64, 128, true>(s, q, k, v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, out, nullptr,
-                                      stream);
+  AttnArgs a{q, k, v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, out, nullptr};
+  if (s.d == 128) return launch_attn_t<128, 128, kDenseBf16>(s, a, stream);
+  return launch_attn_t<64, 128, kDenseBf16>(s, a, stream);
 }
 
 }  // namespace sla2
