@@ -15,9 +15,30 @@ namespace sla2 {
 
 constexpr int kTileTokens = 64;                    // b_kv
 
+// ---- LDS layouts of a 64-token tile of bf16 rows --------------------------------------------------
+// Padded: rows of D + 8 elements (written with ordinary LDS stores).
+// Swizzled: rows of exactly D elements whose 16-byte chunks are XOR-permuted by the row index.  This
+// is the layout for tiles that the load unit writes straight into LDS (global_load_lds_dwordx4 puts
+// lane l's 16 bytes at base + 16 l, so a tile has to be contiguous); the permutation is applied by
+// choosing which global chunk a lane fetches, and keeps both the row-wise 16-byte operand reads and
+// the transposing 8-byte reads spread over the banks.
+template <int D> struct PaddedLayout {
+  static constexpr int kRowElems = D + 8;
+  static constexpr int kTileBytes = kTileTokens * kRowElems * 2;
+  __device__ static __forceinline__ int offset(int row, int col) { return row * kRowElems + col; }   // elements
+};
+template <int D> struct SwizzledLayout {
+  static constexpr int kChunks = D / 8;              // 16-byte chunks per row
+  static constexpr int kRowElems = D;
+  static constexpr int kTileBytes = kTileTokens * D * 2;
+  __device__ static __forceinline__ int swz(int row) { return kChunks >= 16 ? 2 * (row & 7) : (row & 7); }
+  __device__ static __forceinline__ int offset(int row, int col) {
+    return row * D + (((col >> 3) ^ swz(row)) << 3) + (col & 7);
+  }
+};
+
 template <int D> struct TileGeom {
-  static constexpr int kLd = D + 8;                // bf16 elements per LDS row (16-byte padded)
-  static constexpr int kTileElems = kTileTokens * kLd;
+  static constexpr int kLd = D + 8;                // bf16 elements per padded LDS row
   static constexpr int kChunksPerRow = D / 8;      // 16-byte chunks per row
 };
 
@@ -25,22 +46,81 @@ typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 
 // 4 tokens x 16 channels per 16-lane group, transposed on the way out of LDS: on return lane l
 // holds tile[row0 + 0..3][col0 + l % 32] (row0 may differ between the two lane halves).
-template <int LD>
+template <class L>
 __device__ __forceinline__ s16x4 read_tr4(const uint16_t* tile, int row0, int col0, int lane) {
   const int row = row0 + (lane % 16) / 4;
   const int col = col0 + 16 * ((lane / 16) % 2) + 4 * (lane % 4);
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + row * LD + col));
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(tile + L::offset(row, col)));
 }
 
 // V fragment in token order: lane l <- V[token(ks, l/32, 0..7)][col0 + l % 32]   (raw bf16 bits)
-template <int LD>
+template <class L>
 __device__ __forceinline__ bf16x8 v_fragment(const uint16_t* vtile, int ks, int col0, int lane) {
   const int g = lane / 32;
-  s16x4 lo = read_tr4<LD>(vtile, 16 * ks + 4 * g, col0, lane);
-  s16x4 hi = read_tr4<LD>(vtile, 16 * ks + 8 + 4 * g, col0, lane);
+  s16x4 lo = read_tr4<L>(vtile, 16 * ks + 4 * g, col0, lane);
+  s16x4 hi = read_tr4<L>(vtile, 16 * ks + 8 + 4 * g, col0, lane);
   typedef __attribute__((ext_vector_type(8))) short s16x8;
   s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
   return __builtin_bit_cast(bf16x8, r);
+}
+
+// Row-wise operand fragment: lane l <- tile[row][col .. col + 7]  (one 16-byte read)
+template <class L>
+__device__ __forceinline__ bf16x8 row_fragment(const uint16_t* tile, int row, int col) {
+  return *reinterpret_cast<const bf16x8*>(tile + L::offset(row, col));
+}
+
+// One 64 x D bf16 tile, global memory -> LDS without passing through registers.  NW waves cooperate;
+// each global_load_lds_dwordx4 moves 1 KB (64 lanes x 16 bytes) into consecutive LDS bytes.
+// Completion is counted by vmcnt.  The swizzle of a row depends on row % 8 only and every
+// instruction of a wave starts at a multiple of 8 rows apart, so a lane's source offset is one
+// value plus a constant per instruction.  A ragged last tile (valid < 64) repeats its last row.
+template <int D, int NW>
+__device__ __forceinline__ void dma_tile(const uint16_t* src /* first row */, int valid, uint16_t* tile, int w, int lane) {
+  typedef SwizzledLayout<D> L;
+  constexpr int kRowsPerInstr = 1024 / (D * 2);
+  constexpr int kInstrs = kTileTokens / kRowsPerInstr / NW;
+  static_assert((kRowsPerInstr * NW) % 8 == 0, "row swizzle must repeat between the instructions of a wave");
+  const int row_w = w * kRowsPerInstr + lane / L::kChunks;           // row of instruction 0
+  const int chunk = (lane % L::kChunks) ^ L::swz(row_w);
+  if (valid == kTileTokens) {
+    const uint16_t* g = src + row_w * D + 8 * chunk;
+#pragma unroll
+    for (int i = 0; i < kInstrs; i++)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + i * NW * kRowsPerInstr * D),
+                                       (__attribute__((address_space(3))) void*)(tile + (i * NW + w) * 512), 16, 0, 0);
+  } else {
+#pragma unroll
+    for (int i = 0; i < kInstrs; i++) {
+      const int row = min(row_w + i * NW * kRowsPerInstr, valid - 1);
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (size_t)row * D + 8 * chunk),
+                                       (__attribute__((address_space(3))) void*)(tile + (i * NW + w) * 512), 16, 0, 0);
+    }
+  }
+}
+
+// The same for a 64 x D tile of e4m3 codes (rows of D bytes; 8-byte operand reads).
+template <int D> struct SwizzledLayout8 {
+  static constexpr int kChunks = D / 16;             // 16-byte chunks per row
+  static constexpr int kTileBytes = kTileTokens * D;
+  __device__ static __forceinline__ int swz(int row) { return row & (kChunks - 1); }
+  __device__ static __forceinline__ int offset(int row, int col) {   // bytes; col multiple of 8
+    return row * D + (((col >> 4) ^ swz(row)) << 4) + (col & 15);
+  }
+};
+template <int D, int NW>
+__device__ __forceinline__ void dma_tile8(const uint8_t* src, uint8_t* tile, int w, int lane) {
+  typedef SwizzledLayout8<D> L;
+  constexpr int kRowsPerInstr = 1024 / D;
+  constexpr int kInstrs = kTileTokens / kRowsPerInstr / NW;
+  static_assert(kInstrs >= 1 && (kRowsPerInstr * NW) % 8 == 0, "unsupported tile split");
+  const int row_w = w * kRowsPerInstr + lane / L::kChunks;
+  const int chunk = (lane % L::kChunks) ^ L::swz(row_w);
+  const uint8_t* g = src + row_w * D + 16 * chunk;
+#pragma unroll
+  for (int i = 0; i < kInstrs; i++)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + i * NW * kRowsPerInstr * D),
+                                     (__attribute__((address_space(3))) void*)(tile + (i * NW + w) * 1024), 16, 0, 0);
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -49,12 +129,12 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 //   K^phi[t][c] = exp(k[t][c] - mu[c] - lnZ[t]) = exp2(k log2e - (mu2 + lnz2[t]))
 // lnz2: LDS array of 64 floats, lnZ[t] * log2e, +inf for tokens past the end (-> K^phi = 0).
 // Adds the 8 fp32 values to zsum (column sums of K^phi, Alg. 2's z).
-template <int LD>
+template <class L>
 __device__ __forceinline__ bf16x8 kphi_fragment(const uint16_t* ktile, const float* lnz2, float mu2, int ks, int col0,
                                                 int lane, float& zsum) {
   const int g = lane / 32;
-  s16x4 lo = read_tr4<LD>(ktile, 16 * ks + 4 * g, col0, lane);
-  s16x4 hi = read_tr4<LD>(ktile, 16 * ks + 8 + 4 * g, col0, lane);
+  s16x4 lo = read_tr4<L>(ktile, 16 * ks + 4 * g, col0, lane);
+  s16x4 hi = read_tr4<L>(ktile, 16 * ks + 8 + 4 * g, col0, lane);
   const f32x4 zl = *reinterpret_cast<const f32x4*>(lnz2 + 16 * ks + 4 * g);
   const f32x4 zh = *reinterpret_cast<const f32x4*>(lnz2 + 16 * ks + 8 + 4 * g);
   bf16x8 r;
@@ -69,26 +149,26 @@ __device__ __forceinline__ bf16x8 kphi_fragment(const uint16_t* ktile, const flo
   return r;
 }
 
-// 16-byte global loads of one 64 x D bf16 tile into registers (rows past `valid` read as zero),
-// and the matching stores into a padded LDS tile.  NT threads cooperate.
-template <int D, int NT>
-struct TileRegs {
+// 16-byte global loads of one 64 x D bf16 tile into registers and the matching stores into a padded
+// LDS tile.  NT threads cooperate.  Rows past `valid` repeat the last existing row: the loads stay
+// unpredicated, so they can remain in flight across a whole compute phase.
+template <int D, int NT> struct TileCopy {
   static constexpr int kLoads = kTileTokens * TileGeom<D>::kChunksPerRow / NT;
-  uint4 r[kLoads];
-  __device__ __forceinline__ void load(const uint16_t* src /* first row of the tile */, int valid, int tid) {
+  __device__ static __forceinline__ void load(u32x4 (&r)[kLoads], const uint16_t* src /* first row */, int valid,
+                                              int tid) {
 #pragma unroll
     for (int i = 0; i < kLoads; i++) {
-      int idx = tid + NT * i;
-      int row = idx / TileGeom<D>::kChunksPerRow, ch = idx % TileGeom<D>::kChunksPerRow;
-      r[i] = row < valid ? *reinterpret_cast<const uint4*>(src + (size_t)row * D + 8 * ch) : make_uint4(0, 0, 0, 0);
+      const int idx = tid + NT * i;
+      const int row = min(idx / TileGeom<D>::kChunksPerRow, valid - 1), ch = idx % TileGeom<D>::kChunksPerRow;
+      r[i] = *reinterpret_cast<const u32x4*>(src + (size_t)row * D + 8 * ch);
     }
   }
-  __device__ __forceinline__ void store(uint16_t* tile, int tid) const {
+  __device__ static __forceinline__ void store(const u32x4 (&r)[kLoads], uint16_t* tile, int tid) {
 #pragma unroll
     for (int i = 0; i < kLoads; i++) {
-      int idx = tid + NT * i;
-      int row = idx / TileGeom<D>::kChunksPerRow, ch = idx % TileGeom<D>::kChunksPerRow;
-      *reinterpret_cast<uint4*>(tile + row * TileGeom<D>::kLd + 8 * ch) = r[i];
+      const int idx = tid + NT * i;
+      const int row = idx / TileGeom<D>::kChunksPerRow, ch = idx % TileGeom<D>::kChunksPerRow;
+      *reinterpret_cast<u32x4*>(tile + row * TileGeom<D>::kLd + 8 * ch) = r[i];
     }
   }
 };

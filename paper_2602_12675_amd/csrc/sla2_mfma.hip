@@ -91,21 +91,22 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
       for (int e = 0; e < 16; e++) hacc[a][b][e] = 0.f;
   }
 
-  TileRegs<D, 256> kr, vr;
+  typedef TileCopy<D, 256> TC;
+  u32x4 kr[TC::kLoads], vr[TC::kLoads];
   if (j0 < j1) {
     const int valid = min(kTileTokens, N - j0 * kTileTokens);
-    kr.load(kh + (size_t)j0 * kTileTokens * D, valid, tid);
-    vr.load(vh + (size_t)j0 * kTileTokens * D, valid, tid);
+    TC::load(kr, kh + (size_t)j0 * kTileTokens * D, valid, tid);
+    TC::load(vr, vh + (size_t)j0 * kTileTokens * D, valid, tid);
   }
   for (int j = j0; j < j1; j++) {
     const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
     __syncthreads();                                   // previous tile fully consumed
-    kr.store(ktile, tid);
-    vr.store(vtile, tid);
+    TC::store(kr, ktile, tid);
+    TC::store(vr, vtile, tid);
     if (j + 1 < j1) {
       const int nvalid = min(kTileTokens, N - (j + 1) * kTileTokens);
-      kr.load(kh + (size_t)(j + 1) * kTileTokens * D, nvalid, tid);
-      vr.load(vh + (size_t)(j + 1) * kTileTokens * D, nvalid, tid);
+      TC::load(kr, kh + (size_t)(j + 1) * kTileTokens * D, nvalid, tid);
+      TC::load(vr, vh + (size_t)(j + 1) * kTileTokens * D, nvalid, tid);
     }
     __syncthreads();
     {  // per-token log-partition of softmax_d(k'), 4 threads per token
@@ -176,13 +177,13 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
       bf16x8 kf[HS::kMtw];
 #pragma unroll
       for (int a = 0; a < HS::kMtw; a++) {
-        kf[a] = kphi_fragment<LD>(ktile, lnz2, mu2[a], ks, 32 * (mt0 + a), lane, zsum[a]);
+        kf[a] = kphi_fragment<PaddedLayout<D>>(ktile, lnz2, mu2[a], ks, 32 * (mt0 + a), lane, zsum[a]);
         if (nt0 == 0)
           *reinterpret_cast<bf16x8*>(k_phi + kphi_offset<D>((size_t)bh * Tn + j, mt0 + a, ks, lane)) = kf[a];
       }
 #pragma unroll
       for (int b = 0; b < HS::kNtw; b++) {
-        bf16x8 vf = v_fragment<LD>(vtile, ks, 32 * (nt0 + b), lane);
+        bf16x8 vf = v_fragment<PaddedLayout<D>>(vtile, ks, 32 * (nt0 + b), lane);
 #pragma unroll
         for (int a = 0; a < HS::kMtw; a++) hacc[a][b] = mfma_bf16(kf[a], vf, hacc[a][b]);
       }
@@ -231,13 +232,13 @@ __device__ __forceinline__ f32x16 mfma_fp8(long a, long b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, b, c, 0, 0, 0);
 }
 
-// LDS carve-up.  Loop: two buffers, each one K tile (bf16 [64][D+8], or e4m3 [64][D+8 bytes]) and one
-// V tile (bf16 [64][D+8]).  Epilogue: H_i^T as bf16 [D][D+8] and the output tile [BQ][D+8].
+// LDS carve-up.  Loop: two buffers, each one K tile (bf16, or e4m3 in FP8 mode) and one V tile (bf16),
+// all in the swizzled layout the load unit fills directly.  Epilogue: H_i^T as bf16 [D][D+8] and the
+// output tile [BQ][D+8], overlaying the tile buffers.
 template <int D, int BQ, bool FP8> struct AttnSmem {
   static constexpr int kLd = TileGeom<D>::kLd;
-  static constexpr int kLdK8 = D + 8;                               // bytes per row of an e4m3 K tile
-  static constexpr int kVBytes = kTileTokens * kLd * 2;
-  static constexpr int kKBytes = FP8 ? kTileTokens * kLdK8 : kVBytes;
+  static constexpr int kVBytes = SwizzledLayout<D>::kTileBytes;
+  static constexpr int kKBytes = FP8 ? SwizzledLayout8<D>::kTileBytes : kVBytes;
   static constexpr int kBufBytes = kKBytes + kVBytes;
   static constexpr int kLoopBytes = 2 * kBufBytes;
   static constexpr int kEpiBytes = (D + BQ) * kLd * 2;
@@ -247,32 +248,10 @@ template <int D, int BQ, bool FP8> struct AttnSmem {
   static constexpr int kBytes = kRedOff + 16;
 };
 
-// 16-byte global loads of one 64 x D e4m3 tile; 8-byte LDS stores (rows are 8-byte aligned only)
-template <int D, int NT>
-struct TileRegs8 {
-  static constexpr int kChunks = D / 16;
-  static constexpr int kLoads = kTileTokens * kChunks / NT;
-  uint4 r[kLoads];
-  __device__ __forceinline__ void load(const uint8_t* src, int tid) {   // rows past the end are stored as zeros
-#pragma unroll
-    for (int i = 0; i < kLoads; i++) {
-      int idx = tid + NT * i;
-      r[i] = *reinterpret_cast<const uint4*>(src + (size_t)(idx / kChunks) * D + 16 * (idx % kChunks));
-    }
-  }
-  __device__ __forceinline__ void store(uint8_t* tile, int tid) const {
-#pragma unroll
-    for (int i = 0; i < kLoads; i++) {
-      int idx = tid + NT * i;
-      uint2* dst = reinterpret_cast<uint2*>(tile + (idx / kChunks) * (D + 8) + 16 * (idx % kChunks));
-      dst[0] = make_uint2(r[i].x, r[i].y);
-      dst[1] = make_uint2(r[i].z, r[i].w);
-    }
-  }
-};
+constexpr int kVmcnt0 = 0x0F70;   // s_waitcnt vmcnt(0), other counters untouched
 
 template <int D, int BQ, int MODE>
-__global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
+__global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const double* __restrict__ k_mean, const uint16_t* __restrict__ k_phi, const float* __restrict__ z_blocks,
     const uint8_t* __restrict__ k_fp8, const float* __restrict__ k_scale, const float* __restrict__ h_total,
@@ -286,7 +265,9 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
   constexpr int ET = D / 32;            // 32-wide tiles over the head dimension
   typedef HSplit<D, NW> HS;
   typedef AttnSmem<D, BQ, FP8> SM;
-  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  typedef SwizzledLayout<D> SL;
+  typedef SwizzledLayout8<D> SL8;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   float* zs = reinterpret_cast<float*>(smem + SM::kZsOff);
   float* red = reinterpret_cast<float*>(smem + SM::kRedOff);
   auto kbuf = [&](int buf) { return smem + buf * SM::kBufBytes; };
@@ -309,18 +290,28 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
   const int mt0 = HS::mt0(w), nt0 = HS::nt0(w);
   const size_t blk0 = (size_t)bh * Tn;   // first key block of this head in the per-block arrays
 
+  // tile s: global memory -> LDS buffer `buf`, no registers involved (completion: vmcnt)
+  auto dma = [&](int s, int buf) {
+    const int j = DENSE ? s : sel[s];
+    const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
+    if constexpr (FP8) dma_tile8<D, NW>(k_fp8 + (blk0 + j) * kTileTokens * D, kbuf(buf), w, lane);
+    else dma_tile<D, NW>(kh + (size_t)t0 * D, valid, reinterpret_cast<uint16_t*>(kbuf(buf)), w, lane);
+    dma_tile<D, NW>(vh + (size_t)t0 * D, valid, vbuf(buf), w, lane);
+  };
+  if (ntiles > 0) dma(0, 0);
+
   // Q fragments (B operand of S^T = K Q^T): lane <- Q[row0 + 32 w + l%32][16 ks + 8 g + 0..7]
   bf16x8 qf[KS];
   {
-    const int r = 32 * w + lane % 32;
-    const bool ok = r < rows_valid;
-    const uint16_t* src = qh + (size_t)(row0 + (ok ? r : 0)) * D + 8 * g;
+    const int r = min(32 * w + lane % 32, rows_valid - 1);   // rows past the end repeat the last one; never stored
+    const uint16_t* src = qh + (size_t)(row0 + r) * D + 8 * g;
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++) {
-      uint4 u = ok ? *reinterpret_cast<const uint4*>(src + 16 * ks) : make_uint4(0, 0, 0, 0);
-      qf[ks] = __builtin_bit_cast(bf16x8, u);
-    }
+    for (int ks = 0; ks < KS; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
   }
+  // Everything issued so far is settled here, on every path into the main loop; a pending load
+  // left over from the prologue would otherwise put a vmcnt wait in front of every use of a Q
+  // fragment inside the loop and drain the tile prefetch with it.
+  __builtin_amdgcn_s_waitcnt(kVmcnt0);
   // FP8: quant(Q_i) with one scale for the whole query block (Sec. 5)
   long qf8[FP8 ? KS : 1];
   float s_q = 1.f;
@@ -352,6 +343,7 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
       qf8[ks] = (long)(((unsigned long)(unsigned)hi << 32) | (unsigned)lo);
     }
   }
+  __syncthreads();                                   // tile 0 is in LDS for everyone
 
   f32x16 oacc[ET];
 #pragma unroll
@@ -374,58 +366,26 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
   constexpr float kPShift = FP8 ? 8.f : 0.f;
   const float c0 = kLog2e * rsqrtf((float)D);        // scores are used as S * log2(e) / sqrt(d)
 
-  // ---- tile prefetch state ----
-  TileRegs<D, NT> vr;
-  TileRegs<D, NT> kr;          // bf16 K tile (unused in FP8 mode)
-  TileRegs8<D, NT> kr8;        // e4m3 K tile (FP8 mode)
-  bf16x8 kphi_r[DENSE ? 1 : HS::kMtw][kTileTokens / 16];
-  float zj_r[DENSE ? 1 : HS::kMtw];
-  float sk_r = 1.f;
-  auto tile_of = [&](int s) { return DENSE ? s : sel[s]; };
-  auto issue = [&](int s) {
-    const int j = tile_of(s);
-    const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
-    if constexpr (FP8) {
-      kr8.load(k_fp8 + (blk0 + j) * kTileTokens * D, tid);
-      sk_r = k_scale[blk0 + j];
-    } else {
-      kr.load(kh + (size_t)t0 * D, valid, tid);
-    }
-    vr.load(vh + (size_t)t0 * D, valid, tid);
+  for (int s = 0; s < ntiles; s++) {
+    const int buf = s & 1;
+    const int j = DENSE ? s : sel[s];
+    const int valid = min(kTileTokens, N - j * kTileTokens);
+    float sk = 1.f;
+    if constexpr (FP8) sk = k_scale[blk0 + j];
+    if (s + 1 < ntiles) dma(s + 1, buf ^ 1);
+    const uint16_t* vt = vbuf(buf);
+    // K^phi fragments and z_j of this tile straight from global memory into registers (no other
+    // wave needs them); they are consumed after the softmax
+    bf16x8 kphi[DENSE ? 1 : HS::kMtw][kTileTokens / 16];
     if constexpr (!DENSE) {
 #pragma unroll
       for (int a = 0; a < HS::kMtw; a++) {
 #pragma unroll
         for (int ks = 0; ks < kTileTokens / 16; ks++)
-          kphi_r[a][ks] = *reinterpret_cast<const bf16x8*>(k_phi + kphi_offset<D>(blk0 + j, mt0 + a, ks, lane));
-        zj_r[a] = z_blocks[(blk0 + j) * D + 32 * (mt0 + a) + lane % 32];
+          kphi[a][ks] = *reinterpret_cast<const bf16x8*>(k_phi + kphi_offset<D>(blk0 + j, mt0 + a, ks, lane));
+        zsel[a] += z_blocks[(blk0 + j) * D + 32 * (mt0 + a) + lane % 32];
       }
     }
-  };
-  auto commit = [&](int buf) {
-    if constexpr (FP8) kr8.store(kbuf(buf), tid);
-    else kr.store(reinterpret_cast<uint16_t*>(kbuf(buf)), tid);
-    vr.store(vbuf(buf), tid);
-  };
-  bf16x8 kphi_c[DENSE ? 1 : HS::kMtw][kTileTokens / 16];   // fragments of the tile being computed
-  float sk_c = 1.f;
-  if (ntiles > 0) { issue(0); commit(0); }
-  __syncthreads();
-
-  for (int s = 0; s < ntiles; s++) {
-    const int buf = s & 1;
-    const int valid = min(kTileTokens, N - tile_of(s) * kTileTokens);
-    if constexpr (!DENSE) {
-#pragma unroll
-      for (int a = 0; a < HS::kMtw; a++) {
-#pragma unroll
-        for (int ks = 0; ks < kTileTokens / 16; ks++) kphi_c[a][ks] = kphi_r[a][ks];
-        zsel[a] += zj_r[a];
-      }
-    }
-    sk_c = sk_r;
-    if (s + 1 < ntiles) issue(s + 1);
-    const uint16_t* vt = vbuf(buf);
 
     // ---- S^T = K Q^T (keys x query rows), two 32-key halves ----
     f32x16 sacc[2];
@@ -439,7 +399,7 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
       for (int ks = 0; ks < KS; ks++)
 #pragma unroll
         for (int mt = 0; mt < 2; mt++) {
-          long a = *reinterpret_cast<const long*>(kt + (32 * mt + lane % 32) * SM::kLdK8 + 16 * ks + 8 * g);
+          long a = *reinterpret_cast<const long*>(kt + SL8::offset(32 * mt + lane % 32, 16 * ks + 8 * g));
           sacc[mt] = mfma_fp8(a, qf8[ks], sacc[mt]);
         }
     } else {
@@ -447,13 +407,11 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
 #pragma unroll
       for (int ks = 0; ks < KS; ks++)
 #pragma unroll
-        for (int mt = 0; mt < 2; mt++) {
-          bf16x8 a = *reinterpret_cast<const bf16x8*>(kt + (32 * mt + lane % 32) * LD + 16 * ks + 8 * g);
-          sacc[mt] = mfma_bf16(a, qf[ks], sacc[mt]);
-        }
+        for (int mt = 0; mt < 2; mt++)
+          sacc[mt] = mfma_bf16(row_fragment<SL>(kt, 32 * mt + lane % 32, 16 * ks + 8 * g), qf[ks], sacc[mt]);
     }
     // ---- online softmax of this lane's query row over the 64 keys ----
-    const float c1 = FP8 ? c0 * s_q * sk_c : c0;     // dequantisation folded into the score scale
+    const float c1 = FP8 ? c0 * s_q * sk : c0;       // dequantisation folded into the score scale
     if (valid < kTileTokens) {
 #pragma unroll
       for (int mt = 0; mt < 2; mt++)
@@ -504,29 +462,29 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
       if constexpr (HS::kNtw == ET || DENSE) {       // every V fragment feeds both products
 #pragma unroll
         for (int et = 0; et < ET; et++) {
-          bf16x8 vf = v_fragment<LD>(vt, ks, 32 * et, lane);
+          bf16x8 vf = v_fragment<SL>(vt, ks, 32 * et, lane);
           oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
           if constexpr (!DENSE) {
 #pragma unroll
-            for (int a = 0; a < HS::kMtw; a++) hacc[a][et] = mfma_bf16(kphi_c[a][ks], vf, hacc[a][et]);
+            for (int a = 0; a < HS::kMtw; a++) hacc[a][et] = mfma_bf16(kphi[a][ks], vf, hacc[a][et]);
           }
         }
       } else {
 #pragma unroll
         for (int et = 0; et < ET; et++) {
-          bf16x8 vf = v_fragment<LD>(vt, ks, 32 * et, lane);
+          bf16x8 vf = v_fragment<SL>(vt, ks, 32 * et, lane);
           oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
         }
 #pragma unroll
         for (int b = 0; b < HS::kNtw; b++) {
-          bf16x8 vf = v_fragment<LD>(vt, ks, 32 * (nt0 + b), lane);
+          bf16x8 vf = v_fragment<SL>(vt, ks, 32 * (nt0 + b), lane);
 #pragma unroll
-          for (int a = 0; a < HS::kMtw; a++) hacc[a][b] = mfma_bf16(kphi_c[a][ks], vf, hacc[a][b]);
+          for (int a = 0; a < HS::kMtw; a++) hacc[a][b] = mfma_bf16(kphi[a][ks], vf, hacc[a][b]);
         }
       }
     }
-    if (s + 1 < ntiles) commit(buf ^ 1);
-    __syncthreads();
+    __builtin_amdgcn_s_waitcnt(kVmcnt0);             // the next tile has landed in LDS ...
+    __syncthreads();                                 // ... for everyone, and this tile's buffer is free
   }
 
   // ================= epilogue =================
@@ -569,6 +527,7 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
           *reinterpret_cast<bf16x4*>(ht + e_col * LD + cc) = pk;
         }
       }
+      // zsel holds the same sum on both lane halves (each half added z_j of channel l % 32)
       if (g == 0 && nt0 == 0) {
         const int c = 32 * (mt0 + a) + lane;
         zs[c] = z_total[(size_t)bh * D + c] - zsel[a];
@@ -642,7 +601,7 @@ __global__ __launch_bounds__(BQ * 2) void attn_mfma_kernel(
   uint16_t* oh = out + ((size_t)bh * N + row0) * D;
   for (int idx = tid; idx < BQ * (D / 8); idx += NT) {
     const int r = idx / (D / 8), ch = idx % (D / 8);
-    if (r < rows_valid) *reinterpret_cast<uint4*>(oh + (size_t)r * D + 8 * ch) = *reinterpret_cast<const uint4*>(os + r * LD + 8 * ch);
+    if (r < rows_valid) *reinterpret_cast<u32x4*>(oh + (size_t)r * D + 8 * ch) = *reinterpret_cast<const u32x4*>(os + r * LD + 8 * ch);
   }
 }
 
