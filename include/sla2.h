@@ -81,9 +81,8 @@ typedef struct sla2_params {
 typedef struct sla2_ws_layout {
   size_t q_sum;     /* double [BH, T_m, d]   sum of the rows of each query block            (Eq. 15 x block size) */
   size_t k_sum;     /* double [BH, T_n, d]   same for the raw K blocks */
-  size_t k_mean;    /* double [BH, d]        colmean(K) (zeros with SLA2_FLAG_NO_SMOOTH_K)  (Alg. 2, smoothing) */
-  size_t q_proj;    /* double [BH, T_m, d]   proj_q(pool Q) / sqrt(d)                       (Eq. 16) */
-  size_t k_proj;    /* double [BH, T_n, d]   proj_k(pool(K - colmean K)) */
+  size_t k_mean;    /* double [BH, d]        colmean(K) (zeros with SLA2_FLAG_NO_SMOOTH_K)   (Alg. 2, smoothing) */
+  size_t router_m;  /* double [1 or H, d, d] Wq Wk^T / sqrt(d): the two router projections folded into one matrix (Eq. 16) */
   size_t block_idx; /* int32  [BH, T_m, k]   ascending selected key/value blocks (M_c)      (Eq. 16) */
   size_t h_total;   /* float  [BH, d, d]     sum over all key blocks of (K^phi_j)^T V_j     (Alg. 2: h) */
   size_t z_total;   /* float  [BH, d]        sum over all key blocks of colsum(K^phi_j)     (Alg. 2: z) */
@@ -110,8 +109,10 @@ int sla2_num_selected(const sla2_params* params);
  * [d_in, d_out] row-major fp32, proj(x) = x W, no bias), score
  * R = proj_q(Qbar) proj_k(Kbar)^T / sqrt(d) and keep, per query block, the k
  * largest scores; equal scores go to the lower block index.  The row softmax of
- * Alg. 2 is omitted: it does not change a row-wise top-k.  All arithmetic is
- * fp64 so that the selection matches an fp64 reference up to summation order.
+ * Alg. 2 is omitted, and so is the subtraction of colmean(K) inside the router
+ * (it moves all scores of a row by the same amount): neither changes a row-wise
+ * top-k.  All arithmetic is fp64 so that the selection matches an fp64
+ * reference up to summation order.
  * block_idx: int32 [B, H, T_m, k], each row ascending.  With k = 0 nothing is written. */
 int sla2_router(const sla2_params* params, const void* q, const void* k, const float* router_w,
                 int32_t* block_idx, void* workspace, size_t workspace_bytes, void* hip_stream);
@@ -148,15 +149,13 @@ int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, 
  * HOST arrays (each SLA2_STAGE_COUNT long) and destroys the events.
  * Returns SLA2_OK, SLA2_EINVAL (bad arguments / begin without end) or SLA2_EHIP. */
 typedef enum {
-  SLA2_STAGE_BLOCK_SUMS = 0,  /* pooling sums of Q and K blocks            (Eq. 15) */
-  SLA2_STAGE_COL_MEAN = 1,    /* colmean(K)                                (Alg. 2, smoothing) */
-  SLA2_STAGE_PROJECT = 2,     /* proj_q, proj_k                            (Eq. 16) */
-  SLA2_STAGE_TOPK = 3,        /* scores + row-wise top-k                   (Eq. 16) */
-  SLA2_STAGE_KV_STATE = 4,    /* lnZ, partial h and z, FP8 codes of K      (Alg. 2: K^phi, h, z) */
-  SLA2_STAGE_KV_TOTAL = 5,    /* per-head totals of h and z */
-  SLA2_STAGE_ATTN = 6,        /* sparse + linear branch + mix              (Alg. 2 block loop, Eq. 13) */
-  SLA2_STAGE_DENSE = 7,       /* dense attention comparator */
-  SLA2_STAGE_COUNT = 8
+  SLA2_STAGE_BLOCK_SUMS = 0,  /* pooling sums of Q and K blocks; router weights folded   (Eq. 15-16) */
+  SLA2_STAGE_TOPK = 1,        /* projection, scores, row-wise top-k; colmean(K)   (Eq. 16; Alg. 2, smoothing) */
+  SLA2_STAGE_KV_STATE = 2,    /* K^phi, partial h and z, FP8 codes of K    (Alg. 2: K^phi, h, z) */
+  SLA2_STAGE_KV_TOTAL = 3,    /* per-head totals of h and z */
+  SLA2_STAGE_ATTN = 4,        /* sparse + linear branch + mix              (Alg. 2 block loop, Eq. 13) */
+  SLA2_STAGE_DENSE = 5,       /* dense attention comparator */
+  SLA2_STAGE_COUNT = 6
 } sla2_stage;
 int sla2_profile_begin(unsigned stage_mask, int max_calls);
 int sla2_profile_end(double* stage_ms, int* stage_launches);

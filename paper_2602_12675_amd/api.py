@@ -24,7 +24,7 @@ EXPORTS = ("sla2_workspace_bytes", "sla2_workspace_layout", "sla2_num_selected",
            "sla2_forward", "sla2_dense_forward", "sla2_profile_begin", "sla2_profile_end",
            "sla2_strerror", "sla2_version")
 
-STAGES = ("block_sums", "col_mean", "project", "topk", "kv_state", "kv_total", "attn", "dense")   # sla2_stage
+STAGES = ("block_sums", "topk", "kv_state", "kv_total", "attn", "dense")   # sla2_stage
 
 
 class Params(ctypes.Structure):
@@ -38,7 +38,7 @@ class Params(ctypes.Structure):
 class WsLayout(ctypes.Structure):
     """struct sla2_ws_layout"""
     _fields_ = [(n, ctypes.c_size_t) for n in
-                ("q_sum", "k_sum", "k_mean", "q_proj", "k_proj", "block_idx", "h_total", "z_total",
+                ("q_sum", "k_sum", "k_mean", "router_m", "block_idx", "h_total", "z_total",
                  "k_stats", "k_phi", "z_blocks", "k_fp8", "k_scale", "partial", "total")]
 
 

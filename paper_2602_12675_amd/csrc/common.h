@@ -46,12 +46,10 @@ __device__ __forceinline__ void store_elem(float* p, size_t i, float v) { p[i] =
 __device__ __forceinline__ void store_elem(uint16_t* p, size_t i, float v) { p[i] = f32_to_bf16_bits(v); }
 
 // ---- launchers (one per kernel file); all enqueue on `stream` and return hipGetLastError() ----
-hipError_t launch_block_sums(const Shape& s, const void* q, const void* k, double* q_sum, double* k_sum, hipStream_t stream);
-hipError_t launch_col_mean(const Shape& s, const double* k_sum, double* k_mean, hipStream_t stream);
-hipError_t launch_project(const Shape& s, const double* q_sum, const double* k_sum, const double* k_mean,
-                          const float* router_w, double* q_proj, double* k_proj, hipStream_t stream);
-hipError_t launch_router_topk(const Shape& s, const double* q_proj, const double* k_proj, int32_t* block_idx,
-                              hipStream_t stream);
+hipError_t launch_block_sums(const Shape& s, const void* q, const void* k, const float* router_w, double* q_sum,
+                             double* k_sum, double* router_m, hipStream_t stream);
+hipError_t launch_router_topk(const Shape& s, const double* q_sum, const double* k_sum, const double* router_m,
+                              int32_t* block_idx, double* k_mean, hipStream_t stream);
 hipError_t launch_kv_state_f32(const Shape& s, const float* k, const float* v, const double* k_mean, float* k_stats,
                                float* partial, hipStream_t stream);
 hipError_t launch_attn_f32(const Shape& s, const float* q, const float* k, const float* v, const double* k_mean,

@@ -72,9 +72,9 @@ __device__ __forceinline__ bf16x8 row_fragment(const uint16_t* tile, int row, in
 
 // One 64 x D bf16 tile, global memory -> LDS without passing through registers.  NW waves cooperate;
 // each global_load_lds_dwordx4 moves 1 KB (64 lanes x 16 bytes) into consecutive LDS bytes.
-// Completion is counted by vmcnt.  The swizzle of a row depends on row % 8 only and every
-// instruction of a wave starts at a multiple of 8 rows apart, so a lane's source offset is one
-// value plus a constant per instruction.  A ragged last tile (valid < 64) repeats its last row.
+// Completion is counted by vmcnt.  Rows past `valid` (ragged last tile) repeat the last row.  One
+// straight-line sequence for full and ragged tiles alike: the number of transfers in flight is then
+// the same on every path, which lets later waits be counted instead of draining everything.
 template <int D, int NW>
 __device__ __forceinline__ void dma_tile(const uint16_t* src /* first row */, int valid, uint16_t* tile, int w, int lane) {
   typedef SwizzledLayout<D> L;
@@ -82,20 +82,13 @@ __device__ __forceinline__ void dma_tile(const uint16_t* src /* first row */, in
   constexpr int kInstrs = kTileTokens / kRowsPerInstr / NW;
   static_assert((kRowsPerInstr * NW) % 8 == 0, "row swizzle must repeat between the instructions of a wave");
   const int row_w = w * kRowsPerInstr + lane / L::kChunks;           // row of instruction 0
-  const int chunk = (lane % L::kChunks) ^ L::swz(row_w);
-  if (valid == kTileTokens) {
-    const uint16_t* g = src + row_w * D + 8 * chunk;
+  const unsigned col_bytes = 16u * (unsigned)((lane % L::kChunks) ^ L::swz(row_w));
+  const char* base = reinterpret_cast<const char*>(src);
 #pragma unroll
-    for (int i = 0; i < kInstrs; i++)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + i * NW * kRowsPerInstr * D),
-                                       (__attribute__((address_space(3))) void*)(tile + (i * NW + w) * 512), 16, 0, 0);
-  } else {
-#pragma unroll
-    for (int i = 0; i < kInstrs; i++) {
-      const int row = min(row_w + i * NW * kRowsPerInstr, valid - 1);
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src + (size_t)row * D + 8 * chunk),
-                                       (__attribute__((address_space(3))) void*)(tile + (i * NW + w) * 512), 16, 0, 0);
-    }
+  for (int i = 0; i < kInstrs; i++) {
+    const unsigned off = (unsigned)min(row_w + i * NW * kRowsPerInstr, valid - 1) * (unsigned)(D * 2) + col_bytes;
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + off),
+                                     (__attribute__((address_space(3))) void*)(tile + (i * NW + w) * 512), 16, 0, 0);
   }
 }
 

@@ -53,8 +53,7 @@ static void make_layout(const Shape& s, sla2_ws_layout* L) {
   L->q_sum = take(BH * s.Tm * d * sizeof(double));
   L->k_sum = take(BH * s.Tn * d * sizeof(double));
   L->k_mean = take(BH * d * sizeof(double));
-  L->q_proj = take(BH * s.Tm * d * sizeof(double));
-  L->k_proj = take(BH * s.Tn * d * sizeof(double));
+  L->router_m = take((size_t)(s.w_per_head ? s.H : 1) * d * d * sizeof(double));
   L->block_idx = take(BH * s.Tm * (size_t)(s.k > 0 ? s.k : 1) * sizeof(int32_t));
   L->h_total = take(BH * d * d * sizeof(float));
   L->z_total = take(BH * d * sizeof(float));
@@ -114,19 +113,13 @@ static int run_router(const Shape& s, const sla2_ws_layout& L, const void* q, co
                       void* ws, hipStream_t st) {
   double* q_sum = at<double>(ws, L.q_sum);
   double* k_sum = at<double>(ws, L.k_sum);
-  double* k_mean = at<double>(ws, L.k_mean);
-  double* q_proj = at<double>(ws, L.q_proj);
-  double* k_proj = at<double>(ws, L.k_proj);
-  if (SLA2_STAGE(SLA2_STAGE_BLOCK_SUMS, launch_block_sums(s, q, k, q_sum, k_sum, st)) != hipSuccess) return SLA2_EHIP;
-  if (SLA2_STAGE(SLA2_STAGE_COL_MEAN, launch_col_mean(s, k_sum, k_mean, st)) != hipSuccess) return SLA2_EHIP;
-  if (s.k > 0) {
-    if (SLA2_STAGE(SLA2_STAGE_PROJECT, launch_project(s, q_sum, k_sum, k_mean, router_w, q_proj, k_proj, st)) !=
-        hipSuccess)
-      return SLA2_EHIP;
-    if (SLA2_STAGE(SLA2_STAGE_TOPK, launch_router_topk(s, q_proj, k_proj, at<int32_t>(ws, L.block_idx), st)) !=
-        hipSuccess)
-      return SLA2_EHIP;
-  }
+  double* router_m = at<double>(ws, L.router_m);
+  if (SLA2_STAGE(SLA2_STAGE_BLOCK_SUMS, launch_block_sums(s, q, k, router_w, q_sum, k_sum, router_m, st)) !=
+      hipSuccess)
+    return SLA2_EHIP;
+  if (SLA2_STAGE(SLA2_STAGE_TOPK, launch_router_topk(s, q_sum, k_sum, router_m, at<int32_t>(ws, L.block_idx),
+                                                     at<double>(ws, L.k_mean), st)) != hipSuccess)
+    return SLA2_EHIP;
   return SLA2_OK;
 }
 

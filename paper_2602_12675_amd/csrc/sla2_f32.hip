@@ -27,7 +27,10 @@ __global__ __launch_bounds__(256) void kv_state_f32_kernel(const float* __restri
   extern __shared__ float smem[];
   float* ks = smem;                 // [64][LD]  K' tile, then K^phi tile
   float* vs = smem + kBK * LD;      // [64][LD]  V tile
+  __shared__ float mu_s[D];
   const int bh = blockIdx.x / chunks, chunk = blockIdx.x % chunks;
+  if (threadIdx.x < D) mu_s[threadIdx.x] = (float)k_mean[(size_t)bh * D + threadIdx.x];
+  __syncthreads();
   const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
   const float* kh = k + (size_t)bh * N * D;
   const float* vh = v + (size_t)bh * N * D;
@@ -45,7 +48,7 @@ __global__ __launch_bounds__(256) void kv_state_f32_kernel(const float* __restri
     for (int idx = tid; idx < kBK * D; idx += 256) {
       int t = idx / D, c = idx % D;
       bool ok = t < valid;
-      ks[t * LD + c] = ok ? kh[(size_t)(t0 + t) * D + c] - (float)k_mean[(size_t)bh * D + c] : 0.f;
+      ks[t * LD + c] = ok ? kh[(size_t)(t0 + t) * D + c] - mu_s[c] : 0.f;
       vs[t * LD + c] = ok ? vh[(size_t)(t0 + t) * D + c] : 0.f;
     }
     __syncthreads();
@@ -92,23 +95,34 @@ __global__ __launch_bounds__(256) void kv_state_f32_kernel(const float* __restri
   if (tid < D) ph[D * D + tid] = zacc;
 }
 
-// totals over the chunks of a head, summed in chunk order (deterministic)
+// Totals over the chunks of a head (Alg. 2's sums of h_j and z_j over all key blocks).  Each workgroup
+// owns 64 entries; its 4 thread groups walk the chunks 4 apart and meet in LDS, always in the same
+// order, so the totals are the same bits on every run.
 __global__ __launch_bounds__(256) void kv_total_kernel(const float* __restrict__ partial, float* __restrict__ h_total,
                                                        float* __restrict__ z_total, int d, int chunks) {
+  __shared__ float red[256];
   const int per_head = d * d + d;
   const int bh = blockIdx.y;
-  const int e = blockIdx.x * 256 + threadIdx.x;
-  if (e >= per_head) return;
+  const int e = blockIdx.x * 64 + threadIdx.x % 64, cg = threadIdx.x / 64;
   float s = 0.f;
-  for (int c = 0; c < chunks; c++) s += partial[((size_t)bh * chunks + c) * per_head + e];
-  if (e < d * d) h_total[(size_t)bh * d * d + e] = s;
-  else z_total[(size_t)bh * d + (e - d * d)] = s;
+  if (e < per_head) {
+    const float* p = partial + (size_t)bh * chunks * per_head + e;
+#pragma unroll 4
+    for (int c = cg; c < chunks; c += 4) s += p[(size_t)c * per_head];
+  }
+  red[threadIdx.x] = s;
+  __syncthreads();
+  if (cg == 0 && e < per_head) {
+    const float tot = (red[threadIdx.x] + red[threadIdx.x + 64]) + (red[threadIdx.x + 128] + red[threadIdx.x + 192]);
+    if (e < d * d) h_total[(size_t)bh * d * d + e] = tot;
+    else z_total[(size_t)bh * d + (e - d * d)] = tot;
+  }
 }
 
 hipError_t launch_kv_total(const Shape& s, const float* partial, float* h_total, float* z_total, hipStream_t stream) {
   int per_head = s.d * s.d + s.d;
-  kv_total_kernel<<<dim3((unsigned)((per_head + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(partial, h_total,
-                                                                                               z_total, s.d, s.chunks);
+  kv_total_kernel<<<dim3((unsigned)((per_head + 63) / 64), (unsigned)s.BH), 256, 0, stream>>>(partial, h_total, z_total,
+                                                                                             s.d, s.chunks);
   return hipGetLastError();
 }
 

@@ -372,10 +372,10 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     const int valid = min(kTileTokens, N - j * kTileTokens);
     float sk = 1.f;
     if constexpr (FP8) sk = k_scale[blk0 + j];
-    if (s + 1 < ntiles) dma(s + 1, buf ^ 1);
-    const uint16_t* vt = vbuf(buf);
     // K^phi fragments and z_j of this tile straight from global memory into registers (no other
-    // wave needs them); they are consumed after the softmax
+    // wave needs them); they are consumed after the softmax.
+    // Issued before the next tile's transfer: vmcnt counts in order, so waiting for them later
+    // leaves that transfer in flight
     bf16x8 kphi[DENSE ? 1 : HS::kMtw][kTileTokens / 16];
     if constexpr (!DENSE) {
 #pragma unroll
@@ -387,6 +387,11 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       }
     }
 
+    // Next tile -> other buffer.  Unconditional (the last iteration re-fetches its own tile, an L2
+    // hit that nobody reads): a transfer that is issued on every path keeps the vmcnt distance to
+    // the K^phi loads above fixed, so the wait for those does not have to drain it.
+    dma(min(s + 1, ntiles - 1), buf ^ 1);
+    const uint16_t* vt = vbuf(buf);
     // ---- S^T = K Q^T (keys x query rows), two 32-key halves ----
     f32x16 sacc[2];
 #pragma unroll
@@ -507,6 +512,14 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
           l_run > 0.f ? (m_run - kPShift + __log2f(l_run)) * 0.6931471805599453f - qmu * rsqrtf((float)D) : -INFINITY;
   }
 
+  if constexpr (FP8) {
+    // the bf16 Q fragments were dropped after quantisation to keep two waves per SIMD; the linear
+    // branch needs them once more
+    const int r = min(32 * w + lane % 32, rows_valid - 1);
+    const uint16_t* src = qh + (size_t)(row0 + r) * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
+  }
   uint16_t* ht = reinterpret_cast<uint16_t*>(smem);  // H_i^T as bf16 [e][c], row stride LD
   uint16_t* os = ht + D * LD;                        // output tile [BQ][LD]
   f32x16 lacc[ET];

@@ -1,49 +1,86 @@
-// Pooling side of the learnable router (Sec. 4, Eq. 15-16 of the paper; pooling
-// and K-smoothing steps of Alg. 2): block sums of Q and K, colmean(K), and the
-// two d x d projections.  Everything is accumulated in fp64 so that the block
-// selection downstream agrees with an fp64 reference up to summation order.
+// Pooling side of the learnable router (Sec. 4, Eq. 15 of the paper; pooling step of Alg. 2): sums of
+// the rows of every query block and key block, accumulated in fp64 so that the block selection
+// downstream agrees with an fp64 reference up to summation order.
 //
-// block_sums is the bandwidth kernel of the three: it streams Q and K once
-// (16-byte loads, one workgroup per block) and is bound by HBM.
+// This is a bandwidth kernel: it streams Q and K once with 16-byte loads and is bound by HBM.
 #include "common.h"
 
 namespace sla2 {
 
-// ---------------------------------------------------------------------------------------------
-// block sums: out[bh][t][c] = sum over the rows of block t of x[bh][row][c]
-// One workgroup (256 threads) per block of Q or of K; each thread owns EPL consecutive
-// channels of one row per pass, partial sums meet in LDS in a fixed order.
-// ---------------------------------------------------------------------------------------------
 template <typename T> struct Vec16;
 template <> struct Vec16<uint16_t> {
   static constexpr int kElems = 8;
   __device__ static void load(const uint16_t* p, float (&f)[8]) {
-    uint4 u = *reinterpret_cast<const uint4*>(p);
-    uint32_t w[4] = {u.x, u.y, u.z, u.w};
+    u32x4 u = *reinterpret_cast<const u32x4*>(p);
 #pragma unroll
     for (int i = 0; i < 4; i++) {
-      f[2 * i] = __builtin_bit_cast(float, w[i] << 16);
-      f[2 * i + 1] = __builtin_bit_cast(float, w[i] & 0xFFFF0000u);
+      f[2 * i] = __builtin_bit_cast(float, u[i] << 16);
+      f[2 * i + 1] = __builtin_bit_cast(float, u[i] & 0xFFFF0000u);
     }
   }
 };
 template <> struct Vec16<float> {
   static constexpr int kElems = 4;
   __device__ static void load(const float* p, float (&f)[4]) {
-    float4 u = *reinterpret_cast<const float4*>(p);
-    f[0] = u.x; f[1] = u.y; f[2] = u.z; f[3] = u.w;
+    f32x4 u = *reinterpret_cast<const f32x4*>(p);
+    f[0] = u[0]; f[1] = u[1]; f[2] = u[2]; f[3] = u[3];
   }
 };
 
+// Row `a` of M = Wq Wk^T / sqrt(d):  M[a][c] = sum_n Wq[a][n] Wk[c][n] / sqrt(d)   (Eq. 16, both router
+// projections folded into one d x d matrix), fp64 throughout.  256 threads: thread (c, part) sums a
+// 1/(256/d) share of n for column c, with all of its loads in flight at once; shares meet in LDS.
+__device__ void fold_router_row(const float* __restrict__ Wq, const float* __restrict__ Wk, double* __restrict__ M,
+                                int d, int a, double* red /* LDS [256] */) {
+  const int c = threadIdx.x % d, part = threadIdx.x / d, parts = 256 / d;
+  const int n0 = part * (d / parts);
+  f32x4 wk[8], wq[8];                                  // d / parts / 4 = 16 (d = 128) or 4 (d = 64) groups of 4
+  double acc = 0.0;
+  for (int h = 0; h < d / parts / 4; h += 8) {
+#pragma unroll
+    for (int x = 0; x < 8; x++) {
+      const int n = n0 + 4 * (h + x);
+      const bool ok = h + x < d / parts / 4;
+      wk[x] = ok ? *reinterpret_cast<const f32x4*>(Wk + (size_t)c * d + n) : f32x4{0.f, 0.f, 0.f, 0.f};
+      wq[x] = ok ? *reinterpret_cast<const f32x4*>(Wq + (size_t)a * d + n) : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+#pragma unroll
+    for (int x = 0; x < 8; x++)
+#pragma unroll
+      for (int e = 0; e < 4; e++) acc += (double)wq[x][e] * (double)wk[x][e];
+  }
+  red[threadIdx.x] = acc;
+  __syncthreads();
+  if (threadIdx.x < d) {
+    double tot = 0.0;
+    for (int pi = 0; pi < parts; pi++) tot += red[pi * d + threadIdx.x];
+    M[(size_t)a * d + c] = tot / sqrt((double)d);
+  }
+}
+
+// One workgroup (256 threads) per block of Q or of K; each thread owns EPL consecutive channels of
+// one row per pass and has all of its 16-byte loads in flight at once; partial sums meet in LDS in a
+// fixed order.  Thousands of small workgroups keep enough bytes in flight to stream at HBM speed.
 template <typename T>
 __global__ __launch_bounds__(256) void block_sums_kernel(const T* __restrict__ q, const T* __restrict__ k,
                                                          double* __restrict__ q_sum, double* __restrict__ k_sum,
-                                                         int N, int d, int bq, int bk, int Tm, int Tn) {
+                                                         int N, int d, int bq, int bk, int Tm, int Tn, int fold_blocks,
+                                                         const float* __restrict__ router_w,
+                                                         double* __restrict__ router_m) {
   constexpr int EPL = Vec16<T>::kElems;
   __shared__ double red[2048];               // [row group][channel]: at most 32 groups x 64 ch or 16 x 128
+  if ((int)blockIdx.x < fold_blocks) {
+    // the first workgroups of this launch fold the router weights, one row of M each, for every weight
+    // pair; they finish long before the pooling workgroups behind them
+    const int pair = blockIdx.x / d, a = blockIdx.x % d;
+    const float* Wq = router_w + (size_t)pair * 2 * d * d;
+    fold_router_row(Wq, Wq + (size_t)d * d, router_m + (size_t)pair * d * d, d, a, red);
+    return;
+  }
+  const int pool_id = blockIdx.x - fold_blocks;
   const int per_head = Tm + Tn;
-  const int bh = blockIdx.x / per_head;
-  int t = blockIdx.x % per_head;
+  const int bh = pool_id / per_head;
+  int t = pool_id % per_head;
   const bool is_k = t >= Tm;
   if (is_k) t -= Tm;
   const int b = is_k ? bk : bq;
@@ -60,7 +97,7 @@ __global__ __launch_bounds__(256) void block_sums_kernel(const T* __restrict__ q
   double acc[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; e++) acc[e] = 0.0;
-#pragma unroll 4
+#pragma unroll 8
   for (int r = rg; r < rows; r += rpp) {
     float f[EPL];
     Vec16<T>::load(x + (size_t)(row0 + r) * d + col, f);
@@ -72,105 +109,21 @@ __global__ __launch_bounds__(256) void block_sums_kernel(const T* __restrict__ q
   __syncthreads();
   if (threadIdx.x < d) {
     double s = 0.0;
-    for (int g = 0; g < rpp; g++) s += red[g * d + threadIdx.x];
+    for (int gi = 0; gi < rpp; gi++) s += red[gi * d + threadIdx.x];
     out[threadIdx.x] = s;
   }
 }
 
-hipError_t launch_block_sums(const Shape& s, const void* q, const void* k, double* q_sum, double* k_sum,
-                             hipStream_t stream) {
-  dim3 grid((unsigned)(s.BH * (s.Tm + s.Tn)));
+hipError_t launch_block_sums(const Shape& s, const void* q, const void* k, const float* router_w, double* q_sum,
+                             double* k_sum, double* router_m, hipStream_t stream) {
+  const int fold_blocks = (s.w_per_head ? s.H : 1) * s.d;
+  dim3 grid((unsigned)(s.BH * (s.Tm + s.Tn) + fold_blocks));
   if (s.bf16)
     block_sums_kernel<uint16_t><<<grid, 256, 0, stream>>>((const uint16_t*)q, (const uint16_t*)k, q_sum, k_sum, s.N,
-                                                           s.d, s.bq, s.bk, s.Tm, s.Tn);
+                                                           s.d, s.bq, s.bk, s.Tm, s.Tn, fold_blocks, router_w, router_m);
   else
     block_sums_kernel<float><<<grid, 256, 0, stream>>>((const float*)q, (const float*)k, q_sum, k_sum, s.N, s.d, s.bq,
-                                                        s.bk, s.Tm, s.Tn);
-  return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------------------------
-// colmean(K) = (sum over blocks of the block sums) / N          (K-smoothing step of Alg. 2)
-// One workgroup per head.  With smoothing disabled the mean is written as zero so that
-// every consumer can subtract it unconditionally.
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(1024) void col_mean_kernel(const double* __restrict__ k_sum, double* __restrict__ k_mean,
-                                                        int N, int d, int Tn, int smooth) {
-  __shared__ double red[1024];
-  const int bh = blockIdx.x;
-  const int c = threadIdx.x % d, g = threadIdx.x / d, G = 1024 / d;
-  double s = 0.0;
-  if (smooth)
-    for (int j = g; j < Tn; j += G) s += k_sum[((size_t)bh * Tn + j) * d + c];
-  red[threadIdx.x] = s;
-  __syncthreads();
-  if (threadIdx.x < d) {
-    double tot = 0.0;
-    for (int gg = 0; gg < G; gg++) tot += red[gg * d + threadIdx.x];
-    k_mean[(size_t)bh * d + threadIdx.x] = tot / (double)N;
-  }
-}
-
-hipError_t launch_col_mean(const Shape& s, const double* k_sum, double* k_mean, hipStream_t stream) {
-  col_mean_kernel<<<dim3((unsigned)s.BH), 1024, 0, stream>>>(k_sum, k_mean, s.N, s.d, s.Tn, s.smooth ? 1 : 0);
-  return hipGetLastError();
-}
-
-// ---------------------------------------------------------------------------------------------
-// projections: q_proj = (q_sum / rows) Wq / sqrt(d),  k_proj = (k_sum / rows - colmean K) Wk    (Eq. 16)
-// One workgroup of d threads per 16 pooled rows; thread c owns output channel c.
-// W is [d_in, d_out] row-major, so the threads of a wave read consecutive floats of one W row.
-// ---------------------------------------------------------------------------------------------
-constexpr int kProjRows = 16;
-
-__global__ __launch_bounds__(128) void project_kernel(const double* __restrict__ q_sum, const double* __restrict__ k_sum,
-                                                      const double* __restrict__ k_mean,
-                                                      const float* __restrict__ router_w, double* __restrict__ q_proj,
-                                                      double* __restrict__ k_proj, int N, int d, int bq, int bk, int Tm,
-                                                      int Tn, int H, int w_per_head) {
-  __shared__ double x[kProjRows][128];
-  const int tiles_q = (Tm + kProjRows - 1) / kProjRows, tiles_k = (Tn + kProjRows - 1) / kProjRows;
-  const int per_head = tiles_q + tiles_k;
-  const int bh = blockIdx.x / per_head;
-  int tile = blockIdx.x % per_head;
-  const bool is_k = tile >= tiles_q;
-  if (is_k) tile -= tiles_q;
-  const int T = is_k ? Tn : Tm, b = is_k ? bk : bq;
-  const double* src = (is_k ? k_sum : q_sum) + (size_t)bh * T * d;
-  double* dst = (is_k ? k_proj : q_proj) + (size_t)bh * T * d;
-  const float* W = router_w + (w_per_head ? (size_t)(bh % H) * 2 * d * d : 0) + (is_k ? (size_t)d * d : 0);
-  const int c = threadIdx.x;
-  const int r0 = tile * kProjRows;
-  const double mu = is_k ? k_mean[(size_t)bh * d + c] : 0.0;
-  for (int r = 0; r < kProjRows; r++) {
-    int row = r0 + r;
-    double v = 0.0;
-    if (row < T) {
-      int rows = min(b, N - row * b);
-      v = src[(size_t)row * d + c] / (double)rows - mu;
-    }
-    x[r][c] = v;
-  }
-  __syncthreads();
-  double acc[kProjRows];
-#pragma unroll
-  for (int r = 0; r < kProjRows; r++) acc[r] = 0.0;
-  for (int e = 0; e < d; e++) {
-    double w = (double)W[(size_t)e * d + c];
-#pragma unroll
-    for (int r = 0; r < kProjRows; r++) acc[r] += x[r][e] * w;
-  }
-  const double scale = is_k ? 1.0 : 1.0 / sqrt((double)d);
-  for (int r = 0; r < kProjRows; r++)
-    if (r0 + r < T) dst[(size_t)(r0 + r) * d + c] = acc[r] * scale;
-}
-
-hipError_t launch_project(const Shape& s, const double* q_sum, const double* k_sum, const double* k_mean,
-                          const float* router_w, double* q_proj, double* k_proj, hipStream_t stream) {
-  int tiles = (s.Tm + kProjRows - 1) / kProjRows + (s.Tn + kProjRows - 1) / kProjRows;
-  project_kernel<<<dim3((unsigned)(s.BH * tiles)), s.d, 0, stream>>>(q_sum, k_sum, k_mean, router_w, q_proj, k_proj,
-                                                                     s.N, s.d, s.bq, s.bk, s.Tm, s.Tn, s.H,
-                                                                     s.w_per_head ? 1 : 0);
+                                                        s.bk, s.Tm, s.Tn, fold_blocks, router_w, router_m);
   return hipGetLastError();
 }
 

@@ -1,23 +1,35 @@
-// Router scores and row-wise top-k (Sec. 4, Eq. 16 of the paper; router step of Alg. 2).
+// Learnable router: projections, scores and row-wise top-k (Sec. 4, Eq. 16 of the paper; router step of
+// Alg. 2), all in fp64 so that the selection agrees with an fp64 reference up to summation order.
 //
-//   R[i][j] = q_proj[i] . k_proj[j]          (the 1/sqrt(d) is already folded into q_proj)
+//   R[i][j] = proj_q(Qbar_i) . proj_k(Kbar_j) / sqrt(d),   proj(x) = x W
 //   row i keeps its k largest R[i][j]; equal scores go to the lower j; indices come out ascending.
 //
-// One workgroup of 16 waves handles 16 query blocks of one head.  Scores are formed in fp64 on
-// the matrix cores (v_mfma_f64_16x16x4) 256 key blocks at a time: wave w multiplies the 16 x d
-// tile of q_proj with key blocks [256 r + 16 w, +16), parks its 16 x 16 result in LDS, and wave i
-// then picks up row i, so that after the last round every wave holds one complete score row in
-// registers (4 values per lane and round).  The selection is a most-significant-bit-first
-// search for the k-th largest key on order-preserving 64-bit integer images of the scores:
-// counting is a compare plus a scalar popcount of the lane mask, there is no sorting and no
-// atomics, and the result does not depend on timing.  Scores never touch HBM.
+// Two identities keep the work small.  (1) R = (Qbar M) Kbar^T with M = Wq Wk^T / sqrt(d), a d x d
+// matrix formed once per call (fold_router_weights, run by spare workgroups of the pooling launch):
+// only the 16 query rows of a workgroup are projected, the pooled keys are used as they are.  (2) Kbar is pooled from
+// K - colmean(K), which shifts every score of a row by the same amount, (Qbar Wq Wk^T) . colmean(K):
+// a row-wise top-k does not see it, so the raw block sums of K are scored and the mean never enters.
+// The scores formed here therefore differ from R by one constant per row.
+//
+// One workgroup of 16 waves handles 16 query blocks of one head.  Scores are formed on the matrix cores
+// (v_mfma_f64_16x16x4) 256 key blocks at a time: wave w multiplies the projected 16 x d tile with key
+// blocks [256 r + 16 w, +16), parks its 16 x 16 result in LDS, and wave i then picks up row i, so that
+// after the last round every wave holds one complete score row in registers (4 values per lane and
+// round).  The selection is a most-significant-bit-first search for the k-th largest key on
+// order-preserving 64-bit integer images of the scores: counting is a compare plus a scalar popcount
+// of the lane mask, there is no sorting and no atomics, and the result does not depend on timing.
+// Scores never touch HBM.
 #include "common.h"
+
+// Phase markers for timing experiments; compiled out unless a harness defines them.
+#ifndef SLA2_PHASE_MARK
+#define SLA2_PHASE_MARK(i)
+#endif
 
 namespace sla2 {
 
 constexpr int kRouterRows = 16;                       // query blocks per workgroup = waves per workgroup
 constexpr int kColsPerRound = 256;                    // key blocks scored per round (16 waves x 16)
-constexpr int kMaxSlots = kMaxKeyBlocks / kWave;      // score slots per lane
 
 // monotone map double -> uint64: a < b  <=>  key(a) < key(b); every real score maps above 0
 __device__ __forceinline__ uint64_t order_key(double x) {
@@ -27,32 +39,98 @@ __device__ __forceinline__ uint64_t order_key(double x) {
 
 __device__ __forceinline__ int wave_count(bool pred) { return __builtin_popcountll(__ballot(pred)); }
 
+// C[16][D] = A[16][D] M on the matrix cores, M fp64 [D][D] row-major in global memory.  All 16 waves
+// work: wave w forms columns [16 (w % (D/16)), +16) over a 1/(16 / (D/16)) share of the contraction
+// range; the shares are written side by side (C has room for kShares copies) and added by the reader.
+template <int D> struct ProjGeom {
+  static constexpr int kNt = D / 16;                 // column tiles
+  static constexpr int kShares = 16 / kNt;           // waves per column tile: 2 (D = 128) or 4 (D = 64)
+  static constexpr int kSteps = D / 4 / kShares;     // 4-wide contraction steps per wave
+};
 template <int D>
-__global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restrict__ q_proj,
-                                                           const double* __restrict__ k_proj,
-                                                           int32_t* __restrict__ block_idx, int Tm, int Tn, int k) {
-  __shared__ double qp[kRouterRows][D + 2];            // +2: rows land in different banks
-  __shared__ double tile[kRouterRows][kColsPerRound + 2];
+__device__ __forceinline__ void project16(const double (*A)[D + 2], double (*C)[D + 2] /* [kShares*16][D+2] */,
+                                          const double* __restrict__ M, int wave, int lane) {
+  typedef ProjGeom<D> G;
+  const int nt = wave % G::kNt, share = wave / G::kNt;
+  const int n = 16 * nt + lane % 16;
+  double b[G::kSteps];
+#pragma unroll
+  for (int i = 0; i < G::kSteps; i++) b[i] = M[(size_t)(4 * (share * G::kSteps + i) + lane / 16) * D + n];
+  f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+  for (int i = 0; i < G::kSteps; i++)
+    acc = __builtin_amdgcn_mfma_f64_16x16x4f64(A[lane % 16][4 * (share * G::kSteps + i) + lane / 16], b[i], acc, 0, 0, 0);
+#pragma unroll
+  for (int v = 0; v < 4; v++) C[share * 16 + lane / 16 + 4 * v][n] = acc[v];
+}
+
+template <int D, int SLOTS>
+__global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restrict__ q_sum,
+                                                           const double* __restrict__ k_sum,
+                                                           const double* __restrict__ router_m,
+                                                           int32_t* __restrict__ block_idx,
+                                                           double* __restrict__ k_mean, int H, int N, int bq, int bk,
+                                                           int Tm, int Tn, int k, int w_per_head, int topk_blocks,
+                                                           int smooth) {
+  __shared__ double xa[kRouterRows][D + 2];            // pooled queries, later Qbar M
+  __shared__ double tile[kRouterRows][kColsPerRound + 8];
+  static_assert(ProjGeom<D>::kShares * (D + 2) <= kColsPerRound + 8, "projection shares must fit the score tile");
+  double (*xb)[D + 2] = reinterpret_cast<double (*)[D + 2]>(&tile[0][0]);   // partial Qbar M; dead before the first round
+  if ((int)blockIdx.x >= topk_blocks) {
+    // Spare workgroups of this launch form colmean(K) (K-smoothing step of Alg. 2) from the block sums
+    // for the kernels that follow; the router itself does not need it.  16 channels per workgroup,
+    // 64 row groups, fixed summation order.  With smoothing disabled the mean is written as zero.
+    double* red = &tile[0][0];
+    const int job = blockIdx.x - topk_blocks, bh = job / (D / 16), c = 16 * (job % (D / 16)) + threadIdx.x % 16;
+    const int g = threadIdx.x / 16;
+    double s = 0.0;
+    if (smooth)
+      for (int j = g; j < Tn; j += 64) s += k_sum[((size_t)bh * Tn + j) * D + c];
+    red[threadIdx.x] = s;
+    __syncthreads();
+    if (threadIdx.x < 16) {
+      double tot = 0.0;
+      for (int gi = 0; gi < 64; gi++) tot += red[gi * 16 + threadIdx.x];
+      k_mean[(size_t)bh * D + c] = tot / (double)N;
+    }
+    return;
+  }
   const int row_tiles = (Tm + kRouterRows - 1) / kRouterRows;
   const int bh = blockIdx.x / row_tiles;
   const int row0 = (blockIdx.x % row_tiles) * kRouterRows;
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const double* M = router_m + (w_per_head ? (size_t)(bh % H) * D * D : 0);
 
+  SLA2_PHASE_MARK(0)
   for (int e = threadIdx.x; e < kRouterRows * D; e += 1024) {
-    int r = e / D, c = e % D;
-    int row = min(row0 + r, Tm - 1);                   // rows past the end repeat the last one; never stored
-    qp[r][c] = q_proj[((size_t)bh * Tm + row) * D + c];
+    const int r = e / D, c = e % D;
+    const int row = min(row0 + r, Tm - 1);             // rows past the end repeat the last one; never stored
+    const int rows = min(bq, N - row * bq);
+    xa[r][c] = q_sum[((size_t)bh * Tm + row) * D + c] / (double)rows;     // mean pooling (Eq. 15)
+  }
+  __syncthreads();
+  SLA2_PHASE_MARK(1)
+  project16<D>(xa, xb, M, wave, lane);                                    // Qbar (Wq Wk^T / sqrt(d)), in shares
+  __syncthreads();
+  for (int e = threadIdx.x; e < kRouterRows * D; e += 1024) {
+    const int r = e / D, c = e % D;
+    double v = xb[r][c];
+#pragma unroll
+    for (int sh = 1; sh < ProjGeom<D>::kShares; sh++) v += xb[sh * 16 + r][c];
+    xa[r][c] = v;
   }
   __syncthreads();
 
-  uint64_t key[kMaxSlots];
+  SLA2_PHASE_MARK(2)
+  uint64_t key[SLOTS];
 #pragma unroll
-  for (int s = 0; s < kMaxSlots; s++) key[s] = 0;
+  for (int s = 0; s < SLOTS; s++) key[s] = 0;
 
   const int rounds = (Tn + kColsPerRound - 1) / kColsPerRound;
-  const double* kp = k_proj + (size_t)bh * Tn * D;
+  const double* ks = k_sum + (size_t)bh * Tn * D;
+  const double last_cnt = (double)(N - (Tn - 1) * bk);
 #pragma unroll
-  for (int r = 0; r < kMaxSlots / 4; r++) {
+  for (int r = 0; r < SLOTS / 4; r++) {
     if (r < rounds) {
       // --- scores of 16 rows x 16 key blocks on this wave ---
       const int col0 = r * kColsPerRound + wave * 16;
@@ -60,87 +138,133 @@ __global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restr
       if (col0 < Tn) {
         // operand layout of v_mfma_f64_16x16x4: lane l feeds A[l%16][l/16] and B[l/16][l%16]
         const int jrow = min(col0 + lane % 16, Tn - 1);
-        const double* kb = kp + (size_t)jrow * D + lane / 16;
-        const double* qa = &qp[lane % 16][lane / 16];
-#pragma unroll 8
-        for (int kk = 0; kk < D / 4; kk++)
-          acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qa[4 * kk], kb[4 * kk], acc, 0, 0, 0);
+        const double* kb = ks + (size_t)jrow * D + lane / 16;
+        const double* qa = &xa[lane % 16][lane / 16];
+        // 16 operand loads in flight at a time: the loop is bound by their latency, not by the MFMAs
+#pragma unroll
+        for (int c16 = 0; c16 < D / 64; c16++) {
+          double b[16];
+#pragma unroll
+          for (int x = 0; x < 16; x++) b[x] = kb[4 * (16 * c16 + x)];
+#pragma unroll
+          for (int x = 0; x < 16; x++)
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qa[4 * (16 * c16 + x)], b[x], acc, 0, 0, 0);
+        }
       }
       // result layout: lane l, register v holds C[l/16 + 4 v][l%16]
 #pragma unroll
       for (int v = 0; v < 4; v++) tile[lane / 16 + 4 * v][wave * 16 + lane % 16] = acc[v];
       __syncthreads();
-      // --- wave i collects row i ---
+      // --- wave i collects row i; block sums -> block means (only a ragged last block differs) ---
 #pragma unroll
       for (int qd = 0; qd < 4; qd++) {
-        int col = r * kColsPerRound + qd * kWave + lane;
-        double sc = tile[wave][qd * kWave + lane] + 0.0;   // -0 -> +0: zeros tie
+        const int col = r * kColsPerRound + qd * kWave + lane;
+        double sc = tile[wave][qd * kWave + lane] / (col == Tn - 1 ? last_cnt : (double)bk);
+        sc += 0.0;                                     // -0 -> +0: zeros tie
         key[4 * r + qd] = col < Tn ? order_key(sc) : 0ull;
       }
       __syncthreads();
     }
   }
 
+  SLA2_PHASE_MARK(3)
   const int row = row0 + wave;
   if (row >= Tm || k <= 0) return;
   const int slots = rounds * 4;
   int32_t* out = block_idx + ((size_t)bh * Tm + row) * k;
 
-  // k-th largest key, most significant bit first.  Invariant: count(key >= thr) >= k.
-  uint64_t thr = 0;
-  bool exact = false;                                  // true: {key >= thr} has exactly k members
-  for (int bit = 63; bit >= 0; bit--) {
-    uint64_t cand = thr | (1ull << bit);
+  // k-th largest key thr, most significant bit first, on 32-bit halves (32-bit compares run at full
+  // rate).  Invariant of either search: at least `need` candidates are >= the current threshold.
+  // `exact` is set as soon as {key >= thr} has exactly k members - no ties to resolve then.
+  uint32_t hi[SLOTS], lo[SLOTS];
+#pragma unroll
+  for (int s = 0; s < SLOTS; s++) { hi[s] = (uint32_t)(key[s] >> 32); lo[s] = (uint32_t)key[s]; }
+  uint32_t thr_hi = 0;
+  bool exact = false;
+  for (int bit = 31; bit >= 0; bit--) {
+    const uint32_t cand = thr_hi | (1u << bit);
     int cnt = 0;
 #pragma unroll
-    for (int s = 0; s < kMaxSlots; s++)
-      if (s < slots) cnt += wave_count(key[s] >= cand);
+    for (int s = 0; s < SLOTS; s++) cnt += wave_count(hi[s] >= cand);      // unused slots hold 0 < cand
     if (cnt >= k) {
-      thr = cand;
+      thr_hi = cand;
       if (cnt == k) { exact = true; break; }
     }
   }
+  uint32_t thr_lo = 0;
+  if (!exact) {
+    // thr_hi is the high word of the k-th largest key; the keys above it in the high word are in,
+    // `need` more come from those that share it, ranked by their low words
+    int gt = 0, eq = 0;
+#pragma unroll
+    for (int s = 0; s < SLOTS; s++) { gt += wave_count(hi[s] > thr_hi); eq += wave_count(hi[s] == thr_hi); }
+    const int need = k - gt;
+    if (eq == need) {
+      exact = true;                                    // all of them: {key >= (thr_hi, 0)} is the answer
+    } else {
+      for (int bit = 31; bit >= 0; bit--) {
+        const uint32_t cand = thr_lo | (1u << bit);
+        int cnt = 0;
+#pragma unroll
+        for (int s = 0; s < SLOTS; s++) cnt += wave_count(hi[s] == thr_hi && lo[s] >= cand);
+        if (cnt >= need) {
+          thr_lo = cand;
+          if (cnt == need) { exact = true; break; }
+        }
+      }
+    }
+  }
+  const uint64_t thr = ((uint64_t)thr_hi << 32) | thr_lo;
   // not exact: thr is the k-th largest key itself and several keys equal it; those above it
   // are all kept, the equal ones are kept in ascending column order until k are taken.
   int need_eq = 0;
   if (!exact) {
     int gt = 0;
 #pragma unroll
-    for (int s = 0; s < kMaxSlots; s++)
-      if (s < slots) gt += wave_count(key[s] > thr);
+    for (int s = 0; s < SLOTS; s++) gt += wave_count(key[s] > thr);
     need_eq = k - gt;
   }
+  SLA2_PHASE_MARK(4)
   const uint64_t lane_lt = (1ull << lane) - 1ull;
   int written = 0;
 #pragma unroll
-  for (int s = 0; s < kMaxSlots; s++) {
+  for (int s = 0; s < SLOTS; s++) {
     if (s < slots) {
       bool keep;
       if (exact) {
         keep = key[s] >= thr;
       } else {
-        bool eq = key[s] == thr;
-        uint64_t eq_mask = __ballot(eq);
-        int my_rank = __builtin_popcountll(eq_mask & lane_lt);
+        const bool eq = key[s] == thr;
+        const uint64_t eq_mask = __ballot(eq);
+        const int my_rank = __builtin_popcountll(eq_mask & lane_lt);
         keep = key[s] > thr || (eq && my_rank < need_eq);
-        int taken = __builtin_popcountll(eq_mask);
+        const int taken = __builtin_popcountll(eq_mask);
         need_eq -= taken < need_eq ? taken : need_eq;
       }
-      uint64_t m = __ballot(keep);
+      const uint64_t m = __ballot(keep);
       if (keep) out[written + __builtin_popcountll(m & lane_lt)] = s * kWave + lane;
       written += __builtin_popcountll(m);
     }
   }
+  SLA2_PHASE_MARK(5)
 }
 
-hipError_t launch_router_topk(const Shape& s, const double* q_proj, const double* k_proj, int32_t* block_idx,
-                              hipStream_t stream) {
-  int row_tiles = (s.Tm + kRouterRows - 1) / kRouterRows;
-  dim3 grid((unsigned)(s.BH * row_tiles));
-  if (s.d == 128)
-    router_topk_kernel<128><<<grid, 1024, 0, stream>>>(q_proj, k_proj, block_idx, s.Tm, s.Tn, s.k);
-  else
-    router_topk_kernel<64><<<grid, 1024, 0, stream>>>(q_proj, k_proj, block_idx, s.Tm, s.Tn, s.k);
+hipError_t launch_router_topk(const Shape& s, const double* q_sum, const double* k_sum, const double* router_m,
+                              int32_t* block_idx, double* k_mean, hipStream_t stream) {
+  const int row_tiles = (s.Tm + kRouterRows - 1) / kRouterRows;
+  const int topk_blocks = s.k > 0 ? s.BH * row_tiles : 0;        // k = 0: only the colmean workgroups run
+  dim3 grid((unsigned)(topk_blocks + s.BH * (s.d / 16)));
+  const int rounds = (s.Tn + kColsPerRound - 1) / kColsPerRound;     // <= 8 (kMaxKeyBlocks)
+#define SLA2_TOPK(DD, SS)                                                                                       \
+  router_topk_kernel<DD, SS><<<grid, 1024, 0, stream>>>(q_sum, k_sum, router_m, block_idx, k_mean, s.H, s.N, s.bq, \
+                                                        s.bk, s.Tm, s.Tn, s.k, s.w_per_head ? 1 : 0, topk_blocks,    \
+                                                        s.smooth ? 1 : 0)
+  if (s.d == 128) {
+    if (rounds <= 2) SLA2_TOPK(128, 8); else if (rounds <= 4) SLA2_TOPK(128, 16); else SLA2_TOPK(128, 32);
+  } else {
+    if (rounds <= 2) SLA2_TOPK(64, 8); else if (rounds <= 4) SLA2_TOPK(64, 16); else SLA2_TOPK(64, 32);
+  }
+#undef SLA2_TOPK
   return hipGetLastError();
 }
 

@@ -36,10 +36,12 @@ def test_forward_bf16_matches_oracle(w):
     BH = w.B * w.H
     h_total = api.workspace_view(r["ws"], L.h_total, torch.float32, (BH, w.d, w.d)).cpu().numpy()
     z_total = api.workspace_view(r["ws"], L.z_total, torch.float32, (BH, w.d)).cpu().numpy()
+    k_mean = api.workspace_view(r["ws"], L.k_mean, torch.float64, (BH, w.d)).cpu().numpy()
     lnz = api.workspace_view(r["ws"], L.k_stats, torch.float32, (BH, w.N)).cpu().numpy()
     for (b, h), o in ref.items():
         bh = b * w.H + h
         assert check_mask(r["idx"][b, h], o["R"], o["sel"]) == 0
+        np.testing.assert_allclose(k_mean[b * w.H + h], inp.values("k", b, h).mean(axis=0), rtol=1e-11, atol=1e-14)
         Ks = O.smooth_k(inp.values("k", b, h))
         ref_lnz = np.log(np.exp(Ks - Ks.max(axis=1, keepdims=True)).sum(axis=1)) + Ks.max(axis=1)
         np.testing.assert_allclose(lnz[bh], ref_lnz, rtol=0, atol=1e-4)

@@ -32,8 +32,10 @@ def test_forward_f32_matches_oracle(w):
     BH = w.B * w.H
     h_total = api.workspace_view(r["ws"], L.h_total, torch.float32, (BH, w.d, w.d)).cpu().numpy()
     z_total = api.workspace_view(r["ws"], L.z_total, torch.float32, (BH, w.d)).cpu().numpy()
+    k_mean = api.workspace_view(r["ws"], L.k_mean, torch.float64, (BH, w.d)).cpu().numpy()
     for (b, h), o in ref.items():
         assert check_mask(r["idx"][b, h], o["R"], o["sel"]) == 0
+        np.testing.assert_allclose(k_mean[b * w.H + h], inp.values("k", b, h).mean(axis=0), rtol=1e-11, atol=1e-14)
         # totals of h_j, z_j (complement identity: H_i + sum of selected = total)
         Ks = O.smooth_k(inp.values("k", b, h))
         hj, zj = O.kv_state(O.phi(Ks), inp.values("v", b, h), w.block_kv)
