@@ -40,7 +40,24 @@ def parse():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=6, help="heads of the workload the oracle is timed on")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 256 MiB device copy (for scaling FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     return ap.parse_args()
+
+
+def measured_traffic(workload, quant):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (profiles/attn_mfma_traffic.txt: lines `workload quant bytes`), or None."""
+    path = os.path.join(ROOT, "profiles", "attn_mfma_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 3 and not line.startswith("#") and parts[0] == workload and parts[1] == quant:
+                    return float(parts[2])
+    except OSError:
+        pass
+    return None
 
 
 def cpu_baseline(inp, heads):
@@ -103,6 +120,13 @@ def main():
         q, k, v, out = sets[i % len(sets)]
         api.sla2_forward(p, q, k, v, rw, al, out, workspace=ws, stream=stream)
 
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
@@ -134,7 +158,7 @@ def main():
     achieved = attn_flops / (attn_ms * 1e-3) / 1e12
     roofline = {"kernel": "attn_mfma (sparse + linear branch + mix)", "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS["bf16"], 4),
-                "traffic": None, "ms": round(attn_ms, 4),
+                "traffic": measured_traffic(w.name, w.quant), "ms": round(attn_ms, 4),
                 "algorithmic_flops": attn_flops,
                 "note": "peak = dense bf16 MFMA; P V and the linear branch run in bf16 (in fp8 mode only Q K^T is fp8)"}
     qk_bytes = 2.0 * BH * w.N * w.d * esz
