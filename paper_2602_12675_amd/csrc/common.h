@@ -6,6 +6,11 @@
 
 #include "../../include/sla2.h"
 
+// Phase markers for timing experiments; compiled out unless a harness defines them.
+#ifndef SLA2_PHASE_MARK
+#define SLA2_PHASE_MARK(i)
+#endif
+
 namespace sla2 {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;

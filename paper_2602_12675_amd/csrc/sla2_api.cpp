@@ -37,11 +37,15 @@ static int make_shape(const sla2_params* p, Shape* s) {
   s->smooth = !(p->flags & SLA2_FLAG_NO_SMOOTH_K);
   s->w_per_head = p->router_w_per_head != 0;
   s->alpha_per_block = p->alpha_per_block != 0;
-  // key blocks per kv-precompute workgroup: aim at ~512 workgroups, at most 32 blocks each
-  long long total_blocks = (long long)s->BH * s->Tn;
-  int bpc = (int)((total_blocks + 511) / 512);
+  // Key blocks per kv-precompute workgroup.  That kernel keeps 2 workgroups resident per CU (its
+  // d x d accumulator costs registers), 512 on the 256 CUs of an MI355X; one workgroup more than that
+  // would wait for a free slot and double the kernel's time, so the head's blocks are cut into the
+  // largest number of chunks that still fits in one resident set.
+  const int kResident = 512;
+  int chunks_max = kResident / s->BH;
+  if (chunks_max < 1) chunks_max = 1;
+  int bpc = (s->Tn + chunks_max - 1) / chunks_max;
   if (bpc < 1) bpc = 1;
-  if (bpc > 32) bpc = 32;
   s->blocks_per_chunk = bpc;
   s->chunks = (s->Tn + bpc - 1) / bpc;
   return SLA2_OK;

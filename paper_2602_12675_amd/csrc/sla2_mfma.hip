@@ -100,6 +100,7 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
   }
   for (int j = j0; j < j1; j++) {
     const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
+    SLA2_PHASE_MARK(0)
     __syncthreads();                                   // previous tile fully consumed
     TC::store(kr, ktile, tid);
     TC::store(vr, vtile, tid);
@@ -109,6 +110,7 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
       TC::load(vr, vh + (size_t)(j + 1) * kTileTokens * D, nvalid, tid);
     }
     __syncthreads();
+    SLA2_PHASE_MARK(1)
     {  // per-token log-partition of softmax_d(k'), 4 threads per token
       const int t = tid / 4, sub = tid % 4;
       float x[D / 4];
@@ -168,6 +170,7 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
       }
     }
     __syncthreads();
+    SLA2_PHASE_MARK(2)
     // K^phi fragments (kept for the attention kernel), h += K^phi^T V on the matrix cores, z_j
     float zsum[HS::kMtw];
 #pragma unroll
@@ -194,6 +197,7 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
       zacc[a] += z;
       if (g == 0 && nt0 == 0) z_blocks[((size_t)bh * Tn + j) * D + 32 * (mt0 + a) + lane] = z;
     }
+    SLA2_PHASE_MARK(3)
   }
   float* ph = partial + (size_t)blockIdx.x * (D * D + D);
 #pragma unroll
@@ -387,10 +391,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       }
     }
 
-    // Next tile -> other buffer.  Unconditional (the last iteration re-fetches its own tile, an L2
-    // hit that nobody reads): a transfer that is issued on every path keeps the vmcnt distance to
-    // the K^phi loads above fixed, so the wait for those does not have to drain it.
-    dma(min(s + 1, ntiles - 1), buf ^ 1);
+    if (s + 1 < ntiles) dma(s + 1, buf ^ 1);         // next tile -> other buffer
     const uint16_t* vt = vbuf(buf);
     // ---- S^T = K Q^T (keys x query rows), two 32-key halves ----
     f32x16 sacc[2];

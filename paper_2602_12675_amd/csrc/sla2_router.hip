@@ -21,15 +21,15 @@
 // Scores never touch HBM.
 #include "common.h"
 
-// Phase markers for timing experiments; compiled out unless a harness defines them.
-#ifndef SLA2_PHASE_MARK
-#define SLA2_PHASE_MARK(i)
-#endif
-
 namespace sla2 {
 
 constexpr int kRouterRows = 16;                       // query blocks per workgroup = waves per workgroup
 constexpr int kColsPerRound = 256;                    // key blocks scored per round (16 waves x 16)
+constexpr int kStageK = 32;                           // contraction indices per staged operand chunk
+constexpr int kStageLd = kStageK + 2;                 // padded row of a staged chunk (doubles)
+template <int D> constexpr size_t router_lds_bytes() {
+  return sizeof(double) * (kRouterRows * (D + 2) + kRouterRows * (kColsPerRound + 8) + 16 * 16 * kStageLd);
+}
 
 // monotone map double -> uint64: a < b  <=>  key(a) < key(b); every real score maps above 0
 __device__ __forceinline__ uint64_t order_key(double x) {
@@ -48,14 +48,19 @@ template <int D> struct ProjGeom {
   static constexpr int kSteps = D / 4 / kShares;     // 4-wide contraction steps per wave
 };
 template <int D>
+__device__ __forceinline__ void project16_fetch(double (&b)[ProjGeom<D>::kSteps], const double* __restrict__ M, int wave,
+                                                int lane) {
+  typedef ProjGeom<D> G;
+  const int n = 16 * (wave % G::kNt) + lane % 16, share = wave / G::kNt;
+#pragma unroll
+  for (int i = 0; i < G::kSteps; i++) b[i] = M[(size_t)(4 * (share * G::kSteps + i) + lane / 16) * D + n];
+}
+template <int D>
 __device__ __forceinline__ void project16(const double (*A)[D + 2], double (*C)[D + 2] /* [kShares*16][D+2] */,
-                                          const double* __restrict__ M, int wave, int lane) {
+                                          const double (&b)[ProjGeom<D>::kSteps], int wave, int lane) {
   typedef ProjGeom<D> G;
   const int nt = wave % G::kNt, share = wave / G::kNt;
   const int n = 16 * nt + lane % 16;
-  double b[G::kSteps];
-#pragma unroll
-  for (int i = 0; i < G::kSteps; i++) b[i] = M[(size_t)(4 * (share * G::kSteps + i) + lane / 16) * D + n];
   f64x4 acc = {0.0, 0.0, 0.0, 0.0};
 #pragma unroll
   for (int i = 0; i < G::kSteps; i++)
@@ -72,8 +77,14 @@ __global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restr
                                                            double* __restrict__ k_mean, int H, int N, int bq, int bk,
                                                            int Tm, int Tn, int k, int w_per_head, int topk_blocks,
                                                            int smooth) {
-  __shared__ double xa[kRouterRows][D + 2];            // pooled queries, later Qbar M
-  __shared__ double tile[kRouterRows][kColsPerRound + 8];
+  // LDS: xa [16][D+2] pooled queries, later Qbar M | tile [16][264] one round of scores (the partial
+  // projections before the first round) | stage [16 waves][16][34] each wave's private operand chunk
+  extern __shared__ __attribute__((aligned(16))) double lds[];
+  double (*xa)[D + 2] = reinterpret_cast<double (*)[D + 2]>(lds);
+  double (*tile)[kColsPerRound + 8] = reinterpret_cast<double (*)[kColsPerRound + 8]>(lds + kRouterRows * (D + 2));
+  double (*stage)[kStageLd] = reinterpret_cast<double (*)[kStageLd]>(lds + kRouterRows * (D + 2) +
+                                                                       kRouterRows * (kColsPerRound + 8)) +
+                              (threadIdx.x / kWave) * 16;
   static_assert(ProjGeom<D>::kShares * (D + 2) <= kColsPerRound + 8, "projection shares must fit the score tile");
   double (*xb)[D + 2] = reinterpret_cast<double (*)[D + 2]>(&tile[0][0]);   // partial Qbar M; dead before the first round
   if ((int)blockIdx.x >= topk_blocks) {
@@ -102,6 +113,8 @@ __global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restr
   const double* M = router_m + (w_per_head ? (size_t)(bh % H) * D * D : 0);
 
   SLA2_PHASE_MARK(0)
+  double mb[ProjGeom<D>::kSteps];
+  project16_fetch<D>(mb, M, wave, lane);               // operands of the projection, in flight during the Qbar load
   for (int e = threadIdx.x; e < kRouterRows * D; e += 1024) {
     const int r = e / D, c = e % D;
     const int row = min(row0 + r, Tm - 1);             // rows past the end repeat the last one; never stored
@@ -110,7 +123,7 @@ __global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restr
   }
   __syncthreads();
   SLA2_PHASE_MARK(1)
-  project16<D>(xa, xb, M, wave, lane);                                    // Qbar (Wq Wk^T / sqrt(d)), in shares
+  project16<D>(xa, xb, mb, wave, lane);                                   // Qbar (Wq Wk^T / sqrt(d)), in shares
   __syncthreads();
   for (int e = threadIdx.x; e < kRouterRows * D; e += 1024) {
     const int r = e / D, c = e % D;
@@ -136,19 +149,30 @@ __global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restr
       const int col0 = r * kColsPerRound + wave * 16;
       f64x4 acc = {0.0, 0.0, 0.0, 0.0};
       if (col0 < Tn) {
-        // operand layout of v_mfma_f64_16x16x4: lane l feeds A[l%16][l/16] and B[l/16][l%16]
-        const int jrow = min(col0 + lane % 16, Tn - 1);
-        const double* kb = ks + (size_t)jrow * D + lane / 16;
-        const double* qa = &xa[lane % 16][lane / 16];
-        // 16 operand loads in flight at a time: the loop is bound by their latency, not by the MFMAs
+        // The wave's 16 key rows are fetched with coalesced 16-byte loads (a row's 32 doubles of one
+        // chunk are 256 contiguous bytes), one chunk ahead, parked in the wave's private LDS slab and
+        // read back in the operand layout of v_mfma_f64_16x16x4 (lane l feeds A[l%16][l/16] and
+        // B[l/16][l%16]).  A wave's LDS operations execute in order, so no barrier is involved.
+        typedef __attribute__((ext_vector_type(2))) double f64x2;
+        const double* kb = ks + (size_t)col0 * D + 2 * (lane % 16);
+        f64x2 pre[4];
+        auto fetch = [&](int kc) {
 #pragma unroll
-        for (int c16 = 0; c16 < D / 64; c16++) {
-          double b[16];
+          for (int i = 0; i < 4; i++) {
+            const int r = min(col0 + 4 * i + lane / 16, Tn - 1) - col0;       // rows past the end repeat the last one
+            pre[i] = *reinterpret_cast<const f64x2*>(kb + (size_t)r * D + kStageK * kc);
+          }
+        };
+        fetch(0);
 #pragma unroll
-          for (int x = 0; x < 16; x++) b[x] = kb[4 * (16 * c16 + x)];
+        for (int kc = 0; kc < D / kStageK; kc++) {
 #pragma unroll
-          for (int x = 0; x < 16; x++)
-            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(qa[4 * (16 * c16 + x)], b[x], acc, 0, 0, 0);
+          for (int i = 0; i < 4; i++) *reinterpret_cast<f64x2*>(&stage[4 * i + lane / 16][2 * (lane % 16)]) = pre[i];
+          if (kc + 1 < D / kStageK) fetch(kc + 1);
+#pragma unroll
+          for (int kk = 0; kk < kStageK / 4; kk++)
+            acc = __builtin_amdgcn_mfma_f64_16x16x4f64(xa[lane % 16][kStageK * kc + 4 * kk + lane / 16],
+                                                       stage[lane % 16][4 * kk + lane / 16], acc, 0, 0, 0);
         }
       }
       // result layout: lane l, register v holds C[l/16 + 4 v][l%16]
@@ -255,14 +279,23 @@ hipError_t launch_router_topk(const Shape& s, const double* q_sum, const double*
   const int topk_blocks = s.k > 0 ? s.BH * row_tiles : 0;        // k = 0: only the colmean workgroups run
   dim3 grid((unsigned)(topk_blocks + s.BH * (s.d / 16)));
   const int rounds = (s.Tn + kColsPerRound - 1) / kColsPerRound;     // <= 8 (kMaxKeyBlocks)
-#define SLA2_TOPK(DD, SS)                                                                                       \
-  router_topk_kernel<DD, SS><<<grid, 1024, 0, stream>>>(q_sum, k_sum, router_m, block_idx, k_mean, s.H, s.N, s.bq, \
-                                                        s.bk, s.Tm, s.Tn, s.k, s.w_per_head ? 1 : 0, topk_blocks,    \
-                                                        s.smooth ? 1 : 0)
+#define SLA2_TOPK(DD, SS)                                                                                        \
+  {                                                                                                              \
+    static bool configured = false;                                                                              \
+    if (!configured) {                                                                                           \
+      hipError_t e = hipFuncSetAttribute((const void*)router_topk_kernel<DD, SS>,                                \
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)router_lds_bytes<DD>()); \
+      if (e != hipSuccess) return e;                                                                             \
+      configured = true;                                                                                         \
+    }                                                                                                            \
+    router_topk_kernel<DD, SS><<<grid, 1024, router_lds_bytes<DD>(), stream>>>(                                  \
+        q_sum, k_sum, router_m, block_idx, k_mean, s.H, s.N, s.bq, s.bk, s.Tm, s.Tn, s.k, s.w_per_head ? 1 : 0,   \
+        topk_blocks, s.smooth ? 1 : 0);                                                                          \
+  }
   if (s.d == 128) {
-    if (rounds <= 2) SLA2_TOPK(128, 8); else if (rounds <= 4) SLA2_TOPK(128, 16); else SLA2_TOPK(128, 32);
+    if (rounds <= 2) SLA2_TOPK(128, 8) else if (rounds <= 4) SLA2_TOPK(128, 16) else SLA2_TOPK(128, 32)
   } else {
-    if (rounds <= 2) SLA2_TOPK(64, 8); else if (rounds <= 4) SLA2_TOPK(64, 16); else SLA2_TOPK(64, 32);
+    if (rounds <= 2) SLA2_TOPK(64, 8) else if (rounds <= 4) SLA2_TOPK(64, 16) else SLA2_TOPK(64, 32)
   }
 #undef SLA2_TOPK
   return hipGetLastError();
