@@ -21,6 +21,7 @@ typedef __attribute__((ext_vector_type(4))) double f64x4;
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // 16 bytes in flight (a native vector: stays in registers)
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+typedef __attribute__((ext_vector_type(8))) int i32x8;            // operand of the 64-deep FP8 product
 
 constexpr int kWave = 64;
 constexpr int kMaxKeyBlocks = 2048;   // router keeps a whole score row in registers

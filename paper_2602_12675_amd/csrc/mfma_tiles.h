@@ -92,13 +92,33 @@ __device__ __forceinline__ void dma_tile(const uint16_t* src /* first row */, in
   }
 }
 
-// The same for a 64 x D tile of e4m3 codes (rows of D bytes; 8-byte operand reads).
+// The same for a tile whose 64 rows all exist: no clamping, and every address is a per-lane constant
+// plus a multiple of the instruction stride, which keeps the per-tile address arithmetic scalar.
+template <int D, int NW>
+__device__ __forceinline__ void dma_tile_full(const uint16_t* src, uint16_t* tile, int w, int lane) {
+  typedef SwizzledLayout<D> L;
+  constexpr int kRowsPerInstr = 1024 / (D * 2);
+  constexpr int kInstrs = kTileTokens / kRowsPerInstr / NW;
+  const int row_w = w * kRowsPerInstr + lane / L::kChunks;
+  const unsigned lane_off = (unsigned)row_w * (unsigned)(D * 2) + 16u * (unsigned)((lane % L::kChunks) ^ L::swz(row_w));
+  const char* base = reinterpret_cast<const char*>(src);
+#pragma unroll
+  for (int i = 0; i < kInstrs; i++)
+    __builtin_amdgcn_global_load_lds(
+        (const __attribute__((address_space(1))) void*)(base + i * (NW * kRowsPerInstr * D * 2) + lane_off),
+        (__attribute__((address_space(3))) void*)(tile + (i * NW + w) * 512), 16, 0, 0);
+}
+
+// The same for a 64 x D tile of e4m3 codes.  Rows of D bytes; the operand of the 64-deep FP8
+// product is 32 consecutive codes of a row, so the unit that is XOR-permuted is the aligned
+// 32-byte pair of chunks (two 16-byte reads per operand, second at +16).
 template <int D> struct SwizzledLayout8 {
   static constexpr int kChunks = D / 16;             // 16-byte chunks per row
+  static constexpr int kPairs = D / 32;
   static constexpr int kTileBytes = kTileTokens * D;
-  __device__ static __forceinline__ int swz(int row) { return row & (kChunks - 1); }
-  __device__ static __forceinline__ int offset(int row, int col) {   // bytes; col multiple of 8
-    return row * D + (((col >> 4) ^ swz(row)) << 4) + (col & 15);
+  __device__ static __forceinline__ int swz(int row) { return (row >> 1) & (kPairs - 1); }
+  __device__ static __forceinline__ int offset(int row, int col) {   // bytes
+    return row * D + (((col >> 5) ^ swz(row)) << 5) + (col & 31);
   }
 };
 template <int D, int NW>
@@ -108,7 +128,8 @@ __device__ __forceinline__ void dma_tile8(const uint8_t* src, uint8_t* tile, int
   constexpr int kInstrs = kTileTokens / kRowsPerInstr / NW;
   static_assert(kInstrs >= 1 && (kRowsPerInstr * NW) % 8 == 0, "unsupported tile split");
   const int row_w = w * kRowsPerInstr + lane / L::kChunks;
-  const int chunk = (lane % L::kChunks) ^ L::swz(row_w);
+  const int pc = lane % L::kChunks;                  // chunk slot this lane fills; it fetches the chunk that belongs there
+  const int chunk = 2 * ((pc >> 1) ^ L::swz(row_w)) + (pc & 1);
   const uint8_t* g = src + row_w * D + 16 * chunk;
 #pragma unroll
   for (int i = 0; i < kInstrs; i++)

@@ -254,6 +254,84 @@ template <int D, int BQ, bool FP8> struct AttnSmem {
 
 constexpr int kVmcnt0 = 0x0F70;   // s_waitcnt vmcnt(0), other counters untouched
 
+// A global load the compiler does not track: no wait is generated for it, the caller waits with
+// wait_vmcnt<>() and then passes every loaded value through settle() before using it.
+template <class T>
+__device__ __forceinline__ T load_untracked(const void* p) {
+  T r;
+  if constexpr (sizeof(T) == 16) asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(p));
+  else asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p));
+  return r;
+}
+template <class T, bool UNTRACKED>
+__device__ __forceinline__ T load_maybe_tracked(const void* p) {
+  if constexpr (UNTRACKED) return load_untracked<T>(p);
+  else return *reinterpret_cast<const T*>(p);
+}
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N));
+}
+// Orders every later use of x after the preceding wait (volatile statements keep their order).
+template <class T>
+__device__ __forceinline__ void settle(T& x) { asm volatile("" : "+v"(x)); }
+
+// LDS operand reads issued the same way.  The compiler's scheduler keeps a tracked read, its wait
+// and the product that consumes it back to back, so the LDS latency is paid once per product; with
+// the reads untracked the kernel keeps several in flight and waits with the count it knows.  The
+// LDS counter retires in order, so "at most n outstanding" settles everything but the n youngest.
+// Another benefit: a tracked transposing read is treated as a possible alias of the tile transfer
+// in flight and is preceded by vmcnt(0).
+__device__ __forceinline__ unsigned lds_address(const void* p) {
+  return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
+}
+template <int OFF1>   // 8 bytes at addr and 8 bytes at addr + 512 OFF1
+__device__ __forceinline__ u32x4 lds_read2_untracked(unsigned addr) {
+  u32x4 r;
+  asm volatile("ds_read2st64_b64 %0, %1 offset1:%2" : "=v"(r) : "v"(addr), "n"(OFF1));
+  return r;
+}
+template <int OFF>    // 16 bytes at addr + OFF
+__device__ __forceinline__ u32x4 lds_read16_untracked(unsigned addr) {
+  u32x4 r;
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+  return r;
+}
+template <int OFF>    // transposing read, see read_tr4
+__device__ __forceinline__ u32x2 lds_read_tr_untracked(unsigned addr) {
+  u32x2 r;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
+  return r;
+}
+// at addr + n UNIT with the offset in the instruction; n is a constant after unrolling
+template <int UNIT>
+__device__ __forceinline__ u32x2 lds_read_tr_untracked_at(unsigned addr, int n) {
+  switch (n) {
+    case 0: return lds_read_tr_untracked<0>(addr);
+    case 1: return lds_read_tr_untracked<UNIT>(addr);
+    case 2: return lds_read_tr_untracked<2 * UNIT>(addr);
+    case 3: return lds_read_tr_untracked<3 * UNIT>(addr);
+    case 4: return lds_read_tr_untracked<4 * UNIT>(addr);
+    case 5: return lds_read_tr_untracked<5 * UNIT>(addr);
+    case 6: return lds_read_tr_untracked<6 * UNIT>(addr);
+    default: return lds_read_tr_untracked<7 * UNIT>(addr);
+  }
+}
+// n is a constant once the calling loop is unrolled; only the matching statement survives
+__device__ __forceinline__ void wait_lgkmcnt(int n) {
+  switch (n) {
+    case 0: asm volatile("s_waitcnt lgkmcnt(0)"); break;
+    case 1: asm volatile("s_waitcnt lgkmcnt(1)"); break;
+    case 2: asm volatile("s_waitcnt lgkmcnt(2)"); break;
+    case 3: asm volatile("s_waitcnt lgkmcnt(3)"); break;
+    case 4: asm volatile("s_waitcnt lgkmcnt(4)"); break;
+    case 5: asm volatile("s_waitcnt lgkmcnt(5)"); break;
+    case 6: asm volatile("s_waitcnt lgkmcnt(6)"); break;
+    default: asm volatile("s_waitcnt lgkmcnt(0)"); break;
+  }
+}
+
 template <int D, int BQ, int MODE>
 __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
@@ -271,6 +349,13 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   typedef AttnSmem<D, BQ, FP8> SM;
   typedef SwizzledLayout<D> SL;
   typedef SwizzledLayout8<D> SL8;
+  // Loads and LDS reads of the main loop are issued untracked and waited for by count (see
+  // load_untracked).  The one exception is the shape with the highest register pressure, bf16
+  // operands at d = 128 with two workgroups per CU: holding reads in flight costs registers it
+  // does not have, and the compiler-tracked form is the faster one there.
+  constexpr bool kManual = FP8;
+  // global -> LDS transfers one wave issues per tile (1 KB each): V, and K in bf16 or e4m3
+  constexpr int kDmaOps = kTileTokens * D * 2 / 1024 / NW + kTileTokens * D * (FP8 ? 1 : 2) / 1024 / NW;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   float* zs = reinterpret_cast<float*>(smem + SM::kZsOff);
   float* red = reinterpret_cast<float*>(smem + SM::kRedOff);
@@ -283,7 +368,8 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
   if (logical >= total_blocks) return;
   const int bh = logical / Tm, i = logical % Tm, h = bh % H;
-  const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave, g = lane / 32;
+  const int tid = threadIdx.x, lane = tid % kWave, g = lane / 32;
+  const int w = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave index, known to be uniform
   const int row0 = i * BQ;
   const int rows_valid = min(BQ, N - row0);
   const uint16_t* qh = q + (size_t)bh * N * D;
@@ -293,24 +379,35 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   const int ntiles = DENSE ? Tn : ksel;
   const int mt0 = HS::mt0(w), nt0 = HS::nt0(w);
   const size_t blk0 = (size_t)bh * Tn;   // first key block of this head in the per-block arrays
+  // Key block of tile s.  The indices (and the FP8 scales) are fetched one and two tiles ahead of
+  // their use: a scalar load consumed right away stalls the wave for its whole latency.
+  auto tile_block = [&](int s) { return DENSE ? min(s, Tn - 1) : sel[min(s, ntiles - 1)]; };
+  int j_cur = ntiles > 0 ? tile_block(0) : 0, j_nxt = ntiles > 0 ? tile_block(1) : 0;
+  float sk_cur = 1.f;
+  if constexpr (FP8) sk_cur = k_scale[blk0 + j_cur];
 
   // tile s: global memory -> LDS buffer `buf`, no registers involved (completion: vmcnt)
-  auto dma = [&](int s, int buf) {
-    const int j = DENSE ? s : sel[s];
+  auto dma = [&](int j, int buf) {
     const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
     if constexpr (FP8) dma_tile8<D, NW>(k_fp8 + (blk0 + j) * kTileTokens * D, kbuf(buf), w, lane);
+    else if (kManual && valid == kTileTokens) dma_tile_full<D, NW>(kh + (size_t)t0 * D, reinterpret_cast<uint16_t*>(kbuf(buf)), w, lane);
     else dma_tile<D, NW>(kh + (size_t)t0 * D, valid, reinterpret_cast<uint16_t*>(kbuf(buf)), w, lane);
-    dma_tile<D, NW>(vh + (size_t)t0 * D, valid, vbuf(buf), w, lane);
+    if (kManual && valid == kTileTokens) dma_tile_full<D, NW>(vh + (size_t)t0 * D, vbuf(buf), w, lane);
+    else dma_tile<D, NW>(vh + (size_t)t0 * D, valid, vbuf(buf), w, lane);
   };
-  if (ntiles > 0) dma(0, 0);
+
+  if (ntiles > 0) dma(j_cur, 0);
 
   // Q fragments (B operand of S^T = K Q^T): lane <- Q[row0 + 32 w + l%32][16 ks + 8 g + 0..7]
   bf16x8 qf[KS];
   {
     const int r = min(32 * w + lane % 32, rows_valid - 1);   // rows past the end repeat the last one; never stored
-    const uint16_t* src = qh + (size_t)(row0 + r) * D + 8 * g;
+    const uint16_t* src = qh + (size_t)(row0 + r) * D;
+    // bf16 product: fragment ks = columns 16 ks + 8 g + 0..7.  FP8 product (64 deep): the lane's
+    // operand of step ks2 is columns 64 ks2 + 32 g + 0..31, held as fragments 4 ks2 + 0..3.
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
+    for (int ks = 0; ks < KS; ks++)
+      qf[ks] = *reinterpret_cast<const bf16x8*>(src + (FP8 ? 64 * (ks / 4) + 32 * g + 8 * (ks % 4) : 16 * ks + 8 * g));
   }
   // Everything issued so far is settled here, on every path into the main loop; a pending load
   // left over from the prologue would otherwise put a vmcnt wait in front of every use of a Q
@@ -371,27 +468,35 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   const float c0 = kLog2e * rsqrtf((float)D);        // scores are used as S * log2(e) / sqrt(d)
 
   for (int s = 0; s < ntiles; s++) {
+    SLA2_PHASE_MARK(0)
     const int buf = s & 1;
-    const int j = DENSE ? s : sel[s];
+    const int j = j_cur;
     const int valid = min(kTileTokens, N - j * kTileTokens);
-    float sk = 1.f;
-    if constexpr (FP8) sk = k_scale[blk0 + j];
+    const float sk = sk_cur;
+    const int j_nn = tile_block(s + 2);                // consumed in the next iteration
+    if constexpr (FP8) sk_cur = k_scale[blk0 + j_nxt];
     // K^phi fragments and z_j of this tile straight from global memory into registers (no other
-    // wave needs them); they are consumed after the softmax.
-    // Issued before the next tile's transfer: vmcnt counts in order, so waiting for them later
-    // leaves that transfer in flight
+    // wave needs them); they are consumed after the softmax.  They are issued before the next
+    // tile's transfer and, since vmcnt retires in order, are complete once at most kDmaOps
+    // operations are outstanding.  The loads are opaque to the compiler on purpose: its own
+    // bookkeeping across the conditional transfer below falls back to vmcnt(0) at their first
+    // use, which stalls every iteration on the tile that was just requested.
     bf16x8 kphi[DENSE ? 1 : HS::kMtw][kTileTokens / 16];
+    float zj[DENSE ? 1 : HS::kMtw];
     if constexpr (!DENSE) {
 #pragma unroll
       for (int a = 0; a < HS::kMtw; a++) {
 #pragma unroll
         for (int ks = 0; ks < kTileTokens / 16; ks++)
-          kphi[a][ks] = *reinterpret_cast<const bf16x8*>(k_phi + kphi_offset<D>(blk0 + j, mt0 + a, ks, lane));
-        zsel[a] += z_blocks[(blk0 + j) * D + 32 * (mt0 + a) + lane % 32];
+          kphi[a][ks] = load_maybe_tracked<bf16x8, kManual>(k_phi + kphi_offset<D>(blk0 + j, mt0 + a, ks, lane));
+        zj[a] = load_maybe_tracked<float, kManual>(z_blocks + (blk0 + j) * D + 32 * (mt0 + a) + lane % 32);
+        if constexpr (!kManual) zsel[a] += zj[a];
       }
     }
 
-    if (s + 1 < ntiles) dma(s + 1, buf ^ 1);         // next tile -> other buffer
+    if (s + 1 < ntiles) dma(j_nxt, buf ^ 1);         // next tile -> other buffer
+    j_cur = j_nxt;
+    j_nxt = j_nn;
     const uint16_t* vt = vbuf(buf);
     // ---- S^T = K Q^T (keys x query rows), two 32-key halves ----
     f32x16 sacc[2];
@@ -400,13 +505,36 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
 #pragma unroll
       for (int e = 0; e < 16; e++) sacc[mt][e] = 0.f;
     if constexpr (FP8) {
-      const uint8_t* kt = kbuf(buf);
+      // 64-deep products: the operand of (step ks2, key half mt) is 32 consecutive codes of key row
+      // 32 mt + l % 32, two 16-byte reads.  The swizzle is an XOR on the pair bits of the address,
+      // so step ks2 sits at (address of step 0) ^ 64 ks2; all reads of a tile are issued up front.
+      static_assert(D % 64 == 0, "the FP8 product consumes the head dimension 64 at a time");
+      constexpr int KS2 = D / 64;
+      const unsigned ka = lds_address(kbuf(buf) + SL8::offset(lane % 32, 32 * g));
+      u32x4 klo[KS2][2], khi[KS2][2];
 #pragma unroll
-      for (int ks = 0; ks < KS; ks++)
+      for (int ks2 = 0; ks2 < KS2; ks2++) {
+        klo[ks2][0] = lds_read16_untracked<0>(ka ^ (64u * ks2));
+        khi[ks2][0] = lds_read16_untracked<16>(ka ^ (64u * ks2));
+        klo[ks2][1] = lds_read16_untracked<32 * D>(ka ^ (64u * ks2));
+        khi[ks2][1] = lds_read16_untracked<32 * D + 16>(ka ^ (64u * ks2));
+      }
+#pragma unroll
+      for (int ks2 = 0; ks2 < KS2; ks2++)
 #pragma unroll
         for (int mt = 0; mt < 2; mt++) {
-          long a = *reinterpret_cast<const long*>(kt + SL8::offset(32 * mt + lane % 32, 16 * ks + 8 * g));
-          sacc[mt] = mfma_fp8(a, qf8[ks], sacc[mt]);
+          wait_lgkmcnt(2 * (2 * (KS2 - 1 - ks2) + 1 - mt));
+          settle(klo[ks2][mt]);
+          settle(khi[ks2][mt]);
+          const u32x4 lo = klo[ks2][mt], hi = khi[ks2][mt];
+          const i32x8 a = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+          i32x8 b;
+#pragma unroll
+          for (int x = 0; x < 4; x++) {
+            b[2 * x] = (int)(unsigned)((unsigned long)qf8[4 * ks2 + x]);
+            b[2 * x + 1] = (int)(unsigned)((unsigned long)qf8[4 * ks2 + x] >> 32);
+          }
+          sacc[mt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, sacc[mt], 0, 0, 0, 0, 0, 0);   // e4m3 x e4m3, no scales
         }
     } else {
       const uint16_t* kt = reinterpret_cast<const uint16_t*>(kbuf(buf));
@@ -416,6 +544,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         for (int mt = 0; mt < 2; mt++)
           sacc[mt] = mfma_bf16(row_fragment<SL>(kt, 32 * mt + lane % 32, 16 * ks + 8 * g), qf[ks], sacc[mt]);
     }
+    SLA2_PHASE_MARK(1)
     // ---- online softmax of this lane's query row over the 64 keys ----
     const float c1 = FP8 ? c0 * s_q * sk : c0;       // dequantisation folded into the score scale
     if (valid < kTileTokens) {
@@ -462,13 +591,69 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
 #pragma unroll
       for (int e = 0; e < 16; e++) oacc[et][e] *= corr;
 
+    SLA2_PHASE_MARK(2)
+    if constexpr (!DENSE) {
+      if constexpr (kManual) {
+        // the register loads issued at the top have landed; the tile transfer may still be in flight
+        if (s + 1 < ntiles) wait_vmcnt<kDmaOps>();
+        else wait_vmcnt<0>();
+#pragma unroll
+        for (int a = 0; a < HS::kMtw; a++) {
+#pragma unroll
+          for (int ks = 0; ks < kTileTokens / 16; ks++) settle(kphi[a][ks]);
+          settle(zj[a]);
+        }
+#pragma unroll
+        for (int a = 0; a < HS::kMtw; a++) zsel[a] += zj[a];
+      }
+    }
     // ---- O^T += V^T P^T, and the d x d state of this block: h += K^phi^T V ----
+    // address of this lane's first transposing read of fragment (ks = 0, et = 0), cf. read_tr4
+    const unsigned va = lds_address(vt + SL::offset(4 * g + (lane % 16) / 4, 16 * ((lane / 16) % 2) + 4 * (lane % 4)));
+    unsigned vaddr[ET];                              // one address per 32-channel tile; the token step is an immediate
+#pragma unroll
+    for (int et = 0; et < ET; et++) vaddr[et] = va ^ (64u * et);
+    u32x2 vlo[3], vhi[3];
 #pragma unroll
     for (int ks = 0; ks < kTileTokens / 16; ks++) {
-      if constexpr (HS::kNtw == ET || DENSE) {       // every V fragment feeds both products
+      if constexpr (!kManual && (HS::kNtw == ET || DENSE)) {   // every V fragment feeds both products
 #pragma unroll
         for (int et = 0; et < ET; et++) {
           bf16x8 vf = v_fragment<SL>(vt, ks, 32 * et, lane);
+          oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
+          if constexpr (!DENSE) {
+#pragma unroll
+            for (int a = 0; a < HS::kMtw; a++) hacc[a][et] = mfma_bf16(kphi[a][ks], vf, hacc[a][et]);
+          }
+        }
+      } else if constexpr (HS::kNtw == ET || DENSE) {       // the same with the reads kept in flight
+        // fragment f = ks ET + et: two transposing reads (tokens 16 ks + 4 g.. and + 8), kept kVAhead
+        // fragments ahead of the products.  Row swizzle and lane terms are the same for every
+        // fragment of a lane, so fragment (ks, et) sits at (va ^ 64 et) + 32 D ks.
+        constexpr int kVAhead = FP8 ? 2 : 1, kFrags = (kTileTokens / 16) * ET;
+        if (ks == 0) {
+#pragma unroll
+          for (int f = 0; f < kVAhead; f++) {
+            vlo[f] = lds_read_tr_untracked_at<8 * D * 2>(vaddr[f % ET], 2 * (f / ET));
+            vhi[f] = lds_read_tr_untracked_at<8 * D * 2>(vaddr[f % ET], 2 * (f / ET) + 1);
+          }
+        }
+#pragma unroll
+        for (int et = 0; et < ET; et++) {
+          const int f = ks * ET + et;
+          if (f + kVAhead < kFrags) {
+            const int f2 = f + kVAhead;
+            vlo[f2 % (kVAhead + 1)] = lds_read_tr_untracked_at<8 * D * 2>(vaddr[f2 % ET], 2 * (f2 / ET));
+            vhi[f2 % (kVAhead + 1)] = lds_read_tr_untracked_at<8 * D * 2>(vaddr[f2 % ET], 2 * (f2 / ET) + 1);
+          }
+          const int left = kFrags - 1 - f;
+          wait_lgkmcnt(2 * (left < kVAhead ? left : kVAhead));
+          u32x2& lo = vlo[f % (kVAhead + 1)];
+          u32x2& hi = vhi[f % (kVAhead + 1)];
+          settle(lo);
+          settle(hi);
+          const u32x4 v4 = {lo[0], lo[1], hi[0], hi[1]};
+          const bf16x8 vf = __builtin_bit_cast(bf16x8, v4);
           oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
           if constexpr (!DENSE) {
 #pragma unroll
@@ -489,9 +674,12 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         }
       }
     }
+    SLA2_PHASE_MARK(3)
     __builtin_amdgcn_s_waitcnt(kVmcnt0);             // the next tile has landed in LDS ...
     __syncthreads();                                 // ... for everyone, and this tile's buffer is free
+    SLA2_PHASE_MARK(4)
   }
+  SLA2_PHASE_MARK(5)
 
   // ================= epilogue =================
   const float inv_l = l_run > 0.f ? 1.f / l_run : 0.f;
@@ -617,6 +805,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     const int r = idx / (D / 8), ch = idx % (D / 8);
     if (r < rows_valid) *reinterpret_cast<u32x4*>(oh + (size_t)r * D + 8 * ch) = *reinterpret_cast<const u32x4*>(os + r * LD + 8 * ch);
   }
+  SLA2_PHASE_MARK(6)
 }
 
 struct AttnArgs {
