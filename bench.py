@@ -152,15 +152,24 @@ def main():
 
     BH, esz = w.B * w.H, (2 if w.dtype == "bf16" else 4)
     tile_iters = BH * w.T_m * ksel
-    attn_flops = tile_iters * 4.0 * w.block_q * w.block_kv * w.d + BH * w.T_m * 2.0 * w.block_q * w.d * w.d
+    qk_flops = tile_iters * 2.0 * w.block_q * w.block_kv * w.d           # Q K^T: fp8 products in fp8 mode
+    rest_flops = qk_flops + BH * w.T_m * 2.0 * w.block_q * w.d * w.d     # P V and Q^phi H_i: always bf16
+    attn_flops = qk_flops + rest_flops
     attn_ms = prof["attn"][0] / prof["attn"][1]
     mm = "fp8" if w.quant == "fp8" else "bf16"
     achieved = attn_flops / (attn_ms * 1e-3) / 1e12
+    if w.quant == "fp8":
+        # each product priced at the peak of its own operand type: time-weighted (harmonic) blend
+        peak = attn_flops / (qk_flops / MFMA_PEAK_TFLOPS["fp8"] + rest_flops / MFMA_PEAK_TFLOPS["bf16"])
+        note = ("peak = harmonic blend of dense fp8 MFMA (Q K^T, %.3g TFLOP) and dense bf16 MFMA (P V and the linear "
+                "branch, %.3g TFLOP)" % (qk_flops / 1e12, rest_flops / 1e12))
+    else:
+        peak = MFMA_PEAK_TFLOPS["bf16"]
+        note = "peak = dense bf16 MFMA"
     roofline = {"kernel": "attn_mfma (sparse + linear branch + mix)", "bound": "mfma", "achieved": round(achieved, 2),
-                "peak": MFMA_PEAK_TFLOPS["bf16"], "unit": "TFLOP/s", "frac": round(achieved / MFMA_PEAK_TFLOPS["bf16"], 4),
+                "peak": round(peak, 1), "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "traffic": measured_traffic(w.name, w.quant), "ms": round(attn_ms, 4),
-                "algorithmic_flops": attn_flops,
-                "note": "peak = dense bf16 MFMA; P V and the linear branch run in bf16 (in fp8 mode only Q K^T is fp8)"}
+                "algorithmic_flops": attn_flops, "note": note}
     qk_bytes = 2.0 * BH * w.N * w.d * esz
     hbm = {}
     if "block_sums" in stages:
