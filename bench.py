@@ -31,8 +31,8 @@ MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0}
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="wan1.3b-97-fp8")
     ap.add_argument("--quant", choices=["fp8", "none"], default=None, help="override the workload's sparse-branch precision")
     ap.add_argument("--topk", type=float, default=None, help="override the kept fraction of key blocks")
@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=6, help="heads of the workload the oracle is timed on")
+    ap.add_argument("--event-stride", type=int, default=1,
+                    help="bracket the dominant kernel with HIP events on every n-th timed step")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (for scaling FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     return ap.parse_args()
@@ -130,8 +132,10 @@ def main():
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    # timed region: only the dominant kernel carries event pairs (2 event records per step)
-    api.sla2_profile_begin(["attn"], args.steps)
+    # timed region: the dominant kernel carries an event pair (on every step unless --event-stride says
+    # otherwise; measured: the pairs do not change the step time)
+    stride = max(1, args.event_stride)
+    api.sla2_profile_begin_sampled(["attn"], (args.steps + stride - 1) // stride, stride)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
@@ -169,6 +173,7 @@ def main():
     roofline = {"kernel": "attn_mfma (sparse + linear branch + mix)", "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": round(peak, 1), "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
                 "traffic": measured_traffic(w.name, w.quant), "ms": round(attn_ms, 4),
+                "launches_timed": prof["attn"][1],
                 "algorithmic_flops": attn_flops, "note": note}
     qk_bytes = 2.0 * BH * w.N * w.d * esz
     hbm = {}

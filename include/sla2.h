@@ -158,6 +158,9 @@ typedef enum {
   SLA2_STAGE_COUNT = 6
 } sla2_stage;
 int sla2_profile_begin(unsigned stage_mask, int max_calls);
+/* The same, bracketing only calls 1, 1 + every, 1 + 2 every, ... (at most max_calls of them), for
+ * callers that want a few samples out of a long loop.  every >= 1. */
+int sla2_profile_begin_sampled(unsigned stage_mask, int max_calls, int every);
 int sla2_profile_end(double* stage_ms, int* stage_launches);
 
 const char* sla2_strerror(int status);

@@ -21,7 +21,8 @@ SLA2_FLAG_NO_SMOOTH_K = 1
 SLA2_OK, SLA2_EINVAL, SLA2_EUNSUPPORTED, SLA2_EWORKSPACE, SLA2_EALIAS, SLA2_EHIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("sla2_workspace_bytes", "sla2_workspace_layout", "sla2_num_selected", "sla2_router",
-           "sla2_forward", "sla2_dense_forward", "sla2_profile_begin", "sla2_profile_end",
+           "sla2_forward", "sla2_dense_forward", "sla2_profile_begin", "sla2_profile_begin_sampled",
+           "sla2_profile_end",
            "sla2_strerror", "sla2_version")
 
 STAGES = ("block_sums", "topk", "kv_state", "kv_total", "attn", "dense")   # sla2_stage
@@ -61,6 +62,8 @@ _lib.sla2_dense_forward.restype = ctypes.c_int
 _lib.sla2_dense_forward.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp]
 _lib.sla2_profile_begin.restype = ctypes.c_int
 _lib.sla2_profile_begin.argtypes = [ctypes.c_uint, ctypes.c_int]
+_lib.sla2_profile_begin_sampled.restype = ctypes.c_int
+_lib.sla2_profile_begin_sampled.argtypes = [ctypes.c_uint, ctypes.c_int, ctypes.c_int]
 _lib.sla2_profile_end.restype = ctypes.c_int
 _lib.sla2_profile_end.argtypes = [ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int)]
 _lib.sla2_strerror.restype = ctypes.c_char_p
@@ -154,6 +157,16 @@ def sla2_profile_begin(stages, max_calls: int) -> None:
     for name in stages:
         mask |= 1 << STAGES.index(name)
     rc = _lib.sla2_profile_begin(mask, max_calls)
+    if rc != SLA2_OK:
+        raise Sla2Error(rc)
+
+
+def sla2_profile_begin_sampled(stages, max_calls: int, every: int) -> None:
+    """As sla2_profile_begin, bracketing only every `every`-th call (max_calls of them)."""
+    mask = 0
+    for name in stages:
+        mask |= 1 << STAGES.index(name)
+    rc = _lib.sla2_profile_begin_sampled(mask, max_calls, every)
     if rc != SLA2_OK:
         raise Sla2Error(rc)
 

@@ -87,7 +87,7 @@ static T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
 struct Profiler {
   bool active = false;
   unsigned mask = 0;
-  int max_calls = 0, calls = 0;
+  int max_calls = 0, calls = 0, every = 1;          // every-th call is bracketed; max_calls of them
   std::vector<hipEvent_t> pool;                   // created in begin(); two per (call, stage)
   struct Rec { int stage; hipEvent_t a, b; };
   std::vector<Rec> recs;                          // capacity reserved in begin()
@@ -100,7 +100,8 @@ struct StageTimer {
   hipStream_t st; int stage; bool on = false; hipEvent_t a, b;
   StageTimer(int stage_, hipStream_t st_) : st(st_), stage(stage_) {
     Profiler& p = g_prof;
-    if (p.active && (p.mask >> stage & 1u) && p.calls <= p.max_calls && p.next + 2 <= p.pool.size() &&
+    if (p.active && (p.mask >> stage & 1u) && (p.calls - 1) % p.every == 0 && (p.calls - 1) / p.every < p.max_calls &&
+        p.next + 2 <= p.pool.size() &&
         p.recs.size() < p.recs.capacity()) {
       a = p.pool[p.next++]; b = p.pool[p.next++];
       on = hipEventRecord(a, st) == hipSuccess;
@@ -250,9 +251,11 @@ int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, 
   return SLA2_OK;
 }
 
-int sla2_profile_begin(unsigned stage_mask, int max_calls) {
+int sla2_profile_begin(unsigned stage_mask, int max_calls) { return sla2_profile_begin_sampled(stage_mask, max_calls, 1); }
+
+int sla2_profile_begin_sampled(unsigned stage_mask, int max_calls, int every) {
   Profiler& p = g_prof;
-  if (p.active || max_calls < 1 || max_calls > 100000 || (stage_mask >> SLA2_STAGE_COUNT)) return SLA2_EINVAL;
+  if (p.active || max_calls < 1 || max_calls > 100000 || every < 1 || (stage_mask >> SLA2_STAGE_COUNT)) return SLA2_EINVAL;
   int per_call = __builtin_popcount(stage_mask);
   if (per_call == 0) return SLA2_EINVAL;
   size_t n = (size_t)2 * per_call * max_calls;
@@ -265,7 +268,7 @@ int sla2_profile_begin(unsigned stage_mask, int max_calls) {
     }
   p.recs.clear();
   p.recs.reserve(n / 2);
-  p.next = 0; p.calls = 0; p.max_calls = max_calls; p.mask = stage_mask; p.active = true;
+  p.next = 0; p.calls = 0; p.max_calls = max_calls; p.every = every; p.mask = stage_mask; p.active = true;
   return SLA2_OK;
 }
 

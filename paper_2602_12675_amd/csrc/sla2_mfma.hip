@@ -22,7 +22,9 @@
 
 namespace sla2 {
 
-__device__ __forceinline__ float xhalf(float x) { return __shfl_xor(x, 32); }   // partner lane of the other half
+// lanes l and l ^ 32 combine their values; both get the same bits
+__device__ __forceinline__ float half_sum(float x) { return x + __shfl_xor(x, 32); }
+__device__ __forceinline__ float half_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
 
 __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -193,7 +195,7 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
     }
 #pragma unroll
     for (int a = 0; a < HS::kMtw; a++) {
-      const float z = zsum[a] + xhalf(zsum[a]);
+      const float z = half_sum(zsum[a]);
       zacc[a] += z;
       if (g == 0 && nt0 == 0) z_blocks[((size_t)bh * Tn + j) * D + 32 * (mt0 + a) + lane] = z;
     }
@@ -559,7 +561,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     for (int mt = 0; mt < 2; mt++)
 #pragma unroll
       for (int e = 0; e < 16; e++) mx = fmaxf(mx, sacc[mt][e]);
-    mx = fmaxf(mx, xhalf(mx)) * c1;
+    mx = half_max(mx) * c1;
     const float m_new = fmaxf(m_run, mx);            // finite: a tile holds at least one key
     const float m_off = m_new - kPShift;
     float rs = 0.f;
@@ -582,7 +584,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
           pf[2 * mt + e / 8][e % 8 + 1] = (__bf16)p1;
         }
       }
-    rs += xhalf(rs);
+    rs = half_sum(rs);
     const float corr = fast_exp2(m_run - m_new);     // 0 on the first tile
     l_run = l_run * corr + rs;
     m_run = m_new;
@@ -694,7 +696,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       for (int ks = 0; ks < KS; ks++)
 #pragma unroll
         for (int e = 0; e < 8; e++) qmu += (float)qf[ks][e] * (float)k_mean[(size_t)bh * D + 16 * ks + 8 * g + e];
-      qmu += xhalf(qmu);
+      qmu = half_sum(qmu);
     }
     if (g == 0 && qrow < rows_valid)
       lse[(size_t)bh * N + row0 + qrow] =
@@ -745,7 +747,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         qx[ks][e] = (float)qf[ks][e];
         qm = fmaxf(qm, qx[ks][e]);
       }
-    qm = fmaxf(qm, xhalf(qm));
+    qm = half_max(qm);
     float qs = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++)
@@ -754,7 +756,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         qx[ks][e] = fast_exp2((qx[ks][e] - qm) * kLog2e);
         qs += qx[ks][e];
       }
-    qs += xhalf(qs);
+    qs = half_sum(qs);
     const float qinv = 1.f / qs;
     __syncthreads();                                 // H_i^T and Z_i visible
     float den = 0.f;
@@ -769,7 +771,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         qf[ks][e] = (__bf16)qx[ks][e];
       }
     }
-    den += xhalf(den);
+    den = half_sum(den);
     inv_den = ksel >= Tn ? 0.f : 1.f / den;          // every block selected: nothing left for the linear branch
     // O_l^T = H_i^T Q^phi^T
 #pragma unroll
