@@ -3,6 +3,8 @@
 // downstream agrees with an fp64 reference up to summation order.
 //
 // This is a bandwidth kernel: it streams Q and K once with 16-byte loads and is bound by HBM.
+#include <type_traits>
+
 #include "common.h"
 
 namespace sla2 {
@@ -10,8 +12,9 @@ namespace sla2 {
 template <typename T> struct Vec16;
 template <> struct Vec16<uint16_t> {
   static constexpr int kElems = 8;
-  __device__ static void load(const uint16_t* p, float (&f)[8]) {
-    u32x4 u = *reinterpret_cast<const u32x4*>(p);
+  typedef u32x4 Raw;
+  __device__ static Raw load_raw(const uint16_t* p) { return *reinterpret_cast<const u32x4*>(p); }
+  __device__ static void unpack(Raw u, float (&f)[8]) {
 #pragma unroll
     for (int i = 0; i < 4; i++) {
       f[2 * i] = __builtin_bit_cast(float, u[i] << 16);
@@ -21,10 +24,9 @@ template <> struct Vec16<uint16_t> {
 };
 template <> struct Vec16<float> {
   static constexpr int kElems = 4;
-  __device__ static void load(const float* p, float (&f)[4]) {
-    f32x4 u = *reinterpret_cast<const f32x4*>(p);
-    f[0] = u[0]; f[1] = u[1]; f[2] = u[2]; f[3] = u[3];
-  }
+  typedef f32x4 Raw;
+  __device__ static Raw load_raw(const float* p) { return *reinterpret_cast<const f32x4*>(p); }
+  __device__ static void unpack(Raw u, float (&f)[4]) { f[0] = u[0]; f[1] = u[1]; f[2] = u[2]; f[3] = u[3]; }
 };
 
 // Row `a` of M = Wq Wk^T / sqrt(d):  M[a][c] = sum_n Wq[a][n] Wk[c][n] / sqrt(d)   (Eq. 16, both router
@@ -34,18 +36,19 @@ __device__ void fold_router_row(const float* __restrict__ Wq, const float* __res
                                 int d, int a, double* red /* LDS [256] */) {
   const int c = threadIdx.x % d, part = threadIdx.x / d, parts = 256 / d;
   const int n0 = part * (d / parts);
-  f32x4 wk[8], wq[8];                                  // d / parts / 4 = 16 (d = 128) or 4 (d = 64) groups of 4
+  constexpr int kBatch = 4;                            // loads in flight per operand; the pooling path sets the register budget
+  f32x4 wk[kBatch], wq[kBatch];                        // d / parts / 4 = 16 (d = 128) or 4 (d = 64) groups of 4
   double acc = 0.0;
-  for (int h = 0; h < d / parts / 4; h += 8) {
+  for (int h = 0; h < d / parts / 4; h += kBatch) {
 #pragma unroll
-    for (int x = 0; x < 8; x++) {
+    for (int x = 0; x < kBatch; x++) {
       const int n = n0 + 4 * (h + x);
       const bool ok = h + x < d / parts / 4;
       wk[x] = ok ? *reinterpret_cast<const f32x4*>(Wk + (size_t)c * d + n) : f32x4{0.f, 0.f, 0.f, 0.f};
       wq[x] = ok ? *reinterpret_cast<const f32x4*>(Wq + (size_t)a * d + n) : f32x4{0.f, 0.f, 0.f, 0.f};
     }
 #pragma unroll
-    for (int x = 0; x < 8; x++)
+    for (int x = 0; x < kBatch; x++)
 #pragma unroll
       for (int e = 0; e < 4; e++) acc += (double)wq[x][e] * (double)wk[x][e];
   }
@@ -97,12 +100,38 @@ __global__ __launch_bounds__(256) void block_sums_kernel(const T* __restrict__ q
   double acc[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; e++) acc[e] = 0.0;
-#pragma unroll 8
-  for (int r = rg; r < rows; r += rpp) {
-    float f[EPL];
-    Vec16<T>::load(x + (size_t)(row0 + r) * d + col, f);
+  const T* px = x + (size_t)(row0 + rg) * d + col;
+  const size_t pass_stride = (size_t)rpp * d;
+  // A full block is a known number of passes: every load of the thread is issued before the first
+  // sum (a loop with a run-time trip count leaves one load in flight at a time and a round trip
+  // to memory per pass).
+  auto full = [&](auto loads_tag) {
+    constexpr int LOADS = decltype(loads_tag)::value;
+    typename Vec16<T>::Raw raw[LOADS];
 #pragma unroll
-    for (int e = 0; e < EPL; e++) acc[e] += (double)f[e];
+    for (int i = 0; i < LOADS; i++) raw[i] = Vec16<T>::load_raw(px + i * pass_stride);
+#pragma unroll
+    for (int i = 0; i < LOADS; i++) {      // ascending rows, as the run-time loop below
+      float f[EPL];
+      Vec16<T>::unpack(raw[i], f);
+#pragma unroll
+      for (int e = 0; e < EPL; e++) acc[e] += (double)f[e];
+    }
+  };
+  // passes per full block: b / rpp = 2, 4 or 8 for bf16 rows, 4, 8 or 16 for fp32 rows
+  const int passes = (rows == b && b % rpp == 0) ? b / rpp : 0;
+  if (passes == 4) full(std::integral_constant<int, 4>());
+  else if (passes == 8) full(std::integral_constant<int, 8>());
+  else if (passes == 2 && EPL == 8) full(std::integral_constant<int, 2>());
+  else if (passes == 16 && EPL == 4) full(std::integral_constant<int, EPL == 4 ? 16 : 2>());
+  else {
+#pragma unroll 4
+    for (int r = rg; r < rows; r += rpp) {
+      float f[EPL];
+      Vec16<T>::unpack(Vec16<T>::load_raw(x + (size_t)(row0 + r) * d + col), f);
+#pragma unroll
+      for (int e = 0; e < EPL; e++) acc[e] += (double)f[e];
+    }
   }
 #pragma unroll
   for (int e = 0; e < EPL; e++) red[rg * d + col + e] = acc[e];
