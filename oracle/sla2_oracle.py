@@ -28,6 +28,8 @@ independently of itself) live in tests/test_oracle_pins.py:
                              constant-V invariance; block permutation
   e4m3_round                 nearest-with-ties-to-even search over the table of
                              all 256 codes built from the format's definition
+  quant_block_int8           codes against a brute-force nearest-integer search;
+                             range, symmetry, scale round trip
   sparse_branch_lowbit       equals sparse_branch when the quantisers are made
                              exact; small, bounded deviation otherwise.  The
                              quantisation scheme itself (granularity, scale of
@@ -43,8 +45,10 @@ import numpy as np
 
 QUANT_NONE = 0
 QUANT_FP8 = 1
+QUANT_INT8 = 2
 
 E4M3_MAX = 448.0          # largest finite magnitude of the OCP e4m3 format
+INT8_MAX = 127.0          # symmetric int8 range used for Q and K codes
 P_SCALE_LOG2 = 8          # P is rounded on the e4m3 grid after scaling by 2**8
 
 
@@ -208,6 +212,26 @@ def quant_block_e4m3(X32: np.ndarray):
     return e4m3_round(X32 * inv), np.float32(s)
 
 
+def quant_block_int8(X32: np.ndarray):
+    """The INT8 form of quant(.) for one block of Q or of the smoothed K
+    (Sec. 5 names INT8 next to FP8 as the low-bit formats of Q K^T).
+
+    Same granularity and the same float32 decisions as quant_block_e4m3: one
+    scale per block, amax = max |x|; inv = 127 / amax and s = amax / 127, both
+    float32 divisions; the code is the float32 product x * inv rounded to the
+    nearest integer, ties to even, kept within [-127, 127] (the range is
+    symmetric: -128 is never produced).  An all-zero block uses inv = s = 1.
+    Returns (integer codes as float32, s as float32)."""
+    X32 = np.asarray(X32, dtype=np.float32)
+    amax = np.float32(np.max(np.abs(X32))) if X32.size else np.float32(0)
+    if amax == 0:
+        return np.zeros_like(X32), np.float32(1.0)
+    inv = np.float32(INT8_MAX) / amax
+    s = amax / np.float32(INT8_MAX)
+    codes = np.clip(np.rint(X32 * inv), -INT8_MAX, INT8_MAX)     # rint = round half to even
+    return codes.astype(np.float32), np.float32(s)
+
+
 def smooth_k_f32(K: np.ndarray) -> np.ndarray:
     """The smoothed keys as they enter quantisation: float32(K) - float32(mu),
     mu = colmean(K) taken in float64 and rounded once to float32."""
@@ -216,7 +240,7 @@ def smooth_k_f32(K: np.ndarray) -> np.ndarray:
 
 
 def sparse_branch_lowbit(Q, K, V, sel, b_q: int, b_k: int, *, smooth: bool = True,
-                         q_blocks=None):
+                         q_blocks=None, quant_block=None):
     """Sparse branch with low-bit Q, K and P (Sec. 5), following the block loop
     of Alg. 2 step by step, because with a rounded P the result depends on the
     running maximum and therefore on the order of the blocks:
@@ -237,13 +261,18 @@ def sparse_branch_lowbit(Q, K, V, sel, b_q: int, b_k: int, *, smooth: bool = Tru
     updates l before it quantises P); V stays at its input values although Alg. 2
     also quantises V (the workload definition keeps V in bf16).
     K is the raw K: smoothing is done here in float32 (smooth_k_f32).
+    `quant_block` is the quantiser of Q and K blocks: quant_block_e4m3 (the
+    default) or quant_block_int8; everything after the codes - the exact
+    product of codes, the two scales, the rounding of P - is the same.
     Returns (O_s, L) like sparse_branch."""
+    if quant_block is None:
+        quant_block = quant_block_e4m3
     N, d = Q.shape
     Kin = smooth_k_f32(K) if smooth else K.astype(np.float32)
     T_n = num_blocks(N, b_k)
     Khat, sK = [], []
     for j in range(T_n):
-        v, s = quant_block_e4m3(Kin[j * b_k:min(N, (j + 1) * b_k)])
+        v, s = quant_block(Kin[j * b_k:min(N, (j + 1) * b_k)])
         Khat.append(v.astype(np.float64))
         sK.append(float(s))
     O = np.zeros((N, d), dtype=np.float64)
@@ -251,7 +280,7 @@ def sparse_branch_lowbit(Q, K, V, sel, b_q: int, b_k: int, *, smooth: bool = Tru
     rscale = 1.0 / math.sqrt(d)
     for i in (range(sel.shape[0]) if q_blocks is None else q_blocks):
         r0, r1 = i * b_q, min(N, (i + 1) * b_q)
-        Qhat, sQ = quant_block_e4m3(Q[r0:r1].astype(np.float32))
+        Qhat, sQ = quant_block(Q[r0:r1].astype(np.float32))
         Qhat = Qhat.astype(np.float64)
         sQ = float(sQ)
         m = np.full((r1 - r0, 1), -np.inf)
@@ -346,6 +375,9 @@ def forward_head(Q, K, V, Wq, Wk, alpha, topk_frac: float, b_q: int, b_k: int,
         O_s, L = sparse_branch(Q, Ks, V, sel, b_q, b_k, q_blocks=qb)
     elif quant == QUANT_FP8:
         O_s, L = sparse_branch_lowbit(Q, K, V, sel, b_q, b_k, smooth=smooth, q_blocks=qb)
+    elif quant == QUANT_INT8:
+        O_s, L = sparse_branch_lowbit(Q, K, V, sel, b_q, b_k, smooth=smooth, q_blocks=qb,
+                                      quant_block=quant_block_int8)
     else:
         raise ValueError("unknown quant mode")
     O_l, H, Z = linear_branch(Q, Ks, V, sel, b_q, b_k, q_blocks=qb)

@@ -427,6 +427,70 @@ def test_lowbit_products_are_exact_in_float64():
     assert all(F(S[i, j]) == exact[i, j] for i in range(8) for j in range(8))
 
 
+# ---- INT8 form of the Q/K quantiser (Sec. 5) ------------------------------- #
+def test_quant_block_int8_is_nearest_integer_symmetric():
+    rng = np.random.default_rng(23)
+    X = (rng.normal(size=(16, 8)) * 3.0).astype(np.float32)
+    X[3, 2] = -np.abs(X).max() * np.float32(1.5)          # the extreme entry is negative: the range must be symmetric
+    codes, s = O.quant_block_int8(X)
+    amax = np.float32(np.abs(X).max())
+    assert s == amax / np.float32(127)
+    assert codes.min() == -127.0 and codes.max() <= 127.0   # -128 is never produced
+    assert np.array_equal(codes, np.round(codes))
+    # brute force: the nearest integer to the float32 product x * inv, ties to the even integer
+    inv = np.float32(127) / amax
+    grid = np.arange(-127, 128, dtype=np.float64)
+    for x, c in zip(X.ravel(), codes.ravel()):
+        y = float(np.float32(x) * inv)
+        dist = np.abs(grid - y)
+        best = grid[dist == dist.min()]
+        want = best[0] if len(best) == 1 else next(b for b in best if int(b) % 2 == 0)
+        assert c == want, (x, y, c, want)
+    # dequantised values stay within half a step of x (plus the float32 rounding of the product)
+    assert np.all(np.abs(codes * s - X) <= 0.5 * s * (1 + 1e-5))
+    c0, s0 = O.quant_block_int8(np.zeros((4, 4), np.float32))
+    assert not c0.any() and s0 == 1.0
+
+
+def test_quant_block_int8_ties_go_to_even():
+    # amax = 127 makes inv exactly 1: the codes are rint(x)
+    X = np.array([[127.0, 0.5, 1.5, 2.5, -0.5, -1.5, -2.5, 63.5, 64.5]], dtype=np.float32)
+    codes, s = O.quant_block_int8(X)
+    assert s == 1.0
+    np.testing.assert_array_equal(codes[0], [127, 0, 2, 2, -0.0, -2, -2, 64, 64])
+
+
+def test_int8_branch_reduces_to_exact_when_quantiser_is_exact(monkeypatch):
+    """The INT8 mode shares the block loop of the FP8 mode; only the quantiser of Q and K
+    differs.  With both roundings switched off it must give the plain definition."""
+    N, d, bq, bk = 150, 8, 32, 16
+    Q, K, V, Wq, Wk = rand_head(24, N, d)
+    Q, K, V = (a.astype(np.float32).astype(np.float64) for a in (Q, K, V))
+    sel = O.forward_head(Q, K, V, Wq, Wk, 1.0, 0.3, bq, bk)["sel"]
+    monkeypatch.setattr(O, "e4m3_round", lambda x: np.asarray(x, dtype=np.float32))
+    monkeypatch.setattr(O, "quant_block_int8", lambda X: (np.asarray(X, np.float32), np.float32(1.0)))
+    lo = O.forward_head(Q, K, V, Wq, Wk, 1.0, 0.3, bq, bk, quant=O.QUANT_INT8, sel=sel)
+    ex = O.forward_head(Q, K, V, Wq, Wk, 1.0, 0.3, bq, bk, sel=sel)
+    np.testing.assert_allclose(lo["O"], ex["O"], rtol=0, atol=5e-6)
+    np.testing.assert_allclose(lo["L"], ex["L"], rtol=0, atol=5e-6)
+
+
+def test_int8_branch_close_to_exact_and_tighter_than_fp8_scores():
+    N, d, bq, bk = 512, 64, 64, 64
+    Q, K, V, Wq, Wk = rand_head(21, N, d)
+    ex = O.forward_head(Q, K, V, Wq, Wk, 1.0, 0.25, bq, bk)
+    i8 = O.forward_head(Q, K, V, Wq, Wk, 1.0, 0.25, bq, bk, quant=O.QUANT_INT8)
+    f8 = O.forward_head(Q, K, V, Wq, Wk, 1.0, 0.25, bq, bk, quant=O.QUANT_FP8)
+    rel = np.linalg.norm(i8["O"] - ex["O"]) / np.linalg.norm(ex["O"])
+    assert 1e-4 < rel < 5e-2, rel
+    # the scores (seen through the log-sum-exp) carry 7 fraction bits of a block-wide scale in INT8
+    # against 3 mantissa bits in e4m3: for Gaussian blocks the INT8 scores are the closer ones
+    err_i8 = np.abs(i8["L"] - ex["L"]).mean()
+    err_f8 = np.abs(f8["L"] - ex["L"]).mean()
+    assert err_i8 < err_f8, (err_i8, err_f8)
+    assert np.array_equal(i8["sel"], ex["sel"])                     # the router never sees the codes
+
+
 # ---- Table 1: the shapes behind the dense-equivalent FLOP count ----------- #
 def test_table1_flops_confirm_workload_shapes():
     import os
