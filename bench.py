@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the SLA2 forward pass on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--quant fp8|none]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--quant fp8|int8|none]
 
 One "step" is one sla2_forward call (router -> kv state -> fused sparse + linear +
 mix) on a synthetic Wan2.1-1.3B-shaped input set (B=1, H=12, N=32760, d=128,
@@ -25,7 +25,7 @@ for p in (ROOT, os.path.join(ROOT, "oracle")):
         sys.path.insert(0, p)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
-MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0}
+MFMA_PEAK_TFLOPS = {"bf16": 2500.0, "fp8": 5000.0, "int8": 5000.0}   # dense; int8 in TOP/s
 
 
 def parse():
@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="wan1.3b-97-fp8")
-    ap.add_argument("--quant", choices=["fp8", "none"], default=None, help="override the workload's sparse-branch precision")
+    ap.add_argument("--quant", choices=["fp8", "int8", "none"], default=None, help="override the workload's sparse-branch precision")
     ap.add_argument("--topk", type=float, default=None, help="override the kept fraction of key blocks")
     ap.add_argument("--input-sets", type=int, default=3, help="independent input copies rotated between calls")
     ap.add_argument("--no-dense", action="store_true")
@@ -72,7 +72,7 @@ def cpu_baseline(inp, heads):
     except Exception:
         cores = os.cpu_count() or 1
     w = inp.workload
-    quant = O.QUANT_FP8 if w.quant == "fp8" else O.QUANT_NONE
+    quant = {"none": O.QUANT_NONE, "fp8": O.QUANT_FP8, "int8": O.QUANT_INT8}[w.quant]
     Wq, Wk = inp.router_w[0].astype(np.float64), inp.router_w[1].astype(np.float64)
     t0 = time.perf_counter()
     for h in range(heads):
@@ -106,7 +106,7 @@ def main():
         w = w.replace(topk_frac=args.topk)
     inp = W.generate(w)
     dt = api.SLA2_BF16 if w.dtype == "bf16" else api.SLA2_F32
-    qm = api.SLA2_QUANT_FP8 if w.quant == "fp8" else api.SLA2_QUANT_NONE
+    qm = api.QUANT_MODES[w.quant]
     p = api.make_params(w.B, w.H, w.N, w.d, w.block_q, w.block_kv, w.topk_frac, dtype=dt, quant_mode=qm)
     ksel = api.sla2_num_selected(p)
     sets = []
@@ -160,13 +160,13 @@ def main():
     rest_flops = qk_flops + BH * w.T_m * 2.0 * w.block_q * w.d * w.d     # P V and Q^phi H_i: always bf16
     attn_flops = qk_flops + rest_flops
     attn_ms = prof["attn"][0] / prof["attn"][1]
-    mm = "fp8" if w.quant == "fp8" else "bf16"
+    mm = w.quant if w.quant != "none" else "bf16"
     achieved = attn_flops / (attn_ms * 1e-3) / 1e12
-    if w.quant == "fp8":
+    if w.quant != "none":
         # each product priced at the peak of its own operand type: time-weighted (harmonic) blend
-        peak = attn_flops / (qk_flops / MFMA_PEAK_TFLOPS["fp8"] + rest_flops / MFMA_PEAK_TFLOPS["bf16"])
-        note = ("peak = harmonic blend of dense fp8 MFMA (Q K^T, %.3g TFLOP) and dense bf16 MFMA (P V and the linear "
-                "branch, %.3g TFLOP)" % (qk_flops / 1e12, rest_flops / 1e12))
+        peak = attn_flops / (qk_flops / MFMA_PEAK_TFLOPS[w.quant] + rest_flops / MFMA_PEAK_TFLOPS["bf16"])
+        note = ("peak = harmonic blend of dense %s MFMA (Q K^T, %.3g TFLOP) and dense bf16 MFMA (P V and the linear "
+                "branch, %.3g TFLOP)" % (w.quant, qk_flops / 1e12, rest_flops / 1e12))
     else:
         peak = MFMA_PEAK_TFLOPS["bf16"]
         note = "peak = dense bf16 MFMA"
@@ -181,7 +181,7 @@ def main():
         gbs = qk_bytes / (stages["block_sums"] * 1e-3) / 1e9
         hbm["block_sums"] = {"GB/s": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4), "bytes": qk_bytes}
     if "kv_state" in stages:
-        b = qk_bytes + (BH * w.T_n * w.block_kv * w.d if w.quant == "fp8" else 0)
+        b = qk_bytes + (BH * w.T_n * w.block_kv * w.d if w.quant != "none" else 0)
         gbs = b / (stages["kv_state"] * 1e-3) / 1e9
         hbm["kv_state"] = {"GB/s": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4), "bytes": b}
 

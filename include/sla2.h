@@ -57,8 +57,13 @@ typedef enum { SLA2_F32 = 0, SLA2_BF16 = 1 } sla2_dtype;   /* element type of q,
  *                    dequantisation scale amax/448, both divisions in fp32;
  *                    P rounded to e4m3 after scaling by 2^8; V kept in bf16;
  *                    the softmax denominator uses the un-rounded P.
- *                    Requires dtype = SLA2_BF16. */
-typedef enum { SLA2_QUANT_NONE = 0, SLA2_QUANT_FP8 = 1 } sla2_quant;
+ *                    Requires dtype = SLA2_BF16.
+ *   SLA2_QUANT_INT8  as SLA2_QUANT_FP8 with Q and the smoothed K as symmetric INT8 codes
+ *                    (the other low-bit format Sec. 5 names for Q K^T): stored value =
+ *                    rne(x * (127/amax)) in [-127, 127], dequantisation scale amax/127;
+ *                    the products of codes are exact integers.  P, V and the
+ *                    denominator as in FP8 mode.  Requires dtype = SLA2_BF16. */
+typedef enum { SLA2_QUANT_NONE = 0, SLA2_QUANT_FP8 = 1, SLA2_QUANT_INT8 = 2 } sla2_quant;
 
 #define SLA2_FLAG_NO_SMOOTH_K 1u   /* skip K <- K - colmean(K) (first step of Alg. 2) */
 
@@ -91,8 +96,9 @@ typedef struct sla2_ws_layout {
                                                         operand fragments (bf16 path only): lane l of fragment (mt, ks)
                                                         holds channel 32 mt + l%32, tokens 16 ks + 8 (i/4) + 4 (l/32) + i%4, i = 0..7 */
   size_t z_blocks;  /* float  [BH, T_n, d]   z_j = colsum(K^phi_j) per key block (bf16 path only)        (Alg. 2: z) */
-  size_t k_fp8;     /* uint8  [BH, T_n*block_kv, d]  e4m3 codes of the smoothed K (FP8 mode only; rows >= N are 0) */
-  size_t k_scale;   /* float  [BH, T_n]      dequantisation scale of each key block (FP8 mode only) */
+  size_t k_fp8;     /* uint8  [BH, T_n*block_kv, d]  e4m3 (FP8 mode) or two's-complement int8 (INT8 mode) codes of the
+                       smoothed K; low-bit modes only; rows >= N are 0 */
+  size_t k_scale;   /* float  [BH, T_n]      dequantisation scale of each key block (low-bit modes only) */
   size_t partial;   /* scratch for per-chunk partial sums of h and z */
   size_t total;     /* = sla2_workspace_bytes() */
 } sla2_ws_layout;
@@ -151,7 +157,7 @@ int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, 
 typedef enum {
   SLA2_STAGE_BLOCK_SUMS = 0,  /* pooling sums of Q and K blocks; router weights folded   (Eq. 15-16) */
   SLA2_STAGE_TOPK = 1,        /* projection, scores, row-wise top-k; colmean(K)   (Eq. 16; Alg. 2, smoothing) */
-  SLA2_STAGE_KV_STATE = 2,    /* K^phi, partial h and z, FP8 codes of K    (Alg. 2: K^phi, h, z) */
+  SLA2_STAGE_KV_STATE = 2,    /* K^phi, partial h and z, low-bit codes of K (Alg. 2: K^phi, h, z) */
   SLA2_STAGE_KV_TOTAL = 3,    /* per-head totals of h and z */
   SLA2_STAGE_ATTN = 4,        /* sparse + linear branch + mix              (Alg. 2 block loop, Eq. 13) */
   SLA2_STAGE_DENSE = 5,       /* dense attention comparator */

@@ -16,7 +16,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsla2.so")
 
 SLA2_F32, SLA2_BF16 = 0, 1
-SLA2_QUANT_NONE, SLA2_QUANT_FP8 = 0, 1
+SLA2_QUANT_NONE, SLA2_QUANT_FP8, SLA2_QUANT_INT8 = 0, 1, 2
+QUANT_MODES = {"none": SLA2_QUANT_NONE, "fp8": SLA2_QUANT_FP8, "int8": SLA2_QUANT_INT8}   # workload name -> sla2_quant
 SLA2_FLAG_NO_SMOOTH_K = 1
 SLA2_OK, SLA2_EINVAL, SLA2_EUNSUPPORTED, SLA2_EWORKSPACE, SLA2_EALIAS, SLA2_EHIP = 0, -1, -2, -3, -4, -5
 

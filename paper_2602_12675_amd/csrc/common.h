@@ -22,17 +22,21 @@ typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;   // 16 bytes in flight (a native vector: stays in registers)
 typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
 typedef __attribute__((ext_vector_type(8))) int i32x8;            // operand of the 64-deep FP8 product
+typedef __attribute__((ext_vector_type(4))) int i32x4;            // operand of the 32-deep INT8 product
+typedef __attribute__((ext_vector_type(16))) int i32x16;          // its 32 x 32 accumulator
 
 constexpr int kWave = 64;
 constexpr int kMaxKeyBlocks = 2048;   // router keeps a whole score row in registers
 constexpr float kE4M3Max = 448.0f;
+constexpr float kInt8Max = 127.0f;   // symmetric INT8 code range of Q and K
 constexpr float kLog2e = 1.4426950408889634f;
 
 // Host-side description of one call, derived from sla2_params.
 struct Shape {
   int B, H, N, d, bq, bk;
   int BH, Tm, Tn, k;
-  bool bf16, fp8, smooth, w_per_head, alpha_per_block;
+  bool bf16, smooth, w_per_head, alpha_per_block;
+  int quant;                                 // sla2_quant: 0 none, 1 FP8 e4m3, 2 INT8 codes of Q and K
   // kv precompute: each workgroup reduces `blocks_per_chunk` key blocks; `chunks` per head
   int blocks_per_chunk, chunks;
 };
@@ -64,10 +68,10 @@ hipError_t launch_attn_f32(const Shape& s, const float* q, const float* k, const
 
 hipError_t launch_kv_total(const Shape& s, const float* partial, float* h_total, float* z_total, hipStream_t stream);
 hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_t* v, const double* k_mean,
-                                float* k_stats, float* partial, uint16_t* k_phi, float* z_blocks, uint8_t* k_fp8,
+                                float* k_stats, float* partial, uint16_t* k_phi, float* z_blocks, uint8_t* k_codes,
                                 float* k_scale, hipStream_t stream);
 hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v,
-                            const double* k_mean, const uint16_t* k_phi, const float* z_blocks, const uint8_t* k_fp8,
+                            const double* k_mean, const uint16_t* k_phi, const float* z_blocks, const uint8_t* k_codes,
                             const float* k_scale, const float* h_total, const float* z_total,
                             const int32_t* block_idx, const float* alpha, uint16_t* out, float* lse,
                             hipStream_t stream);

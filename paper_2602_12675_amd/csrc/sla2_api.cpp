@@ -17,13 +17,14 @@ static int make_shape(const sla2_params* p, Shape* s) {
   if (p->B < 1 || p->H < 1 || p->N < 1) return SLA2_EINVAL;
   if (!(p->topk_frac >= 0.0f && p->topk_frac <= 1.0f)) return SLA2_EINVAL;   // also rejects NaN
   if (p->dtype != SLA2_F32 && p->dtype != SLA2_BF16) return SLA2_EINVAL;
-  if (p->quant_mode != SLA2_QUANT_NONE && p->quant_mode != SLA2_QUANT_FP8) return SLA2_EINVAL;
+  if (p->quant_mode != SLA2_QUANT_NONE && p->quant_mode != SLA2_QUANT_FP8 && p->quant_mode != SLA2_QUANT_INT8)
+    return SLA2_EINVAL;
   if (p->router_w_per_head != 0 && p->router_w_per_head != 1) return SLA2_EINVAL;
   if (p->alpha_per_block != 0 && p->alpha_per_block != 1) return SLA2_EINVAL;
   if (p->flags & ~SLA2_FLAG_NO_SMOOTH_K) return SLA2_EINVAL;
   if (p->d != 64 && p->d != 128) return SLA2_EUNSUPPORTED;
   if (!((p->block_q == 64 || p->block_q == 128) && p->block_kv == 64)) return SLA2_EUNSUPPORTED;
-  if (p->quant_mode == SLA2_QUANT_FP8 && p->dtype != SLA2_BF16) return SLA2_EUNSUPPORTED;
+  if (p->quant_mode != SLA2_QUANT_NONE && p->dtype != SLA2_BF16) return SLA2_EUNSUPPORTED;
   if ((long long)p->B * p->H > 65535) return SLA2_EUNSUPPORTED;
   s->B = p->B; s->H = p->H; s->N = p->N; s->d = p->d; s->bq = p->block_q; s->bk = p->block_kv;
   s->BH = p->B * p->H;
@@ -33,7 +34,7 @@ static int make_shape(const sla2_params* p, Shape* s) {
   int k = (int)floor((double)p->topk_frac * (double)s->Tn + 0.5);
   s->k = k < 0 ? 0 : (k > s->Tn ? s->Tn : k);
   s->bf16 = p->dtype == SLA2_BF16;
-  s->fp8 = p->quant_mode == SLA2_QUANT_FP8;
+  s->quant = (int)p->quant_mode;
   s->smooth = !(p->flags & SLA2_FLAG_NO_SMOOTH_K);
   s->w_per_head = p->router_w_per_head != 0;
   s->alpha_per_block = p->alpha_per_block != 0;
@@ -64,8 +65,8 @@ static void make_layout(const Shape& s, sla2_ws_layout* L) {
   L->k_stats = take(BH * (size_t)s.N * sizeof(float));
   L->k_phi = take(s.bf16 ? BH * (size_t)s.Tn * s.bk * d * 2 : 0);
   L->z_blocks = take(s.bf16 ? BH * (size_t)s.Tn * d * sizeof(float) : 0);
-  L->k_fp8 = take(s.fp8 ? BH * (size_t)s.Tn * s.bk * d : 0);
-  L->k_scale = take(s.fp8 ? BH * (size_t)s.Tn * sizeof(float) : 0);
+  L->k_fp8 = take(s.quant ? BH * (size_t)s.Tn * s.bk * d : 0);
+  L->k_scale = take(s.quant ? BH * (size_t)s.Tn * sizeof(float) : 0);
   L->partial = take(BH * (size_t)s.chunks * (d * d + d) * sizeof(float));
   L->total = off;
 }

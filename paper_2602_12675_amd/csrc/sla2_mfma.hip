@@ -30,6 +30,12 @@ __device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// four values already scaled into [-127, 127] -> their nearest integers (ties to even), one per byte
+__device__ __forceinline__ int pack_int8(float a, float b, float c, float d) {
+  const int ia = (int)__builtin_rintf(a), ib = (int)__builtin_rintf(b), ic = (int)__builtin_rintf(c), id = (int)__builtin_rintf(d);
+  return (ia & 0xff) | ((ib & 0xff) << 8) | ((ic & 0xff) << 16) | (id << 24);
+}
+
 // How the (D/32)^2 32x32 tiles of the d x d state h are spread over NW waves: wave w owns
 // kMtw x kNtw tiles starting at (mt0, nt0).
 template <int D, int NW> struct HSplit {
@@ -54,13 +60,13 @@ __device__ __forceinline__ size_t kphi_offset(size_t block, int mt, int ks, int 
 // =============================================================================================
 // kv_state_bf16
 // =============================================================================================
-template <int D, bool FP8>
+template <int D, int QUANT>   // QUANT: 0 none, 1 FP8 e4m3 codes of K - colmean K, 2 INT8 codes
 __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __restrict__ k,
                                                             const uint16_t* __restrict__ v,
                                                             const double* __restrict__ k_mean,
                                                             float* __restrict__ k_stats, float* __restrict__ partial,
                                                             uint16_t* __restrict__ k_phi, float* __restrict__ z_blocks,
-                                                            uint8_t* __restrict__ k_fp8, float* __restrict__ k_scale,
+                                                            uint8_t* __restrict__ k_codes, float* __restrict__ k_scale,
                                                             int N, int Tn, int chunks, int blocks_per_chunk) {
   constexpr int LD = TileGeom<D>::kLd;
   typedef HSplit<D, 4> HS;
@@ -143,17 +149,18 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
         lnz2[t] = ok ? lnz * kLog2e : INFINITY;
         if (ok) k_stats[(size_t)bh * N + t0 + t] = lnz;
       }
-      if (FP8) {
+      if (QUANT) {
         // one scale per key block: amax over the block's existing tokens (Sec. 5; see sla2.h)
+        constexpr float kCodeMax = QUANT == 2 ? kInt8Max : kE4M3Max;
         if (!ok) amax = 0.f;
 #pragma unroll
         for (int o = 1; o < kWave; o <<= 1) amax = fmaxf(amax, __shfl_xor(amax, o));
         if (lane == 0) red[w] = amax;
         __syncthreads();
         amax = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-        const float inv = amax > 0.f ? kE4M3Max / amax : 1.f;
-        if (tid == 0) k_scale[(size_t)bh * Tn + j] = amax > 0.f ? amax / kE4M3Max : 1.f;
-        uint8_t* dst = k_fp8 + (((size_t)bh * Tn + j) * kTileTokens + t) * D;
+        const float inv = amax > 0.f ? kCodeMax / amax : 1.f;
+        if (tid == 0) k_scale[(size_t)bh * Tn + j] = amax > 0.f ? amax / kCodeMax : 1.f;
+        uint8_t* dst = k_codes + (((size_t)bh * Tn + j) * kTileTokens + t) * D;
 #pragma unroll
         for (int i = 0; i < D / 32; i++) {
           const int c0 = 8 * (sub + 4 * i);
@@ -161,11 +168,16 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
           if (ok) {
             float y[8];
 #pragma unroll
-            for (int e = 0; e < 8; e++) y[e] = fminf(fmaxf(x[8 * i + e] * inv, -kE4M3Max), kE4M3Max);
-            lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], lo, false);
-            lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], lo, true);
-            hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], hi, false);
-            hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], hi, true);
+            for (int e = 0; e < 8; e++) y[e] = fminf(fmaxf(x[8 * i + e] * inv, -kCodeMax), kCodeMax);
+            if constexpr (QUANT == 2) {
+              lo = pack_int8(y[0], y[1], y[2], y[3]);
+              hi = pack_int8(y[4], y[5], y[6], y[7]);
+            } else {
+              lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], lo, false);
+              lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], lo, true);
+              hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], hi, false);
+              hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], hi, true);
+            }
           }
           *reinterpret_cast<int2*>(dst + c0) = make_int2(lo, hi);
         }
@@ -222,8 +234,8 @@ hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_
 #define SLA2_KV(DD, F8)                                                                                        \
   kv_state_bf16_kernel<DD, F8><<<grid, 256, 0, stream>>>(k, v, k_mean, k_stats, partial, k_phi, z_blocks, k_fp8, \
                                                          k_scale, s.N, s.Tn, s.chunks, s.blocks_per_chunk)
-  if (s.d == 128) { if (s.fp8) SLA2_KV(128, true); else SLA2_KV(128, false); }
-  else            { if (s.fp8) SLA2_KV(64, true);  else SLA2_KV(64, false); }
+  if (s.d == 128) { if (s.quant == 2) SLA2_KV(128, 2); else if (s.quant == 1) SLA2_KV(128, 1); else SLA2_KV(128, 0); }
+  else            { if (s.quant == 2) SLA2_KV(64, 2);  else if (s.quant == 1) SLA2_KV(64, 1);  else SLA2_KV(64, 0); }
 #undef SLA2_KV
   return hipGetLastError();
 }
@@ -232,7 +244,7 @@ hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_
 // attn_mfma
 // =============================================================================================
 constexpr int kXcds = 8;
-enum AttnMode { kSparseBf16 = 0, kSparseFp8 = 1, kDenseBf16 = 2 };
+enum AttnMode { kSparseBf16 = 0, kSparseFp8 = 1, kDenseBf16 = 2, kSparseInt8 = 3 };
 
 __device__ __forceinline__ f32x16 mfma_fp8(long a, long b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, b, c, 0, 0, 0);
@@ -330,6 +342,7 @@ __device__ __forceinline__ void wait_lgkmcnt(int n) {
     case 4: asm volatile("s_waitcnt lgkmcnt(4)"); break;
     case 5: asm volatile("s_waitcnt lgkmcnt(5)"); break;
     case 6: asm volatile("s_waitcnt lgkmcnt(6)"); break;
+    case 7: asm volatile("s_waitcnt lgkmcnt(7)"); break;
     default: asm volatile("s_waitcnt lgkmcnt(0)"); break;
   }
 }
@@ -338,11 +351,13 @@ template <int D, int BQ, int MODE>
 __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const double* __restrict__ k_mean, const uint16_t* __restrict__ k_phi, const float* __restrict__ z_blocks,
-    const uint8_t* __restrict__ k_fp8, const float* __restrict__ k_scale, const float* __restrict__ h_total,
+    const uint8_t* __restrict__ k_codes, const float* __restrict__ k_scale, const float* __restrict__ h_total,
     const float* __restrict__ z_total, const int32_t* __restrict__ block_idx, const float* __restrict__ alpha,
     uint16_t* __restrict__ out, float* __restrict__ lse, int H, int N, int Tm, int Tn, int ksel, int alpha_per_block,
     int total_blocks) {
-  constexpr bool DENSE = MODE == kDenseBf16, FP8 = MODE == kSparseFp8;
+  // FP8 below means "8-bit codes of Q and K": everything the two low-bit modes share.  INT8 marks the
+  // places where the integer mode differs (the quantiser of Q and the Q K^T product).
+  constexpr bool DENSE = MODE == kDenseBf16, INT8 = MODE == kSparseInt8, FP8 = MODE == kSparseFp8 || INT8;
   constexpr int NW = BQ / 32, NT = NW * kWave;
   constexpr int LD = TileGeom<D>::kLd;
   constexpr int KS = D / 16;            // contraction steps over the head dimension
@@ -391,7 +406,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   // tile s: global memory -> LDS buffer `buf`, no registers involved (completion: vmcnt)
   auto dma = [&](int j, int buf) {
     const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
-    if constexpr (FP8) dma_tile8<D, NW>(k_fp8 + (blk0 + j) * kTileTokens * D, kbuf(buf), w, lane);
+    if constexpr (FP8) dma_tile8<D, NW>(k_codes + (blk0 + j) * kTileTokens * D, kbuf(buf), w, lane);
     else if (kManual && valid == kTileTokens) dma_tile_full<D, NW>(kh + (size_t)t0 * D, reinterpret_cast<uint16_t*>(kbuf(buf)), w, lane);
     else dma_tile<D, NW>(kh + (size_t)t0 * D, valid, reinterpret_cast<uint16_t*>(kbuf(buf)), w, lane);
     if (kManual && valid == kTileTokens) dma_tile_full<D, NW>(vh + (size_t)t0 * D, vbuf(buf), w, lane);
@@ -407,9 +422,11 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     const uint16_t* src = qh + (size_t)(row0 + r) * D;
     // bf16 product: fragment ks = columns 16 ks + 8 g + 0..7.  FP8 product (64 deep): the lane's
     // operand of step ks2 is columns 64 ks2 + 32 g + 0..31, held as fragments 4 ks2 + 0..3.
+    // INT8 product (32 deep): columns 32 ks4 + 16 g + 0..15, fragments 2 ks4 + 0..1.
 #pragma unroll
     for (int ks = 0; ks < KS; ks++)
-      qf[ks] = *reinterpret_cast<const bf16x8*>(src + (FP8 ? 64 * (ks / 4) + 32 * g + 8 * (ks % 4) : 16 * ks + 8 * g));
+      qf[ks] = *reinterpret_cast<const bf16x8*>(
+          src + (INT8 ? 32 * (ks / 2) + 16 * g + 8 * (ks % 2) : FP8 ? 64 * (ks / 4) + 32 * g + 8 * (ks % 4) : 16 * ks + 8 * g));
   }
   // Everything issued so far is settled here, on every path into the main loop; a pending load
   // left over from the prologue would otherwise put a vmcnt wait in front of every use of a Q
@@ -431,18 +448,24 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     amax = red[0];
 #pragma unroll
     for (int x = 1; x < NW; x++) amax = fmaxf(amax, red[x]);
-    const float inv = amax > 0.f ? kE4M3Max / amax : 1.f;
-    s_q = amax > 0.f ? amax / kE4M3Max : 1.f;
+    constexpr float kCodeMax = INT8 ? kInt8Max : kE4M3Max;
+    const float inv = amax > 0.f ? kCodeMax / amax : 1.f;
+    s_q = amax > 0.f ? amax / kCodeMax : 1.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
       float y[8];
 #pragma unroll
-      for (int e = 0; e < 8; e++) y[e] = fminf(fmaxf((float)qf[ks][e] * inv, -kE4M3Max), kE4M3Max);
+      for (int e = 0; e < 8; e++) y[e] = fminf(fmaxf((float)qf[ks][e] * inv, -kCodeMax), kCodeMax);
       int lo = 0, hi = 0;
-      lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], lo, false);
-      lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], lo, true);
-      hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], hi, false);
-      hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], hi, true);
+      if constexpr (INT8) {
+        lo = pack_int8(y[0], y[1], y[2], y[3]);
+        hi = pack_int8(y[4], y[5], y[6], y[7]);
+      } else {
+        lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], lo, false);
+        lo = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], lo, true);
+        hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[4], y[5], hi, false);
+        hi = __builtin_amdgcn_cvt_pk_fp8_f32(y[6], y[7], hi, true);
+      }
       qf8[ks] = (long)(((unsigned long)(unsigned)hi << 32) | (unsigned)lo);
     }
   }
@@ -506,7 +529,41 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     for (int mt = 0; mt < 2; mt++)
 #pragma unroll
       for (int e = 0; e < 16; e++) sacc[mt][e] = 0.f;
-    if constexpr (FP8) {
+    if constexpr (INT8) {
+      // 32-deep integer products (v_mfma_i32_32x32x32_i8: lane l holds row l % 32, contraction indices
+      // 16 (l / 32) + 0..15): the operand of (step ks4, key half mt) is 16 consecutive codes of key row
+      // 32 mt + l % 32 - one 16-byte read at (address of step 0) ^ 32 ks4 in the pair-swizzled tile.
+      // Sums of 128 products of codes stay below 2^21: exact in the int32 accumulator and in fp32.
+      constexpr int KS4 = D / 32;
+      const unsigned ka = lds_address(kbuf(buf) + SL8::offset(lane % 32, 16 * g));
+      u32x4 kq[KS4][2];
+#pragma unroll
+      for (int ks4 = 0; ks4 < KS4; ks4++) {
+        kq[ks4][0] = lds_read16_untracked<0>(ka ^ (32u * ks4));
+        kq[ks4][1] = lds_read16_untracked<32 * D>(ka ^ (32u * ks4));
+      }
+      i32x16 iacc[2];
+#pragma unroll
+      for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) iacc[mt][e] = 0;
+#pragma unroll
+      for (int ks4 = 0; ks4 < KS4; ks4++)
+#pragma unroll
+        for (int mt = 0; mt < 2; mt++) {
+          wait_lgkmcnt(2 * (KS4 - 1 - ks4) + 1 - mt);
+          settle(kq[ks4][mt]);
+          const u32x4 kk = kq[ks4][mt];
+          const i32x4 a = {(int)kk[0], (int)kk[1], (int)kk[2], (int)kk[3]};
+          const i32x4 b = {(int)(unsigned)((unsigned long)qf8[2 * ks4]), (int)(unsigned)((unsigned long)qf8[2 * ks4] >> 32),
+                           (int)(unsigned)((unsigned long)qf8[2 * ks4 + 1]), (int)(unsigned)((unsigned long)qf8[2 * ks4 + 1] >> 32)};
+          iacc[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, iacc[mt], 0, 0, 0);
+        }
+#pragma unroll
+      for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+        for (int e = 0; e < 16; e++) sacc[mt][e] = (float)iacc[mt][e];
+    } else if constexpr (FP8) {
       // 64-deep products: the operand of (step ks2, key half mt) is 32 consecutive codes of key row
       // 32 mt + l % 32, two 16-byte reads.  The swizzle is an XOR on the pair bits of the address,
       // so step ks2 sits at (address of step 0) ^ 64 ks2; all reads of a tile are issued up front.
@@ -825,7 +882,7 @@ struct AttnArgs {
 
 template <int D, int BQ, int MODE>
 static hipError_t launch_attn_t(const Shape& s, const AttnArgs& a, hipStream_t stream) {
-  constexpr int smem = AttnSmem<D, BQ, MODE == kSparseFp8>::kBytes;
+  constexpr int smem = AttnSmem<D, BQ, MODE == kSparseFp8 || MODE == kSparseInt8>::kBytes;
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<D, BQ, MODE>,
@@ -849,8 +906,9 @@ hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k
                             hipStream_t stream) {
   AttnArgs a{q, k, v, k_mean, k_phi, z_blocks, k_fp8, k_scale, h_total, z_total, block_idx, alpha, out, lse};
 #define SLA2_ATTN(DD, QQ)                                                  \
-  return s.fp8 ? launch_attn_t<DD, QQ, kSparseFp8>(s, a, stream)           \
-               : launch_attn_t<DD, QQ, kSparseBf16>(s, a, stream)
+  return s.quant == 2 ? launch_attn_t<DD, QQ, kSparseInt8>(s, a, stream)   \
+       : s.quant == 1 ? launch_attn_t<DD, QQ, kSparseFp8>(s, a, stream)    \
+                      : launch_attn_t<DD, QQ, kSparseBf16>(s, a, stream)
   if (s.d == 128 && s.bq == 128) SLA2_ATTN(128, 128);
   if (s.d == 128 && s.bq == 64) SLA2_ATTN(128, 64);
   if (s.d == 64 && s.bq == 128) SLA2_ATTN(64, 128);

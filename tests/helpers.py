@@ -12,7 +12,7 @@ def oracle_heads(inp: W.Inputs, quant=None, smooth=True, alpha=None, heads=None,
                  topk_frac=None):
     """Oracle results for the chosen (b, h) pairs: dict (b, h) -> forward_head dict."""
     w = inp.workload
-    quant = {"none": O.QUANT_NONE, "fp8": O.QUANT_FP8}[w.quant] if quant is None else quant
+    quant = {"none": O.QUANT_NONE, "fp8": O.QUANT_FP8, "int8": O.QUANT_INT8}[w.quant] if quant is None else quant
     Wq = inp.router_w[0].astype(np.float64)
     Wk = inp.router_w[1].astype(np.float64)
     alpha = inp.alpha if alpha is None else alpha
@@ -56,7 +56,7 @@ def rel_l2(a, b):
 def run_forward(api, torch, inp, flags=0, alpha=None, alpha_per_block=0, want_lse=True):
     w = inp.workload
     dt = api.SLA2_BF16 if w.dtype == "bf16" else api.SLA2_F32
-    qm = api.SLA2_QUANT_FP8 if w.quant == "fp8" else api.SLA2_QUANT_NONE
+    qm = api.QUANT_MODES[w.quant]
     p = api.make_params(w.B, w.H, w.N, w.d, w.block_q, w.block_kv, w.topk_frac, dtype=dt, quant_mode=qm,
                         alpha_per_block=alpha_per_block, flags=flags)
     q, k, v = (api.to_device(a, dt) for a in (inp.q, inp.k, inp.v))

@@ -16,7 +16,7 @@ from paper_2602_12675_amd import workloads as W
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
 
-TOL = {"none": 2e-2, "fp8": 5e-2}
+TOL = {"none": 2e-2, "fp8": 5e-2, "int8": 5e-2}
 
 
 def sampled_check(w, heads, n_blocks=6, seed=0):
@@ -50,11 +50,15 @@ def test_wan_1p3b_fp8_97():
     sampled_check(W.WAN_1P3B_97_FP8, heads=[(0, 0), (0, 5), (0, 11)])
 
 
+def test_wan_1p3b_int8_97():
+    sampled_check(W.WAN_1P3B_97_FP8.replace(name="wan1.3b-97-int8", quant="int8"), heads=[(0, 2), (0, 9)])
+
+
 def test_wan_14b_fp8_97():
     sampled_check(W.WAN_14B_97_FP8, heads=[(0, 0), (0, 39)], n_blocks=5)
 
 
-@pytest.mark.parametrize("quant,topk", [("none", 0.15), ("fp8", 0.01), ("fp8", 0.10)])
+@pytest.mark.parametrize("quant,topk", [("none", 0.15), ("fp8", 0.01), ("fp8", 0.10), ("int8", 0.05)])
 def test_sweep_shape_ragged_75601(quant, topk):
     """B = 2, N = 75,601 (a 17-token last key block and an 81-token last query
     block); heads reduced to 4 to bound the test's memory and time, the kernels
