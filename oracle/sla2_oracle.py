@@ -46,6 +46,7 @@ import numpy as np
 QUANT_NONE = 0
 QUANT_FP8 = 1
 QUANT_INT8 = 2
+QUANT_FP8_V = 3           # FP8 mode with V quantised as well (Alg. 2 as printed: quant(P) quant(V_j))
 
 E4M3_MAX = 448.0          # largest finite magnitude of the OCP e4m3 format
 INT8_MAX = 127.0          # symmetric int8 range used for Q and K codes
@@ -240,7 +241,7 @@ def smooth_k_f32(K: np.ndarray) -> np.ndarray:
 
 
 def sparse_branch_lowbit(Q, K, V, sel, b_q: int, b_k: int, *, smooth: bool = True,
-                         q_blocks=None, quant_block=None):
+                         q_blocks=None, quant_block=None, quant_v: bool = False):
     """Sparse branch with low-bit Q, K and P (Sec. 5), following the block loop
     of Alg. 2 step by step, because with a rounded P the result depends on the
     running maximum and therefore on the order of the blocks:
@@ -264,7 +265,12 @@ def sparse_branch_lowbit(Q, K, V, sel, b_q: int, b_k: int, *, smooth: bool = Tru
     `quant_block` is the quantiser of Q and K blocks: quant_block_e4m3 (the
     default) or quant_block_int8; everything after the codes - the exact
     product of codes, the two scales, the rounding of P - is the same.
-    Returns (O_s, L) like sparse_branch."""
+    `quant_v` takes the second product the way Alg. 2 prints it,
+    dequant(quant(P) quant(V_j)): V_j is quantised like a key block (e4m3, one
+    scale per b_k x d block over its existing tokens, quant_block_e4m3) and
+        O = diag(exp(m - m_new)) O + (Ptilde Vhat_j) s_Vj ;
+    the linear branch keeps the input V (Alg. 2 forms h_j from the unquantised
+    V_j).  Returns (O_s, L) like sparse_branch."""
     if quant_block is None:
         quant_block = quant_block_e4m3
     N, d = Q.shape
@@ -294,7 +300,11 @@ def sparse_branch_lowbit(Q, K, V, sel, b_q: int, b_k: int, *, smooth: bool = Tru
             corr = np.exp(m - m_new)
             l = corr * l + P.sum(axis=1, keepdims=True)
             Pt = e4m3_round((P * 2.0 ** P_SCALE_LOG2).astype(np.float32)).astype(np.float64) / 2.0 ** P_SCALE_LOG2
-            acc = corr * acc + Pt @ V[c0:c1]
+            if quant_v:
+                Vhat, sV = quant_block_e4m3(V[c0:c1].astype(np.float32))
+                acc = corr * acc + (Pt @ Vhat.astype(np.float64)) * float(sV)
+            else:
+                acc = corr * acc + Pt @ V[c0:c1]
             m = m_new
         if len(sel[i]):
             O[r0:r1] = acc / l
@@ -378,6 +388,8 @@ def forward_head(Q, K, V, Wq, Wk, alpha, topk_frac: float, b_q: int, b_k: int,
     elif quant == QUANT_INT8:
         O_s, L = sparse_branch_lowbit(Q, K, V, sel, b_q, b_k, smooth=smooth, q_blocks=qb,
                                       quant_block=quant_block_int8)
+    elif quant == QUANT_FP8_V:
+        O_s, L = sparse_branch_lowbit(Q, K, V, sel, b_q, b_k, smooth=smooth, q_blocks=qb, quant_v=True)
     else:
         raise ValueError("unknown quant mode")
     O_l, H, Z = linear_branch(Q, Ks, V, sel, b_q, b_k, q_blocks=qb)

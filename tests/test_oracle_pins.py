@@ -491,6 +491,42 @@ def test_int8_branch_close_to_exact_and_tighter_than_fp8_scores():
     assert np.array_equal(i8["sel"], ex["sel"])                     # the router never sees the codes
 
 
+# ---- FP8 V in the second product (Alg. 2 as printed) ------------------------ #
+def test_fp8v_branch_reduces_to_exact_when_quantisers_are_exact(monkeypatch):
+    N, d, bq, bk = 150, 8, 32, 16
+    Q, K, V, Wq, Wk = rand_head(25, N, d)
+    Q, K, V = (a.astype(np.float32).astype(np.float64) for a in (Q, K, V))
+    sel = O.forward_head(Q, K, V, Wq, Wk, 1.0, 0.3, bq, bk)["sel"]
+    monkeypatch.setattr(O, "e4m3_round", lambda x: np.asarray(x, dtype=np.float32))
+    # an "exact quantiser" with a scale that is not 1: the scale must come back exactly once
+    monkeypatch.setattr(O, "quant_block_e4m3", lambda X: (np.asarray(X, np.float32) * np.float32(4), np.float32(0.25)))
+    lo = O.forward_head(Q, K, V, Wq, Wk, 1.0, 0.3, bq, bk, quant=O.QUANT_FP8_V, sel=sel)
+    ex = O.forward_head(Q, K, V, Wq, Wk, 1.0, 0.3, bq, bk, sel=sel)
+    np.testing.assert_allclose(lo["O"], ex["O"], rtol=0, atol=5e-6)
+    np.testing.assert_allclose(lo["L"], ex["L"], rtol=0, atol=5e-6)
+
+
+def test_fp8v_differs_from_fp8_only_through_v_and_leaves_the_linear_branch_alone():
+    N, d, bq, bk = 512, 64, 64, 64
+    Q, K, V, Wq, Wk = rand_head(21, N, d)
+    f8 = O.forward_head(Q, K, V, Wq, Wk, 0.4, 0.25, bq, bk, quant=O.QUANT_FP8)
+    f8v = O.forward_head(Q, K, V, Wq, Wk, 0.4, 0.25, bq, bk, quant=O.QUANT_FP8_V)
+    ex = O.forward_head(Q, K, V, Wq, Wk, 0.4, 0.25, bq, bk)
+    np.testing.assert_array_equal(f8v["O_l"], f8["O_l"])          # h_j is built from the input V
+    np.testing.assert_array_equal(f8v["L"], f8["L"])              # the scores never see V
+    rel = lambda a, b: np.linalg.norm(a - b) / np.linalg.norm(b)
+    e8, e8v = rel(f8["O_s"], ex["O_s"]), rel(f8v["O_s"], ex["O_s"])
+    assert e8 < e8v < 5e-2, (e8, e8v)                             # one more rounding, still small
+    # a V that is exactly representable (all entries on the e4m3 grid after its block scale) changes nothing
+    Vg = np.sign(V) * 2.0 ** np.round(np.log2(np.abs(V) + 1e-30))       # powers of two, spread < 2^15 per block
+    Vg = np.clip(Vg, -2.0, 2.0)
+    Vg[np.abs(Vg) < 2.0 ** -4] = 2.0 ** -4
+    Vg[::bk] = 3.5                                                        # every block's amax, exactly on the grid: scale 2^-7
+    a = O.forward_head(Q, K, Vg, Wq, Wk, 1.0, 0.25, bq, bk, quant=O.QUANT_FP8)
+    b = O.forward_head(Q, K, Vg, Wq, Wk, 1.0, 0.25, bq, bk, quant=O.QUANT_FP8_V)
+    np.testing.assert_allclose(b["O"], a["O"], rtol=1e-12, atol=1e-12)
+
+
 # ---- Table 1: the shapes behind the dense-equivalent FLOP count ----------- #
 def test_table1_flops_confirm_workload_shapes():
     import os
