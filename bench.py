@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the SLA2 forward pass on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--quant fp8|int8|none]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--quant fp8|int8|fp8v|none]
 
 One "step" is one sla2_forward call (router -> kv state -> fused sparse + linear +
 mix) on a synthetic Wan2.1-1.3B-shaped input set (B=1, H=12, N=32760, d=128,
@@ -34,7 +34,7 @@ def parse():
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="wan1.3b-97-fp8")
-    ap.add_argument("--quant", choices=["fp8", "int8", "none"], default=None, help="override the workload's sparse-branch precision")
+    ap.add_argument("--quant", choices=["fp8", "int8", "fp8v", "none"], default=None, help="override the workload's sparse-branch precision")
     ap.add_argument("--topk", type=float, default=None, help="override the kept fraction of key blocks")
     ap.add_argument("--input-sets", type=int, default=3, help="independent input copies rotated between calls")
     ap.add_argument("--no-dense", action="store_true")
@@ -72,7 +72,7 @@ def cpu_baseline(inp, heads):
     except Exception:
         cores = os.cpu_count() or 1
     w = inp.workload
-    quant = {"none": O.QUANT_NONE, "fp8": O.QUANT_FP8, "int8": O.QUANT_INT8}[w.quant]
+    quant = {"none": O.QUANT_NONE, "fp8": O.QUANT_FP8, "int8": O.QUANT_INT8, "fp8v": O.QUANT_FP8_V}[w.quant]
     Wq, Wk = inp.router_w[0].astype(np.float64), inp.router_w[1].astype(np.float64)
     t0 = time.perf_counter()
     for h in range(heads):
@@ -156,17 +156,20 @@ def main():
 
     BH, esz = w.B * w.H, (2 if w.dtype == "bf16" else 4)
     tile_iters = BH * w.T_m * ksel
-    qk_flops = tile_iters * 2.0 * w.block_q * w.block_kv * w.d           # Q K^T: fp8 products in fp8 mode
-    rest_flops = qk_flops + BH * w.T_m * 2.0 * w.block_q * w.d * w.d     # P V and Q^phi H_i: always bf16
-    attn_flops = qk_flops + rest_flops
+    qk_flops = tile_iters * 2.0 * w.block_q * w.block_kv * w.d           # Q K^T: 8-bit products in the low-bit modes
+    lin_flops = BH * w.T_m * 2.0 * w.block_q * w.d * w.d                 # Q^phi H_i: always bf16
+    attn_flops = 2.0 * qk_flops + lin_flops                              # + P V, same count as Q K^T
+    low_flops = {"none": 0.0, "fp8": qk_flops, "int8": qk_flops, "fp8v": 2.0 * qk_flops}[w.quant]
+    rest_flops = attn_flops - low_flops
     attn_ms = prof["attn"][0] / prof["attn"][1]
-    mm = w.quant if w.quant != "none" else "bf16"
+    mm = {"none": "bf16", "fp8v": "fp8"}.get(w.quant, w.quant)
     achieved = attn_flops / (attn_ms * 1e-3) / 1e12
     if w.quant != "none":
         # each product priced at the peak of its own operand type: time-weighted (harmonic) blend
-        peak = attn_flops / (qk_flops / MFMA_PEAK_TFLOPS[w.quant] + rest_flops / MFMA_PEAK_TFLOPS["bf16"])
-        note = ("peak = harmonic blend of dense %s MFMA (Q K^T, %.3g TFLOP) and dense bf16 MFMA (P V and the linear "
-                "branch, %.3g TFLOP)" % (w.quant, qk_flops / 1e12, rest_flops / 1e12))
+        low = "int8" if w.quant == "int8" else "fp8"
+        peak = attn_flops / (low_flops / MFMA_PEAK_TFLOPS[low] + rest_flops / MFMA_PEAK_TFLOPS["bf16"])
+        note = ("peak = harmonic blend of dense %s MFMA (%s, %.3g TFLOP) and dense bf16 MFMA (the rest, %.3g TFLOP)"
+                % (low, "Q K^T and P V" if w.quant == "fp8v" else "Q K^T", low_flops / 1e12, rest_flops / 1e12))
     else:
         peak = MFMA_PEAK_TFLOPS["bf16"]
         note = "peak = dense bf16 MFMA"
@@ -181,7 +184,7 @@ def main():
         gbs = qk_bytes / (stages["block_sums"] * 1e-3) / 1e9
         hbm["block_sums"] = {"GB/s": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4), "bytes": qk_bytes}
     if "kv_state" in stages:
-        b = qk_bytes + (BH * w.T_n * w.block_kv * w.d if w.quant != "none" else 0)
+        b = qk_bytes + BH * w.T_n * w.block_kv * w.d * {"none": 0, "fp8v": 2}.get(w.quant, 1)
         gbs = b / (stages["kv_state"] * 1e-3) / 1e9
         hbm["kv_state"] = {"GB/s": round(gbs, 1), "frac": round(gbs / HBM_PEAK_GBS, 4), "bytes": b}
 

@@ -62,8 +62,12 @@ typedef enum { SLA2_F32 = 0, SLA2_BF16 = 1 } sla2_dtype;   /* element type of q,
  *                    (the other low-bit format Sec. 5 names for Q K^T): stored value =
  *                    rne(x * (127/amax)) in [-127, 127], dequantisation scale amax/127;
  *                    the products of codes are exact integers.  P, V and the
- *                    denominator as in FP8 mode.  Requires dtype = SLA2_BF16. */
-typedef enum { SLA2_QUANT_NONE = 0, SLA2_QUANT_FP8 = 1, SLA2_QUANT_INT8 = 2 } sla2_quant;
+ *                    denominator as in FP8 mode.  Requires dtype = SLA2_BF16.
+ *   SLA2_QUANT_FP8_V as SLA2_QUANT_FP8, and the second product as Alg. 2 prints it,
+ *                    dequant(quant(P) quant(V_j)): V_j in e4m3 with one scale per b_kv x d block
+ *                    (same rule as for K, over the block's existing tokens), P V on the FP8
+ *                    matrix product.  The linear branch keeps the input V.  Requires dtype = SLA2_BF16. */
+typedef enum { SLA2_QUANT_NONE = 0, SLA2_QUANT_FP8 = 1, SLA2_QUANT_INT8 = 2, SLA2_QUANT_FP8_V = 3 } sla2_quant;
 
 #define SLA2_FLAG_NO_SMOOTH_K 1u   /* skip K <- K - colmean(K) (first step of Alg. 2) */
 
@@ -99,6 +103,11 @@ typedef struct sla2_ws_layout {
   size_t k_fp8;     /* uint8  [BH, T_n*block_kv, d]  e4m3 (FP8 mode) or two's-complement int8 (INT8 mode) codes of the
                        smoothed K; low-bit modes only; rows >= N are 0 */
   size_t k_scale;   /* float  [BH, T_n]      dequantisation scale of each key block (low-bit modes only) */
+  size_t v_fp8;     /* uint8  [BH, T_n, d, block_kv]  e4m3 codes of V, one d x 64 tile per key block, transposed
+                       (channel-major) with the 64 tokens of a row in the order the FP8 product consumes them:
+                       byte 32 g + b of a row holds token 32 (b / 16) + 8 ((b % 16) / 4) + 4 g + b % 4
+                       (g = 0, 1; b = 0..31).  SLA2_QUANT_FP8_V only; tokens >= N are 0 */
+  size_t v_scale;   /* float  [BH, T_n]      dequantisation scale of each V block (SLA2_QUANT_FP8_V only) */
   size_t partial;   /* scratch for per-chunk partial sums of h and z */
   size_t total;     /* = sla2_workspace_bytes() */
 } sla2_ws_layout;

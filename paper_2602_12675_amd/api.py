@@ -16,8 +16,9 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsla2.so")
 
 SLA2_F32, SLA2_BF16 = 0, 1
-SLA2_QUANT_NONE, SLA2_QUANT_FP8, SLA2_QUANT_INT8 = 0, 1, 2
-QUANT_MODES = {"none": SLA2_QUANT_NONE, "fp8": SLA2_QUANT_FP8, "int8": SLA2_QUANT_INT8}   # workload name -> sla2_quant
+SLA2_QUANT_NONE, SLA2_QUANT_FP8, SLA2_QUANT_INT8, SLA2_QUANT_FP8_V = 0, 1, 2, 3
+QUANT_MODES = {"none": SLA2_QUANT_NONE, "fp8": SLA2_QUANT_FP8, "int8": SLA2_QUANT_INT8,
+               "fp8v": SLA2_QUANT_FP8_V}   # workload name -> sla2_quant
 SLA2_FLAG_NO_SMOOTH_K = 1
 SLA2_OK, SLA2_EINVAL, SLA2_EUNSUPPORTED, SLA2_EWORKSPACE, SLA2_EALIAS, SLA2_EHIP = 0, -1, -2, -3, -4, -5
 
@@ -41,7 +42,7 @@ class WsLayout(ctypes.Structure):
     """struct sla2_ws_layout"""
     _fields_ = [(n, ctypes.c_size_t) for n in
                 ("q_sum", "k_sum", "k_mean", "router_m", "block_idx", "h_total", "z_total",
-                 "k_stats", "k_phi", "z_blocks", "k_fp8", "k_scale", "partial", "total")]
+                 "k_stats", "k_phi", "z_blocks", "k_fp8", "k_scale", "v_fp8", "v_scale", "partial", "total")]
 
 
 if not os.path.exists(LIB_PATH):

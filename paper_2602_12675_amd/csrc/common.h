@@ -36,7 +36,7 @@ struct Shape {
   int B, H, N, d, bq, bk;
   int BH, Tm, Tn, k;
   bool bf16, smooth, w_per_head, alpha_per_block;
-  int quant;                                 // sla2_quant: 0 none, 1 FP8 e4m3, 2 INT8 codes of Q and K
+  int quant;                                 // sla2_quant: 0 none, 1 FP8 e4m3, 2 INT8 codes of Q and K, 3 FP8 with V in e4m3 too
   // kv precompute: each workgroup reduces `blocks_per_chunk` key blocks; `chunks` per head
   int blocks_per_chunk, chunks;
 };
@@ -69,10 +69,11 @@ hipError_t launch_attn_f32(const Shape& s, const float* q, const float* k, const
 hipError_t launch_kv_total(const Shape& s, const float* partial, float* h_total, float* z_total, hipStream_t stream);
 hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_t* v, const double* k_mean,
                                 float* k_stats, float* partial, uint16_t* k_phi, float* z_blocks, uint8_t* k_codes,
-                                float* k_scale, hipStream_t stream);
+                                float* k_scale, uint8_t* v_codes, float* v_scale, hipStream_t stream);
 hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v,
                             const double* k_mean, const uint16_t* k_phi, const float* z_blocks, const uint8_t* k_codes,
-                            const float* k_scale, const float* h_total, const float* z_total,
+                            const float* k_scale, const uint8_t* v_codes, const float* v_scale,
+                            const float* h_total, const float* z_total,
                             const int32_t* block_idx, const float* alpha, uint16_t* out, float* lse,
                             hipStream_t stream);
 hipError_t launch_dense_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,

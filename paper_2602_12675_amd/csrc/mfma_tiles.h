@@ -137,6 +137,30 @@ __device__ __forceinline__ void dma_tile8(const uint8_t* src, uint8_t* tile, int
                                      (__attribute__((address_space(3))) void*)(tile + (i * NW + w) * 1024), 16, 0, 0);
 }
 
+// A d x 64 tile of e4m3 codes of V, channel-major (rows of 64 bytes = the 64 tokens of a key block in
+// the order the 64-deep product consumes them).  An operand is the 32 bytes of one half of a row,
+// read as two 16-byte chunks; the chunk index is XOR-ed with (row / 4) % 4 so that the 16 rows one
+// read instruction covers per lane group spread over all banks.
+template <int D> struct SwizzledLayoutVq {
+  static constexpr int kTileBytes = D * kTileTokens;
+  __device__ static __forceinline__ int swz(int row) { return (row >> 2) & 3; }
+  __device__ static __forceinline__ int offset(int row, int chunk) { return row * kTileTokens + ((chunk ^ swz(row)) << 4); }
+};
+template <int D, int NW>
+__device__ __forceinline__ void dma_tile_vq(const uint8_t* src, uint8_t* tile, int w, int lane) {
+  typedef SwizzledLayoutVq<D> L;
+  constexpr int kRowsPerInstr = 1024 / kTileTokens;           // 16 rows of 64 bytes per instruction
+  constexpr int kInstrs = D / kRowsPerInstr / NW;
+  static_assert(kInstrs >= 1, "unsupported tile split");
+#pragma unroll
+  for (int i = 0; i < kInstrs; i++) {
+    const int row = (i * NW + w) * kRowsPerInstr + lane / 4;  // the slot this lane fills holds chunk (lane % 4) ^ swz(row)
+    const uint8_t* g = src + row * kTileTokens + 16 * ((lane % 4) ^ L::swz(row));
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                     (__attribute__((address_space(3))) void*)(tile + (i * NW + w) * 1024), 16, 0, 0);
+  }
+}
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 // K^phi fragment in token order for channel col0 + l % 32:

@@ -17,7 +17,8 @@ static int make_shape(const sla2_params* p, Shape* s) {
   if (p->B < 1 || p->H < 1 || p->N < 1) return SLA2_EINVAL;
   if (!(p->topk_frac >= 0.0f && p->topk_frac <= 1.0f)) return SLA2_EINVAL;   // also rejects NaN
   if (p->dtype != SLA2_F32 && p->dtype != SLA2_BF16) return SLA2_EINVAL;
-  if (p->quant_mode != SLA2_QUANT_NONE && p->quant_mode != SLA2_QUANT_FP8 && p->quant_mode != SLA2_QUANT_INT8)
+  if (p->quant_mode != SLA2_QUANT_NONE && p->quant_mode != SLA2_QUANT_FP8 && p->quant_mode != SLA2_QUANT_INT8 &&
+      p->quant_mode != SLA2_QUANT_FP8_V)
     return SLA2_EINVAL;
   if (p->router_w_per_head != 0 && p->router_w_per_head != 1) return SLA2_EINVAL;
   if (p->alpha_per_block != 0 && p->alpha_per_block != 1) return SLA2_EINVAL;
@@ -67,6 +68,8 @@ static void make_layout(const Shape& s, sla2_ws_layout* L) {
   L->z_blocks = take(s.bf16 ? BH * (size_t)s.Tn * d * sizeof(float) : 0);
   L->k_fp8 = take(s.quant ? BH * (size_t)s.Tn * s.bk * d : 0);
   L->k_scale = take(s.quant ? BH * (size_t)s.Tn * sizeof(float) : 0);
+  L->v_fp8 = take(s.quant == 3 ? BH * (size_t)s.Tn * s.bk * d : 0);
+  L->v_scale = take(s.quant == 3 ? BH * (size_t)s.Tn * sizeof(float) : 0);
   L->partial = take(BH * (size_t)s.chunks * (d * d + d) * sizeof(float));
   L->total = off;
 }
@@ -219,15 +222,17 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
   float* z_blocks = at<float>(workspace, L.z_blocks);
   uint8_t* k_fp8 = at<uint8_t>(workspace, L.k_fp8);
   float* k_scale = at<float>(workspace, L.k_scale);
+  uint8_t* v_fp8 = at<uint8_t>(workspace, L.v_fp8);
+  float* v_scale = at<float>(workspace, L.v_scale);
   if (SLA2_STAGE(SLA2_STAGE_KV_STATE,
                  launch_kv_state_bf16(s, (const uint16_t*)k, (const uint16_t*)v, k_mean, k_stats, partial, k_phi,
-                                      z_blocks, k_fp8, k_scale, st)) != hipSuccess)
+                                      z_blocks, k_fp8, k_scale, v_fp8, v_scale, st)) != hipSuccess)
     return SLA2_EHIP;
   if (SLA2_STAGE(SLA2_STAGE_KV_TOTAL, launch_kv_total(s, partial, h_total, z_total, st)) != hipSuccess)
     return SLA2_EHIP;
   if (SLA2_STAGE(SLA2_STAGE_ATTN,
                  launch_attn_bf16(s, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, k_mean, k_phi,
-                                  z_blocks, k_fp8, k_scale, h_total, z_total, idx, alpha, (uint16_t*)out,
+                                  z_blocks, k_fp8, k_scale, v_fp8, v_scale, h_total, z_total, idx, alpha, (uint16_t*)out,
                                   lse_or_null, st)) != hipSuccess)
     return SLA2_EHIP;
   return SLA2_OK;

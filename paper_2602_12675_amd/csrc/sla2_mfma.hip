@@ -60,13 +60,14 @@ __device__ __forceinline__ size_t kphi_offset(size_t block, int mt, int ks, int 
 // =============================================================================================
 // kv_state_bf16
 // =============================================================================================
-template <int D, int QUANT>   // QUANT: 0 none, 1 FP8 e4m3 codes of K - colmean K, 2 INT8 codes
+template <int D, int QUANT>   // QUANT: 0 none, 1 FP8 e4m3 codes of K - colmean K, 2 INT8 codes, 3 as 1 plus e4m3 codes of V
 __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __restrict__ k,
                                                             const uint16_t* __restrict__ v,
                                                             const double* __restrict__ k_mean,
                                                             float* __restrict__ k_stats, float* __restrict__ partial,
                                                             uint16_t* __restrict__ k_phi, float* __restrict__ z_blocks,
                                                             uint8_t* __restrict__ k_codes, float* __restrict__ k_scale,
+                                                            uint8_t* __restrict__ v_codes, float* __restrict__ v_scale,
                                                             int N, int Tn, int chunks, int blocks_per_chunk) {
   constexpr int LD = TileGeom<D>::kLd;
   typedef HSplit<D, 4> HS;
@@ -75,6 +76,7 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
   __shared__ __attribute__((aligned(16))) float lnz2[kTileTokens];
   __shared__ float mu_s[D];
   __shared__ float red[4];
+  __shared__ float red_v[4];
   const int bh = blockIdx.x / chunks, chunk = blockIdx.x % chunks;
   const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave, g = lane / 32;
   const uint16_t* kh = k + (size_t)bh * N * D;
@@ -183,6 +185,55 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
         }
       }
     }
+    if constexpr (QUANT == 3) {
+      // quant(V_j) for the second product (Alg. 2): one e4m3 scale per block over its existing tokens,
+      // codes stored channel-major with the tokens of a row in the order the 64-deep product consumes
+      // them (layout: sla2.h, v_fp8).  Thread (token t, quarter sub) finds the maximum ...
+      const int t = tid / 4, sub = tid % 4;
+      float vmax = 0.f;
+      if (t < valid) {
+#pragma unroll
+        for (int i = 0; i < D / 32; i++) {
+          const uint4 u = *reinterpret_cast<const uint4*>(vtile + t * LD + 8 * (sub + 4 * i));
+          const uint32_t wds[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+          for (int e = 0; e < 4; e++) {
+            vmax = fmaxf(vmax, fabsf(__builtin_bit_cast(float, wds[e] << 16)));
+            vmax = fmaxf(vmax, fabsf(__builtin_bit_cast(float, wds[e] & 0xFFFF0000u)));
+          }
+        }
+      }
+#pragma unroll
+      for (int o = 1; o < kWave; o <<= 1) vmax = fmaxf(vmax, __shfl_xor(vmax, o));
+      if (lane == 0) red_v[w] = vmax;
+      __syncthreads();
+      vmax = fmaxf(fmaxf(red_v[0], red_v[1]), fmaxf(red_v[2], red_v[3]));
+      const float vinv = vmax > 0.f ? kE4M3Max / vmax : 1.f;
+      if (tid == 0) v_scale[(size_t)bh * Tn + j] = vmax > 0.f ? vmax / kE4M3Max : 1.f;
+      // ... and thread (channel c, half gh) writes the 32 codes of bytes 32 gh .. 32 gh + 31 of row c
+      if (tid < 2 * D) {
+        const int c = tid / 2, gh = tid % 2;
+        int wd[8];
+#pragma unroll
+        for (int q = 0; q < 8; q++) {                  // dword q = bytes 4 q .. 4 q + 3
+          float y[4];
+#pragma unroll
+          for (int r = 0; r < 4; r++) {
+            const int b = 4 * q + r;
+            const int tok = 32 * (b / 16) + 8 * ((b % 16) / 4) + 4 * gh + b % 4;
+            const float x = __builtin_bit_cast(float, (uint32_t)vtile[tok * LD + c] << 16);
+            y[r] = tok < valid ? fminf(fmaxf(x * vinv, -kE4M3Max), kE4M3Max) : 0.f;
+          }
+          int d0 = 0;
+          d0 = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], d0, false);
+          d0 = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], d0, true);
+          wd[q] = d0;
+        }
+        int4* dst = reinterpret_cast<int4*>(v_codes + (((size_t)bh * Tn + j) * D + c) * kTileTokens + 32 * gh);
+        dst[0] = make_int4(wd[0], wd[1], wd[2], wd[3]);
+        dst[1] = make_int4(wd[4], wd[5], wd[6], wd[7]);
+      }
+    }
     __syncthreads();
     SLA2_PHASE_MARK(2)
     // K^phi fragments (kept for the attention kernel), h += K^phi^T V on the matrix cores, z_j
@@ -228,14 +279,21 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
 }
 
 hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_t* v, const double* k_mean,
-                                float* k_stats, float* partial, uint16_t* k_phi, float* z_blocks, uint8_t* k_fp8,
-                                float* k_scale, hipStream_t stream) {
+                                float* k_stats, float* partial, uint16_t* k_phi, float* z_blocks, uint8_t* k_codes,
+                                float* k_scale, uint8_t* v_codes, float* v_scale, hipStream_t stream) {
   dim3 grid((unsigned)(s.BH * s.chunks));
-#define SLA2_KV(DD, F8)                                                                                        \
-  kv_state_bf16_kernel<DD, F8><<<grid, 256, 0, stream>>>(k, v, k_mean, k_stats, partial, k_phi, z_blocks, k_fp8, \
-                                                         k_scale, s.N, s.Tn, s.chunks, s.blocks_per_chunk)
-  if (s.d == 128) { if (s.quant == 2) SLA2_KV(128, 2); else if (s.quant == 1) SLA2_KV(128, 1); else SLA2_KV(128, 0); }
-  else            { if (s.quant == 2) SLA2_KV(64, 2);  else if (s.quant == 1) SLA2_KV(64, 1);  else SLA2_KV(64, 0); }
+#define SLA2_KV(DD, QQ)                                                                                          \
+  kv_state_bf16_kernel<DD, QQ><<<grid, 256, 0, stream>>>(k, v, k_mean, k_stats, partial, k_phi, z_blocks, k_codes, \
+                                                         k_scale, v_codes, v_scale, s.N, s.Tn, s.chunks,          \
+                                                         s.blocks_per_chunk)
+#define SLA2_KV_D(DD)                                                                                  \
+  do {                                                                                                 \
+    if (s.quant == 3) SLA2_KV(DD, 3); else if (s.quant == 2) SLA2_KV(DD, 2);                           \
+    else if (s.quant == 1) SLA2_KV(DD, 1); else SLA2_KV(DD, 0);                                        \
+  } while (0)
+  if (s.d == 128) SLA2_KV_D(128);
+  else SLA2_KV_D(64);
+#undef SLA2_KV_D
 #undef SLA2_KV
   return hipGetLastError();
 }
@@ -244,20 +302,22 @@ hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_
 // attn_mfma
 // =============================================================================================
 constexpr int kXcds = 8;
-enum AttnMode { kSparseBf16 = 0, kSparseFp8 = 1, kDenseBf16 = 2, kSparseInt8 = 3 };
+enum AttnMode { kSparseBf16 = 0, kSparseFp8 = 1, kDenseBf16 = 2, kSparseInt8 = 3, kSparseFp8V = 4 };
 
 __device__ __forceinline__ f32x16 mfma_fp8(long a, long b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, b, c, 0, 0, 0);
 }
 
-// LDS carve-up.  Loop: two buffers, each one K tile (bf16, or e4m3 in FP8 mode) and one V tile (bf16),
+// LDS carve-up.  Loop: two buffers, each one K tile (bf16, or 8-bit codes), one V tile (bf16) and, when
+// V is quantised for the second product, one tile of its codes,
 // all in the swizzled layout the load unit fills directly.  Epilogue: H_i^T as bf16 [D][D+8] and the
 // output tile [BQ][D+8], overlaying the tile buffers.
-template <int D, int BQ, bool FP8> struct AttnSmem {
+template <int D, int BQ, bool FP8, bool VQ = false> struct AttnSmem {
   static constexpr int kLd = TileGeom<D>::kLd;
   static constexpr int kVBytes = SwizzledLayout<D>::kTileBytes;
   static constexpr int kKBytes = FP8 ? SwizzledLayout8<D>::kTileBytes : kVBytes;
-  static constexpr int kBufBytes = kKBytes + kVBytes;
+  static constexpr int kVqBytes = VQ ? SwizzledLayoutVq<D>::kTileBytes : 0;   // e4m3 codes of V, when P V is an FP8 product
+  static constexpr int kBufBytes = kKBytes + kVBytes + kVqBytes;
   static constexpr int kLoopBytes = 2 * kBufBytes;
   static constexpr int kEpiBytes = (D + BQ) * kLd * 2;
   static constexpr int kTiles = kLoopBytes > kEpiBytes ? kLoopBytes : kEpiBytes;
@@ -312,6 +372,15 @@ __device__ __forceinline__ u32x4 lds_read16_untracked(unsigned addr) {
   asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
   return r;
 }
+template <int UNIT>   // 16 bytes at addr + n UNIT, the offset in the instruction (n constant after unrolling)
+__device__ __forceinline__ u32x4 lds_read16_untracked_at(unsigned addr, int n) {
+  switch (n) {
+    case 0: return lds_read16_untracked<0>(addr);
+    case 1: return lds_read16_untracked<UNIT>(addr);
+    case 2: return lds_read16_untracked<2 * UNIT>(addr);
+    default: return lds_read16_untracked<3 * UNIT>(addr);
+  }
+}
 template <int OFF>    // transposing read, see read_tr4
 __device__ __forceinline__ u32x2 lds_read_tr_untracked(unsigned addr) {
   u32x2 r;
@@ -351,19 +420,22 @@ template <int D, int BQ, int MODE>
 __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const double* __restrict__ k_mean, const uint16_t* __restrict__ k_phi, const float* __restrict__ z_blocks,
-    const uint8_t* __restrict__ k_codes, const float* __restrict__ k_scale, const float* __restrict__ h_total,
+    const uint8_t* __restrict__ k_codes, const float* __restrict__ k_scale, const uint8_t* __restrict__ v_codes,
+    const float* __restrict__ v_scale, const float* __restrict__ h_total,
     const float* __restrict__ z_total, const int32_t* __restrict__ block_idx, const float* __restrict__ alpha,
     uint16_t* __restrict__ out, float* __restrict__ lse, int H, int N, int Tm, int Tn, int ksel, int alpha_per_block,
     int total_blocks) {
   // FP8 below means "8-bit codes of Q and K": everything the two low-bit modes share.  INT8 marks the
   // places where the integer mode differs (the quantiser of Q and the Q K^T product).
-  constexpr bool DENSE = MODE == kDenseBf16, INT8 = MODE == kSparseInt8, FP8 = MODE == kSparseFp8 || INT8;
+  // FP8V: V is quantised too and P V runs as an FP8 product (the linear branch still reads the bf16 V).
+  constexpr bool DENSE = MODE == kDenseBf16, INT8 = MODE == kSparseInt8, FP8V = MODE == kSparseFp8V;
+  constexpr bool FP8 = MODE == kSparseFp8 || INT8 || FP8V;
   constexpr int NW = BQ / 32, NT = NW * kWave;
   constexpr int LD = TileGeom<D>::kLd;
   constexpr int KS = D / 16;            // contraction steps over the head dimension
   constexpr int ET = D / 32;            // 32-wide tiles over the head dimension
   typedef HSplit<D, NW> HS;
-  typedef AttnSmem<D, BQ, FP8> SM;
+  typedef AttnSmem<D, BQ, FP8, FP8V> SM;
   typedef SwizzledLayout<D> SL;
   typedef SwizzledLayout8<D> SL8;
   // Loads and LDS reads of the main loop are issued untracked and waited for by count (see
@@ -372,12 +444,14 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   // does not have, and the compiler-tracked form is the faster one there.
   constexpr bool kManual = FP8;
   // global -> LDS transfers one wave issues per tile (1 KB each): V, and K in bf16 or e4m3
-  constexpr int kDmaOps = kTileTokens * D * 2 / 1024 / NW + kTileTokens * D * (FP8 ? 1 : 2) / 1024 / NW;
+  constexpr int kDmaOps = kTileTokens * D * 2 / 1024 / NW + kTileTokens * D * (FP8 ? 1 : 2) / 1024 / NW +
+                          (FP8V ? kTileTokens * D / 1024 / NW : 0);
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
   float* zs = reinterpret_cast<float*>(smem + SM::kZsOff);
   float* red = reinterpret_cast<float*>(smem + SM::kRedOff);
   auto kbuf = [&](int buf) { return smem + buf * SM::kBufBytes; };
   auto vbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + buf * SM::kBufBytes + SM::kKBytes); };
+  auto vqbuf = [&](int buf) { return smem + buf * SM::kBufBytes + SM::kKBytes + SM::kVBytes; };
 
   // consecutive query blocks of a head share key/value tiles: keep them on one XCD (workgroups are
   // dealt round-robin to the 8 XCDs, each with its own L2)
@@ -402,6 +476,10 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   int j_cur = ntiles > 0 ? tile_block(0) : 0, j_nxt = ntiles > 0 ? tile_block(1) : 0;
   float sk_cur = 1.f;
   if constexpr (FP8) sk_cur = k_scale[blk0 + j_cur];
+  // FP8V: O^T is carried in units of the V scale of the tile being added (the factor between two tiles
+  // joins the online-softmax correction); sv_cur is the scale of the coming tile, sv_prev of the last one
+  float sv_cur = 1.f, sv_prev = 1.f;
+  if constexpr (FP8V) sv_cur = sv_prev = ntiles > 0 ? v_scale[blk0 + j_cur] : 1.f;
 
   // tile s: global memory -> LDS buffer `buf`, no registers involved (completion: vmcnt)
   auto dma = [&](int j, int buf) {
@@ -411,6 +489,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     else dma_tile<D, NW>(kh + (size_t)t0 * D, valid, reinterpret_cast<uint16_t*>(kbuf(buf)), w, lane);
     if (kManual && valid == kTileTokens) dma_tile_full<D, NW>(vh + (size_t)t0 * D, vbuf(buf), w, lane);
     else dma_tile<D, NW>(vh + (size_t)t0 * D, valid, vbuf(buf), w, lane);
+    if constexpr (FP8V) dma_tile_vq<D, NW>(v_codes + (blk0 + j) * kTileTokens * D, vqbuf(buf), w, lane);
   };
 
   if (ntiles > 0) dma(j_cur, 0);
@@ -500,6 +579,8 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     const float sk = sk_cur;
     const int j_nn = tile_block(s + 2);                // consumed in the next iteration
     if constexpr (FP8) sk_cur = k_scale[blk0 + j_nxt];
+    const float sv = sv_cur;
+    if constexpr (FP8V) sv_cur = v_scale[blk0 + j_nxt];
     // K^phi fragments and z_j of this tile straight from global memory into registers (no other
     // wave needs them); they are consumed after the softmax.  They are issued before the next
     // tile's transfer and, since vmcnt retires in order, are complete once at most kDmaOps
@@ -622,7 +703,8 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     const float m_new = fmaxf(m_run, mx);            // finite: a tile holds at least one key
     const float m_off = m_new - kPShift;
     float rs = 0.f;
-    bf16x8 pf[4];                                    // P^T fragments, token order
+    bf16x8 pf[FP8V ? 1 : 4];                         // P^T fragments, token order
+    i32x8 pb;                                        // FP8V: the e4m3 codes of P^T, byte 16 mt + e of the lane's half
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
 #pragma unroll
@@ -630,7 +712,11 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         const float p0 = fast_exp2(sacc[mt][e] * c1 - m_off);
         const float p1 = fast_exp2(sacc[mt][e + 1] * c1 - m_off);
         rs += p0 + p1;                               // the denominator keeps the un-rounded P
-        if constexpr (FP8) {
+        if constexpr (FP8V) {
+          const int q = 4 * mt + e / 4;              // two codes into the lower or upper half of dword q
+          if (e % 4 == 0) pb[q] = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, 0, false);
+          else pb[q] = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, pb[q], true);
+        } else if constexpr (FP8) {
           const int codes = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, 0, false);       // quant(P): e4m3 grid
           typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
           const bf16x2 pq = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes, 1.0f, false);
@@ -645,10 +731,12 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     const float corr = fast_exp2(m_run - m_new);     // 0 on the first tile
     l_run = l_run * corr + rs;
     m_run = m_new;
+    const float corr_o = FP8V ? corr * (sv_prev / sv) : corr;   // FP8V: also from the last tile's V scale to this one's
+    sv_prev = sv;
 #pragma unroll
     for (int et = 0; et < ET; et++)
 #pragma unroll
-      for (int e = 0; e < 16; e++) oacc[et][e] *= corr;
+      for (int e = 0; e < 16; e++) oacc[et][e] *= corr_o;
 
     SLA2_PHASE_MARK(2)
     if constexpr (!DENSE) {
@@ -666,6 +754,27 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         for (int a = 0; a < HS::kMtw; a++) zsel[a] += zj[a];
       }
     }
+    if constexpr (FP8V) {
+      // O^T += Vhat^T Ptilde^T as 64-deep FP8 products, one per 32-channel tile: the operand is the half
+      // row (l / 32) of channel row 32 et + l % 32 of the code tile, two 16-byte reads
+      typedef SwizzledLayoutVq<D> SLV;
+      const unsigned qa = lds_address(vqbuf(buf) + SLV::offset(lane % 32, 2 * g));
+      u32x4 vq_lo[ET], vq_hi[ET];
+#pragma unroll
+      for (int et = 0; et < ET; et++) {
+        vq_lo[et] = lds_read16_untracked_at<32 * kTileTokens>(qa, et);
+        vq_hi[et] = lds_read16_untracked_at<32 * kTileTokens>(qa ^ 16u, et);
+      }
+#pragma unroll
+      for (int et = 0; et < ET; et++) {
+        wait_lgkmcnt(2 * (ET - 1 - et));
+        settle(vq_lo[et]);
+        settle(vq_hi[et]);
+        const u32x4 lo = vq_lo[et], hi = vq_hi[et];
+        const i32x8 a = {(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3], (int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]};
+        oacc[et] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, pb, oacc[et], 0, 0, 0, 0, 0, 0);
+      }
+    }
     // ---- O^T += V^T P^T, and the d x d state of this block: h += K^phi^T V ----
     // address of this lane's first transposing read of fragment (ks = 0, et = 0), cf. read_tr4
     const unsigned va = lds_address(vt + SL::offset(4 * g + (lane % 16) / 4, 16 * ((lane / 16) % 2) + 4 * (lane % 4)));
@@ -679,7 +788,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
 #pragma unroll
         for (int et = 0; et < ET; et++) {
           bf16x8 vf = v_fragment<SL>(vt, ks, 32 * et, lane);
-          oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
+          if constexpr (!FP8V) oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
           if constexpr (!DENSE) {
 #pragma unroll
             for (int a = 0; a < HS::kMtw; a++) hacc[a][et] = mfma_bf16(kphi[a][ks], vf, hacc[a][et]);
@@ -713,7 +822,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
           settle(hi);
           const u32x4 v4 = {lo[0], lo[1], hi[0], hi[1]};
           const bf16x8 vf = __builtin_bit_cast(bf16x8, v4);
-          oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
+          if constexpr (!FP8V) oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
           if constexpr (!DENSE) {
 #pragma unroll
             for (int a = 0; a < HS::kMtw; a++) hacc[a][et] = mfma_bf16(kphi[a][ks], vf, hacc[a][et]);
@@ -723,7 +832,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
 #pragma unroll
         for (int et = 0; et < ET; et++) {
           bf16x8 vf = v_fragment<SL>(vt, ks, 32 * et, lane);
-          oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
+          if constexpr (!FP8V) oacc[et] = mfma_bf16(vf, pf[ks], oacc[et]);
         }
 #pragma unroll
         for (int b = 0; b < HS::kNtw; b++) {
@@ -844,7 +953,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   }
   // ---- mix (Eq. 13), transpose through LDS, coalesced store ----
   const float al = DENSE ? 1.f : alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
-  const float ws = al * inv_l, wl = (1.f - al) * inv_den;
+  const float ws = al * inv_l * (FP8V ? sv_prev : 1.f), wl = (1.f - al) * inv_den;   // FP8V: back from the last tile's V scale
 #pragma unroll
   for (int et = 0; et < ET; et++)
 #pragma unroll
@@ -873,7 +982,9 @@ struct AttnArgs {
   const uint16_t* k_phi;
   const float* z_blocks;
   const uint8_t* k_fp8;
-  const float *k_scale, *h_total, *z_total;
+  const float* k_scale;
+  const uint8_t* v_codes;
+  const float *v_scale, *h_total, *z_total;
   const int32_t* block_idx;
   const float* alpha;
   uint16_t* out;
@@ -882,7 +993,7 @@ struct AttnArgs {
 
 template <int D, int BQ, int MODE>
 static hipError_t launch_attn_t(const Shape& s, const AttnArgs& a, hipStream_t stream) {
-  constexpr int smem = AttnSmem<D, BQ, MODE == kSparseFp8 || MODE == kSparseInt8>::kBytes;
+  constexpr int smem = AttnSmem<D, BQ, MODE == kSparseFp8 || MODE == kSparseInt8 || MODE == kSparseFp8V, MODE == kSparseFp8V>::kBytes;
   static bool configured = false;
   if (!configured) {
     hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<D, BQ, MODE>,
@@ -894,19 +1005,22 @@ static hipError_t launch_attn_t(const Shape& s, const AttnArgs& a, hipStream_t s
   const int total = s.BH * Tm;
   const int grid = ((total + kXcds - 1) / kXcds) * kXcds;
   attn_mfma_kernel<D, BQ, MODE><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(
-      a.q, a.k, a.v, a.k_mean, a.k_phi, a.z_blocks, a.k_fp8, a.k_scale, a.h_total, a.z_total, a.block_idx, a.alpha,
+      a.q, a.k, a.v, a.k_mean, a.k_phi, a.z_blocks, a.k_fp8, a.k_scale, a.v_codes, a.v_scale, a.h_total, a.z_total,
+      a.block_idx, a.alpha,
       a.out, a.lse, s.H, s.N, Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0, total);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v,
                             const double* k_mean, const uint16_t* k_phi, const float* z_blocks, const uint8_t* k_fp8,
-                            const float* k_scale, const float* h_total, const float* z_total,
+                            const float* k_scale, const uint8_t* v_codes, const float* v_scale,
+                            const float* h_total, const float* z_total,
                             const int32_t* block_idx, const float* alpha, uint16_t* out, float* lse,
                             hipStream_t stream) {
-  AttnArgs a{q, k, v, k_mean, k_phi, z_blocks, k_fp8, k_scale, h_total, z_total, block_idx, alpha, out, lse};
+  AttnArgs a{q, k, v, k_mean, k_phi, z_blocks, k_fp8, k_scale, v_codes, v_scale, h_total, z_total, block_idx, alpha, out, lse};
 #define SLA2_ATTN(DD, QQ)                                                  \
-  return s.quant == 2 ? launch_attn_t<DD, QQ, kSparseInt8>(s, a, stream)   \
+  return s.quant == 3 ? launch_attn_t<DD, QQ, kSparseFp8V>(s, a, stream)   \
+       : s.quant == 2 ? launch_attn_t<DD, QQ, kSparseInt8>(s, a, stream)   \
        : s.quant == 1 ? launch_attn_t<DD, QQ, kSparseFp8>(s, a, stream)    \
                       : launch_attn_t<DD, QQ, kSparseBf16>(s, a, stream)
   if (s.d == 128 && s.bq == 128) SLA2_ATTN(128, 128);
@@ -918,7 +1032,7 @@ hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k
 
 hipError_t launch_dense_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
                              hipStream_t stream) {
-  AttnArgs a{q, k, v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, out, nullptr};
+  AttnArgs a{q, k, v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, out, nullptr};
   if (s.d == 128) return launch_attn_t<128, 128, kDenseBf16>(s, a, stream);
   return launch_attn_t<64, 128, kDenseBf16>(s, a, stream);
 }

@@ -32,7 +32,7 @@ class Workload:
     block_kv: int
     topk_frac: float
     dtype: str             # storage type of q, k, v, out: "f32" | "bf16"
-    quant: str             # "none" | "fp8" | "int8"
+    quant: str             # "none" | "fp8" | "int8" | "fp8v" (FP8 with V quantised too)
     seed: int
     per_head_freq: bool    # False: f = (1,1,1); True: f ~ U[0.5, 4) per head and axis
     extra_tokens: int = 0  # tokens appended after the grid (ragged-tail cases)

@@ -12,7 +12,8 @@ def oracle_heads(inp: W.Inputs, quant=None, smooth=True, alpha=None, heads=None,
                  topk_frac=None):
     """Oracle results for the chosen (b, h) pairs: dict (b, h) -> forward_head dict."""
     w = inp.workload
-    quant = {"none": O.QUANT_NONE, "fp8": O.QUANT_FP8, "int8": O.QUANT_INT8}[w.quant] if quant is None else quant
+    quant = {"none": O.QUANT_NONE, "fp8": O.QUANT_FP8, "int8": O.QUANT_INT8,
+             "fp8v": O.QUANT_FP8_V}[w.quant] if quant is None else quant
     Wq = inp.router_w[0].astype(np.float64)
     Wk = inp.router_w[1].astype(np.float64)
     alpha = inp.alpha if alpha is None else alpha

@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(api):
 
 def test_struct_sizes_match_header(api):
     assert ctypes.sizeof(api.Params) == 12 * 4
-    assert ctypes.sizeof(api.WsLayout) == 14 * ctypes.sizeof(ctypes.c_size_t)
+    assert ctypes.sizeof(api.WsLayout) == 16 * ctypes.sizeof(ctypes.c_size_t)
 
 
 def test_num_selected_and_workspace(api):
@@ -59,9 +59,10 @@ def test_num_selected_and_workspace(api):
 @pytest.mark.parametrize("kw,status", [
     (dict(d=96), "EUNSUPPORTED"), (dict(block_q=32), "EUNSUPPORTED"), (dict(block_kv=128), "EUNSUPPORTED"),
     (dict(topk_frac=1.5), "EINVAL"), (dict(topk_frac=-0.1), "EINVAL"), (dict(topk_frac=float("nan")), "EINVAL"),
-    (dict(N=0), "EINVAL"), (dict(B=0), "EINVAL"), (dict(dtype=7), "EINVAL"), (dict(quant_mode=3), "EINVAL"),
+    (dict(N=0), "EINVAL"), (dict(B=0), "EINVAL"), (dict(dtype=7), "EINVAL"), (dict(quant_mode=4), "EINVAL"), (dict(quant_mode=-1), "EINVAL"),
     (dict(flags=8), "EINVAL"), (dict(N=64 * 2048 + 1), "EUNSUPPORTED"),
-    (dict(dtype=0, quant_mode=1), "EUNSUPPORTED"),
+    (dict(dtype=0, quant_mode=1), "EUNSUPPORTED"), (dict(dtype=0, quant_mode=2), "EUNSUPPORTED"),
+    (dict(dtype=0, quant_mode=3), "EUNSUPPORTED"),
 ])
 def test_bad_parameters_are_rejected_on_the_host(api, kw, status):
     base = dict(B=1, H=2, N=1024, d=64, block_q=64, block_kv=64, topk_frac=0.125, dtype=api.SLA2_BF16)

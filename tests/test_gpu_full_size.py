@@ -16,7 +16,7 @@ from paper_2602_12675_amd import workloads as W
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
 
-TOL = {"none": 2e-2, "fp8": 5e-2, "int8": 5e-2}
+TOL = {"none": 2e-2, "fp8": 5e-2, "int8": 5e-2, "fp8v": 5e-2}
 
 
 def sampled_check(w, heads, n_blocks=6, seed=0):
@@ -52,6 +52,10 @@ def test_wan_1p3b_fp8_97():
 
 def test_wan_1p3b_int8_97():
     sampled_check(W.WAN_1P3B_97_FP8.replace(name="wan1.3b-97-int8", quant="int8"), heads=[(0, 2), (0, 9)])
+
+
+def test_wan_1p3b_fp8v_97():
+    sampled_check(W.WAN_1P3B_97_FP8.replace(name="wan1.3b-97-fp8v", quant="fp8v"), heads=[(0, 3), (0, 10)])
 
 
 def test_wan_14b_fp8_97():
