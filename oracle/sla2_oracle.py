@@ -20,6 +20,8 @@ independently of itself) live in tests/test_oracle_pins.py:
   smooth_k, phi, pool        closed forms + brute force with the expanded mask
   router_scores, topk_rows   single-entry projections (orientation), brute-force
                              ranking, invariances the paper's text implies
+  soft_topk_rows             row sums, the closed form for equal scores and for two
+                             columns, order preservation, the hard mask as tau -> 0
   sparse_branch              dense softmax attention when every block is kept;
                              library SDPA; hand-worked micro case; alpha identity
   linear_branch              linear-attention closed form when no block is kept;
@@ -124,6 +126,51 @@ def topk_rows(R: np.ndarray, k: int) -> np.ndarray:
         order = np.argsort(-R[i], kind="stable")      # descending, stable
         sel[i] = np.sort(order[:k])
     return sel
+
+
+def _sigmoid(x: np.ndarray) -> np.ndarray:
+    """1 / (1 + exp(-x)) without overflow for large |x|."""
+    e = np.exp(-np.abs(x))
+    return np.where(x >= 0, 1.0 / (1.0 + e), e / (1.0 + e))
+
+
+def soft_topk_rows(R: np.ndarray, k: int, tau: float = 0.1) -> np.ndarray:
+    """SoftTop-k(k%, P_c) of Sec. 6.1 (the differentiable stand-in for Top-k used in the
+    first training stage), row-wise:
+
+        P_c    = softmax over the row of R             (the router step of Alg. 2)
+        M_ij   = sigmoid(P_c[i, j] / tau + lambda_i)
+        lambda_i solved by bisection so that the row sums to k.
+
+    The row sum is increasing in lambda_i, from 0 to T_n, so the root is unique
+    for 0 < k < T_n.  Reading taken: k is the same integer as for the hard mask
+    (num_selected), so that both masks keep the same mass per row; k = 0 gives
+    the zero mask and k = T_n the all-ones mask (the limits lambda -> -inf, +inf).
+    The bisection runs in float64 on a bracket that provably contains the root
+    until the interval stops shrinking.  Returns [T_m, T_n] float64."""
+    T_m, T_n = R.shape
+    if k <= 0:
+        return np.zeros((T_m, T_n))
+    if k >= T_n:
+        return np.ones((T_m, T_n))
+    M = np.empty((T_m, T_n))
+    for i in range(T_m):
+        e = np.exp(R[i] - R[i].max())
+        x = (e / e.sum()) / tau                       # P_c / tau, in [0, 1 / tau]
+        # sigmoid(x + lam) <= sigmoid(x.max() + lam): sum < k once lam < logit(k / T_n) - x.max();
+        # sigmoid(x + lam) >= sigmoid(x.min() + lam): sum > k once lam > logit(k / T_n) - x.min()
+        logit = math.log(k / (T_n - k))
+        lo, hi = logit - x.max() - 1e-9, logit - x.min() + 1e-9
+        while True:
+            mid = 0.5 * (lo + hi)
+            if mid <= lo or mid >= hi:
+                break
+            if _sigmoid(x + mid).sum() < k:
+                lo = mid
+            else:
+                hi = mid
+        M[i] = _sigmoid(x + 0.5 * (lo + hi))
+    return M
 
 
 def mask_from_sel(sel: np.ndarray, T_n: int) -> np.ndarray:

@@ -427,6 +427,58 @@ def test_lowbit_products_are_exact_in_float64():
     assert all(F(S[i, j]) == exact[i, j] for i in range(8) for j in range(8))
 
 
+# ---- SoftTop-k (Sec. 6.1) ---------------------------------------------------- #
+def test_soft_topk_row_sums_range_and_order():
+    rng = np.random.default_rng(30)
+    R = rng.normal(size=(7, 40)) * 3.0
+    for k in (1, 5, 39):
+        M = O.soft_topk_rows(R, k, tau=0.1)
+        np.testing.assert_allclose(M.sum(axis=1), k, rtol=0, atol=1e-9)
+        assert np.all(M > 0) and np.all(M < 1)
+        for i in range(R.shape[0]):                   # larger score, larger weight
+            o = np.argsort(R[i])
+            assert np.all(np.diff(M[i, o]) >= 0)
+    assert not O.soft_topk_rows(R, 0).any()
+    assert np.all(O.soft_topk_rows(R, 40) == 1.0)
+
+
+def test_soft_topk_closed_forms():
+    # equal scores: every entry k / T_n whatever tau
+    M = O.soft_topk_rows(np.full((2, 10), 0.7), 3, tau=0.05)
+    np.testing.assert_allclose(M, 0.3, rtol=0, atol=1e-12)
+    # two columns, k = 1: sigmoid(a + l) + sigmoid(b + l) = 1  <=>  l = -(a + b) / 2
+    R = np.array([[0.3, -1.1]])
+    e = np.exp(R[0] - R[0].max()); p = e / e.sum()
+    tau = 0.2
+    lam = -(p[0] + p[1]) / (2 * tau)
+    want = 1.0 / (1.0 + np.exp(-(p / tau + lam)))
+    np.testing.assert_allclose(O.soft_topk_rows(R, 1, tau=tau)[0], want, rtol=0, atol=1e-12)
+    # a per-row constant added to the scores changes nothing (softmax), a permutation permutes
+    rng = np.random.default_rng(31)
+    R = rng.normal(size=(3, 12))
+    A = O.soft_topk_rows(R, 4)
+    np.testing.assert_allclose(O.soft_topk_rows(R + np.array([[5.0], [-2.0], [0.5]]), 4), A, rtol=0, atol=1e-12)
+    perm = rng.permutation(12)
+    np.testing.assert_allclose(O.soft_topk_rows(R[:, perm], 4), A[:, perm], rtol=0, atol=1e-12)
+
+
+def test_soft_topk_tends_to_the_hard_mask():
+    rng = np.random.default_rng(32)
+    R = rng.normal(size=(5, 16)) * 1.5               # softmax values spread over (0, 0.5)
+    k = 3
+    hard = O.mask_from_sel(O.topk_rows(R, k), 16).astype(np.float64)
+    soft = O.soft_topk_rows(R, k, tau=1e-5)
+    # entries of the softmax closer than a few tau to the k-th / (k+1)-th boundary stay soft
+    e = np.exp(R - R.max(axis=1, keepdims=True)); P = e / e.sum(axis=1, keepdims=True)
+    srt = np.sort(P, axis=1)[:, ::-1]
+    clear = (np.abs(P - 0.5 * (srt[:, k - 1] + srt[:, k])[:, None]) > 30e-5)
+    assert clear.mean() > 0.8
+    np.testing.assert_allclose(soft[clear], hard[clear], rtol=0, atol=1e-6)
+    # and the order of the soft weights is the order the hard mask cuts
+    for i in range(5):
+        assert set(np.argsort(-soft[i])[:k]) == set(np.nonzero(hard[i])[0])
+
+
 # ---- INT8 form of the Q/K quantiser (Sec. 5) ------------------------------- #
 def test_quant_block_int8_is_nearest_integer_symmetric():
     rng = np.random.default_rng(23)
