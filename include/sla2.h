@@ -132,6 +132,16 @@ int sla2_num_selected(const sla2_params* params);
 int sla2_router(const sla2_params* params, const void* q, const void* k, const float* router_w,
                 int32_t* block_idx, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* SoftTop-k form of the router (Sec. 6.1: the differentiable operator that replaces Top-k in the
+ * first training stage):  mask[b,h,i,j] = sigmoid(P_c[i,j] / tau + lambda_i), P_c the row softmax
+ * of the router scores of Eq. 16 (with the 1/sqrt(d) of Alg. 2), lambda_i found by bisection so that
+ * row i sums to k = sla2_num_selected(params); k = 0 gives zeros, k = T_n ones.  fp64 inside.
+ *   q, k, router_w  as for sla2_router;  tau > 0 (the paper uses 0.1)
+ *   mask_out        DEVICE float [B, H, T_m, T_n], written
+ * Same workspace, stream and error conventions as sla2_router; SLA2_EINVAL if tau is not positive. */
+int sla2_router_soft(const sla2_params* params, const void* q, const void* k, const float* router_w,
+                     float tau, float* mask_out, void* workspace, size_t workspace_bytes, void* hip_stream);
+
 /* The whole forward pass (Alg. 2; Eq. 13-16): router as above, then for every
  * query block the sparse branch over its selected key/value blocks in ascending
  * order (online softmax), the linear branch over the others - formed as the

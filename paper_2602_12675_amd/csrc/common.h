@@ -60,6 +60,8 @@ hipError_t launch_block_sums(const Shape& s, const void* q, const void* k, const
                              double* k_sum, double* router_m, hipStream_t stream);
 hipError_t launch_router_topk(const Shape& s, const double* q_sum, const double* k_sum, const double* router_m,
                               int32_t* block_idx, double* k_mean, hipStream_t stream);
+hipError_t launch_router_soft(const Shape& s, const double* q_sum, const double* k_sum, const double* router_m,
+                              float* mask, double tau, hipStream_t stream);
 hipError_t launch_kv_state_f32(const Shape& s, const float* k, const float* v, const double* k_mean, float* k_stats,
                                float* partial, hipStream_t stream);
 hipError_t launch_attn_f32(const Shape& s, const float* q, const float* k, const float* v, const double* k_mean,

@@ -180,6 +180,27 @@ int sla2_router(const sla2_params* params, const void* q, const void* k, const f
   return SLA2_OK;
 }
 
+int sla2_router_soft(const sla2_params* params, const void* q, const void* k, const float* router_w, float tau,
+                     float* mask_out, void* workspace, size_t workspace_bytes, void* hip_stream) {
+  Shape s; sla2_ws_layout L;
+  int rc = make_shape(params, &s);
+  if (rc != SLA2_OK) return rc;
+  if (!q || !k || !router_w || !mask_out || !(tau > 0.f)) return SLA2_EINVAL;
+  make_layout(s, &L);
+  if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
+  hipStream_t st = (hipStream_t)hip_stream;
+  g_prof.calls++;
+  if (SLA2_STAGE(SLA2_STAGE_BLOCK_SUMS, launch_block_sums(s, q, k, router_w, at<double>(workspace, L.q_sum),
+                                                          at<double>(workspace, L.k_sum),
+                                                          at<double>(workspace, L.router_m), st)) != hipSuccess)
+    return SLA2_EHIP;
+  if (SLA2_STAGE(SLA2_STAGE_TOPK, launch_router_soft(s, at<double>(workspace, L.q_sum), at<double>(workspace, L.k_sum),
+                                                     at<double>(workspace, L.router_m), mask_out, (double)tau,
+                                                     st)) != hipSuccess)
+    return SLA2_EHIP;
+  return SLA2_OK;
+}
+
 int sla2_forward(const sla2_params* params, const void* q, const void* k, const void* v, const float* router_w,
                  const float* alpha, void* out, int32_t* block_idx_or_null, float* lse_or_null, void* workspace,
                  size_t workspace_bytes, void* hip_stream) {

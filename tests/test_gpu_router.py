@@ -106,3 +106,42 @@ def test_router_degenerate_k(frac):
     assert kk == (0 if frac == 0.0 else w.T_n)
     if kk:
         assert np.array_equal(idx, np.broadcast_to(np.arange(kk, dtype=np.int32), idx.shape))
+
+
+def test_router_identity_weights_is_topk_of_pooled_scores():
+    """router_w = (I, I): the learnable router reduces to Top-k of pool(Q) pool(K)^T, the fixed
+    router the paper ablates against (Sec. 8.3, "Topk-router")."""
+    import torch
+    from paper_2602_12675_amd import api
+    w = W.TINY.replace(name="identity-router", grid=(5, 16, 33), d=128, block_q=128, dtype="bf16", H=2,
+                       topk_frac=0.1, per_head_freq=True)
+    inp = W.generate(w)
+    inp.router_w[:] = np.eye(w.d, dtype=np.float32)[None]
+    _, _, idx, kk = run_router(api, torch, inp)
+    for h in range(w.H):
+        Q, K = inp.values("q", 0, h), inp.values("k", 0, h)
+        R = O.pool(Q, w.block_q) @ O.pool(O.smooth_k(K), w.block_kv).T      # no projection, no scale
+        assert check_mask(idx[0, h], R, O.topk_rows(R, kk)) == 0
+
+
+def test_router_per_head_weights():
+    """router_w_per_head = 1: one (Wq, Wk) pair per head, [H, 2, d, d]."""
+    import torch
+    from paper_2602_12675_amd import api
+    w = W.TINY.replace(name="per-head-router", grid=(3, 11, 31), H=3, topk_frac=0.2)
+    inp = W.generate(w)
+    rng = np.random.default_rng(5)
+    rw = (rng.normal(size=(w.H, 2, w.d, w.d)) / np.sqrt(w.d)).astype(np.float32)
+    p = api.make_params(w.B, w.H, w.N, w.d, w.block_q, w.block_kv, w.topk_frac, dtype=api.SLA2_F32,
+                        router_w_per_head=1)
+    q, k = api.to_device(inp.q, api.SLA2_F32), api.to_device(inp.k, api.SLA2_F32)
+    ws = api.alloc_workspace(p)
+    kk = api.sla2_num_selected(p)
+    idx = torch.full((w.B, w.H, w.T_m, kk), -1, dtype=torch.int32, device="cuda")
+    api.sla2_router(p, q, k, torch.from_numpy(rw).cuda(), idx, ws)
+    torch.cuda.synchronize()
+    idx = idx.cpu().numpy()
+    for h in range(w.H):
+        Q, K = inp.values("q", 0, h), inp.values("k", 0, h)
+        R = O.router_scores(Q, O.smooth_k(K), rw[h, 0].astype(np.float64), rw[h, 1].astype(np.float64), w.block_q, w.block_kv)
+        assert check_mask(idx[0, h], R, O.topk_rows(R, kk)) == 0
