@@ -37,6 +37,8 @@ def parse():
     ap.add_argument("--quant", choices=["fp8", "int8", "fp8v", "none"], default=None, help="override the workload's sparse-branch precision")
     ap.add_argument("--topk", type=float, default=None, help="override the kept fraction of key blocks")
     ap.add_argument("--input-sets", type=int, default=3, help="independent input copies rotated between calls")
+    ap.add_argument("--packed-qkv", action="store_true",
+                    help="q, k, v as slices of one [B, N, 3, H, d] tensor and out as [B, N, H, d], passed by strides")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-heads", type=int, default=6, help="heads of the workload the oracle is timed on")
@@ -107,12 +109,23 @@ def main():
     inp = W.generate(w)
     dt = api.SLA2_BF16 if w.dtype == "bf16" else api.SLA2_F32
     qm = api.QUANT_MODES[w.quant]
-    p = api.make_params(w.B, w.H, w.N, w.d, w.block_q, w.block_kv, w.topk_frac, dtype=dt, quant_mode=qm)
+    strides = {}
+    if args.packed_qkv:
+        strides = dict(in_stride=(w.N * 3 * w.H * w.d, w.d, 3 * w.H * w.d), out_stride=(w.N * w.H * w.d, w.d, w.H * w.d))
+    p = api.make_params(w.B, w.H, w.N, w.d, w.block_q, w.block_kv, w.topk_frac, dtype=dt, quant_mode=qm, **strides)
     ksel = api.sla2_num_selected(p)
     sets = []
     for s in range(max(1, args.input_sets)):
         q, k, v = (api.to_device(a, dt) for a in (inp.q, inp.k, inp.v))
-        sets.append((q, k, v, torch.empty_like(q)))
+        if args.packed_qkv:
+            qkv = torch.empty((w.B, w.N, 3, w.H, w.d), dtype=q.dtype, device="cuda")
+            for x, t in enumerate((q, k, v)):
+                qkv[:, :, x] = t.permute(0, 2, 1, 3)
+            del q, k, v
+            sets.append((qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2],
+                         torch.empty((w.B, w.N, w.H, w.d), dtype=qkv.dtype, device="cuda")))
+        else:
+            sets.append((q, k, v, torch.empty_like(q)))
     rw = torch.from_numpy(inp.router_w).cuda()
     al = torch.from_numpy(inp.alpha).cuda()
     ws = api.alloc_workspace(p)
@@ -195,7 +208,8 @@ def main():
         "dtype": mm, "data": "synthetic",
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "block_q": w.block_q,
                    "block_kv": w.block_kv, "topk_frac": w.topk_frac, "k": ksel, "T_n": w.T_n,
-                   "sparsity": round(1.0 - ksel / w.T_n, 4), "quant": w.quant, "input_sets": len(sets)},
+                   "sparsity": round(1.0 - ksel / w.T_n, 4), "quant": w.quant, "input_sets": len(sets),
+                   "layout": "packed [B,N,3,H,d] -> [B,N,H,d]" if args.packed_qkv else "[B,H,N,d]"},
         "roofline": roofline,
         "stage_ms": {k_: round(v_, 4) for k_, v_ in stages.items()},
         "hbm_kernels": hbm,

@@ -83,6 +83,15 @@ typedef struct sla2_params {
   int alpha_per_block;     /* 0: alpha is [H]; 1: alpha is [H, T_m], T_m = ceil(N / block_q)
                               (Alg. 2 takes one alpha per query block) */
   unsigned flags;          /* SLA2_FLAG_* */
+  /* Element strides (batch, head, token) of q, k, v - which share one layout, e.g. the three
+   * slices of a packed [B, N, 3, H, d] projection - and of out.  The head dimension is always
+   * contiguous.  All three zero (the default) means the contiguous [B, H, N, d] layout,
+   * i.e. (H*N*d, N*d, d).  A [B, N, H, d] tensor is (N*H*d, d, H*d).  Every stride must be
+   * positive, a multiple of 16 bytes, the token stride at least d and below 2^24 elements;
+   * the caller guarantees that the strides describe memory it owns.  lse, block_idx and the
+   * workspace arrays are not affected. */
+  long long in_stride[3];
+  long long out_stride[3];
 } sla2_params;
 
 /* Byte offsets, inside the workspace, of what a call leaves behind.  All are

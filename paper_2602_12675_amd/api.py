@@ -35,7 +35,8 @@ class Params(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int), ("H", ctypes.c_int), ("N", ctypes.c_int), ("d", ctypes.c_int),
                 ("block_q", ctypes.c_int), ("block_kv", ctypes.c_int), ("topk_frac", ctypes.c_float),
                 ("dtype", ctypes.c_int), ("quant_mode", ctypes.c_int), ("router_w_per_head", ctypes.c_int),
-                ("alpha_per_block", ctypes.c_int), ("flags", ctypes.c_uint)]
+                ("alpha_per_block", ctypes.c_int), ("flags", ctypes.c_uint),
+                ("in_stride", ctypes.c_longlong * 3), ("out_stride", ctypes.c_longlong * 3)]
 
 
 class WsLayout(ctypes.Structure):
@@ -97,9 +98,16 @@ def _stream(stream):
 
 
 def make_params(B, H, N, d, block_q, block_kv, topk_frac, dtype=SLA2_BF16, quant_mode=SLA2_QUANT_NONE,
-                router_w_per_head=0, alpha_per_block=0, flags=0) -> Params:
-    return Params(B, H, N, d, block_q, block_kv, topk_frac, dtype, quant_mode, router_w_per_head,
-                  alpha_per_block, flags)
+                router_w_per_head=0, alpha_per_block=0, flags=0, in_stride=None, out_stride=None) -> Params:
+    """in_stride / out_stride: (batch, head, token) element strides of q, k, v / of out; None = contiguous
+    [B, H, N, d]."""
+    p = Params(B, H, N, d, block_q, block_kv, topk_frac, dtype, quant_mode, router_w_per_head,
+               alpha_per_block, flags)
+    if in_stride is not None:
+        p.in_stride[:] = [int(x) for x in in_stride]
+    if out_stride is not None:
+        p.out_stride[:] = [int(x) for x in out_stride]
+    return p
 
 
 def sla2_version() -> int:
@@ -148,8 +156,9 @@ def sla2_router_soft(params, q, k, router_w, tau, mask_out, workspace, stream=No
 
 
 def sla2_forward(params, q, k, v, router_w, alpha, out, block_idx=None, lse=None, workspace=None,
-                 stream=None, check=True) -> int:
-    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+                 stream=None, check=True, ws_bytes=None) -> int:
+    if ws_bytes is None:                               # a raw address needs its size spelled out
+        ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     rc = _lib.sla2_forward(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(router_w), _ptr(alpha),
                            _ptr(out), _ptr(block_idx), _ptr(lse), _ptr(workspace), ws_bytes, _stream(stream))
     if check and rc != SLA2_OK:

@@ -31,8 +31,18 @@ constexpr float kE4M3Max = 448.0f;
 constexpr float kInt8Max = 127.0f;   // symmetric INT8 code range of Q and K
 constexpr float kLog2e = 1.4426950408889634f;
 
+// Where (batch b, head h, token t) of a [.., d] tensor starts, in elements: b * b_ + h * h_ + t * n.
+struct Strides {
+  long long b, h;
+  int n;
+};
+__host__ __device__ __forceinline__ size_t head_offset(const Strides& st, int bh, int H) {
+  return (size_t)(bh / H) * (size_t)st.b + (size_t)(bh % H) * (size_t)st.h;
+}
+
 // Host-side description of one call, derived from sla2_params.
 struct Shape {
+  Strides sin, sout;                         // q, k, v share `sin`; out has `sout`
   int B, H, N, d, bq, bk;
   int BH, Tm, Tn, k;
   bool bf16, smooth, w_per_head, alpha_per_block;

@@ -76,7 +76,8 @@ __device__ __forceinline__ bf16x8 row_fragment(const uint16_t* tile, int row, in
 // straight-line sequence for full and ragged tiles alike: the number of transfers in flight is then
 // the same on every path, which lets later waits be counted instead of draining everything.
 template <int D, int NW>
-__device__ __forceinline__ void dma_tile(const uint16_t* src /* first row */, int valid, uint16_t* tile, int w, int lane) {
+__device__ __forceinline__ void dma_tile(const uint16_t* src /* first row */, int row_stride /* elements */, int valid,
+                                         uint16_t* tile, int w, int lane) {
   typedef SwizzledLayout<D> L;
   constexpr int kRowsPerInstr = 1024 / (D * 2);
   constexpr int kInstrs = kTileTokens / kRowsPerInstr / NW;
@@ -86,7 +87,7 @@ __device__ __forceinline__ void dma_tile(const uint16_t* src /* first row */, in
   const char* base = reinterpret_cast<const char*>(src);
 #pragma unroll
   for (int i = 0; i < kInstrs; i++) {
-    const unsigned off = (unsigned)min(row_w + i * NW * kRowsPerInstr, valid - 1) * (unsigned)(D * 2) + col_bytes;
+    const unsigned off = (unsigned)min(row_w + i * NW * kRowsPerInstr, valid - 1) * (unsigned)(row_stride * 2) + col_bytes;
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + off),
                                      (__attribute__((address_space(3))) void*)(tile + (i * NW + w) * 512), 16, 0, 0);
   }
@@ -95,17 +96,18 @@ __device__ __forceinline__ void dma_tile(const uint16_t* src /* first row */, in
 // The same for a tile whose 64 rows all exist: no clamping, and every address is a per-lane constant
 // plus a multiple of the instruction stride, which keeps the per-tile address arithmetic scalar.
 template <int D, int NW>
-__device__ __forceinline__ void dma_tile_full(const uint16_t* src, uint16_t* tile, int w, int lane) {
+__device__ __forceinline__ void dma_tile_full(const uint16_t* src, int row_stride /* elements */, uint16_t* tile, int w,
+                                              int lane) {
   typedef SwizzledLayout<D> L;
   constexpr int kRowsPerInstr = 1024 / (D * 2);
   constexpr int kInstrs = kTileTokens / kRowsPerInstr / NW;
   const int row_w = w * kRowsPerInstr + lane / L::kChunks;
-  const unsigned lane_off = (unsigned)row_w * (unsigned)(D * 2) + 16u * (unsigned)((lane % L::kChunks) ^ L::swz(row_w));
+  const unsigned lane_off = (unsigned)row_w * (unsigned)(row_stride * 2) + 16u * (unsigned)((lane % L::kChunks) ^ L::swz(row_w));
   const char* base = reinterpret_cast<const char*>(src);
 #pragma unroll
   for (int i = 0; i < kInstrs; i++)
     __builtin_amdgcn_global_load_lds(
-        (const __attribute__((address_space(1))) void*)(base + i * (NW * kRowsPerInstr * D * 2) + lane_off),
+        (const __attribute__((address_space(1))) void*)(base + (size_t)i * (size_t)(NW * kRowsPerInstr * row_stride * 2) + lane_off),
         (__attribute__((address_space(3))) void*)(tile + (i * NW + w) * 512), 16, 0, 0);
 }
 
@@ -192,13 +194,13 @@ __device__ __forceinline__ bf16x8 kphi_fragment(const uint16_t* ktile, const flo
 // unpredicated, so they can remain in flight across a whole compute phase.
 template <int D, int NT> struct TileCopy {
   static constexpr int kLoads = kTileTokens * TileGeom<D>::kChunksPerRow / NT;
-  __device__ static __forceinline__ void load(u32x4 (&r)[kLoads], const uint16_t* src /* first row */, int valid,
-                                              int tid) {
+  __device__ static __forceinline__ void load(u32x4 (&r)[kLoads], const uint16_t* src /* first row */,
+                                              int row_stride /* elements */, int valid, int tid) {
 #pragma unroll
     for (int i = 0; i < kLoads; i++) {
       const int idx = tid + NT * i;
       const int row = min(idx / TileGeom<D>::kChunksPerRow, valid - 1), ch = idx % TileGeom<D>::kChunksPerRow;
-      r[i] = *reinterpret_cast<const u32x4*>(src + (size_t)row * D + 8 * ch);
+      r[i] = *reinterpret_cast<const u32x4*>(src + (size_t)row * row_stride + 8 * ch);
     }
   }
   __device__ static __forceinline__ void store(const u32x4 (&r)[kLoads], uint16_t* tile, int tid) {

@@ -1,6 +1,7 @@
 // Host side of libsla2: argument validation, workspace carve-up, kernel launches.
 // Declarations and their contracts are in include/sla2.h.
 #include <math.h>
+#include <stdint.h>
 #include <string.h>
 
 #include <vector>
@@ -35,6 +36,21 @@ static int make_shape(const sla2_params* p, Shape* s) {
   int k = (int)floor((double)p->topk_frac * (double)s->Tn + 0.5);
   s->k = k < 0 ? 0 : (k > s->Tn ? s->Tn : k);
   s->bf16 = p->dtype == SLA2_BF16;
+  {
+    const long long esz = s->bf16 ? 2 : 4;
+    const long long dflt[3] = {(long long)p->H * p->N * p->d, (long long)p->N * p->d, (long long)p->d};
+    Strides* dst[2] = {&s->sin, &s->sout};
+    const long long* src[2] = {p->in_stride, p->out_stride};
+    for (int x = 0; x < 2; x++) {
+      const long long* st = src[x];
+      const bool unset = st[0] == 0 && st[1] == 0 && st[2] == 0;
+      const long long b = unset ? dflt[0] : st[0], h = unset ? dflt[1] : st[1], n = unset ? dflt[2] : st[2];
+      if (b <= 0 || h <= 0 || n <= 0) return SLA2_EINVAL;
+      if (n < p->d || n >= (1 << 24)) return SLA2_EUNSUPPORTED;
+      if ((b * esz) % 16 || (h * esz) % 16 || (n * esz) % 16) return SLA2_EUNSUPPORTED;
+      dst[x]->b = b; dst[x]->h = h; dst[x]->n = (int)n;
+    }
+  }
   s->quant = (int)p->quant_mode;
   s->smooth = !(p->flags & SLA2_FLAG_NO_SMOOTH_K);
   s->w_per_head = p->router_w_per_head != 0;
@@ -73,6 +89,14 @@ static void make_layout(const Shape& s, sla2_ws_layout* L) {
   L->partial = take(BH * (size_t)s.chunks * (d * d + d) * sizeof(float));
   L->total = off;
 }
+
+// bytes from the first to one past the last element a strided [B, H, N, d] view touches
+static size_t span_bytes(const Shape& s, const Strides& st) {
+  const size_t elems = (size_t)(s.B - 1) * (size_t)st.b + (size_t)(s.H - 1) * (size_t)st.h +
+                       (size_t)(s.N - 1) * (size_t)st.n + (size_t)s.d;
+  return elems * (s.bf16 ? 2 : 4);
+}
+static bool misaligned16(const void* p) { return ((uintptr_t)p & 15u) != 0; }
 
 static bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
   uintptr_t x = (uintptr_t)a, y = (uintptr_t)b;
@@ -167,6 +191,7 @@ int sla2_router(const sla2_params* params, const void* q, const void* k, const f
   int rc = make_shape(params, &s);
   if (rc != SLA2_OK) return rc;
   if (!q || !k || !router_w || (!block_idx && s.k > 0)) return SLA2_EINVAL;
+  if (misaligned16(q) || misaligned16(k)) return SLA2_EINVAL;
   make_layout(s, &L);
   if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -186,6 +211,7 @@ int sla2_router_soft(const sla2_params* params, const void* q, const void* k, co
   int rc = make_shape(params, &s);
   if (rc != SLA2_OK) return rc;
   if (!q || !k || !router_w || !mask_out || !(tau > 0.f)) return SLA2_EINVAL;
+  if (misaligned16(q) || misaligned16(k)) return SLA2_EINVAL;
   make_layout(s, &L);
   if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
@@ -208,9 +234,10 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
   int rc = make_shape(params, &s);
   if (rc != SLA2_OK) return rc;
   if (!q || !k || !v || !router_w || !alpha || !out) return SLA2_EINVAL;
-  size_t tensor_bytes = (size_t)s.BH * s.N * s.d * (s.bf16 ? 2 : 4);
-  if (overlaps(out, tensor_bytes, q, tensor_bytes) || overlaps(out, tensor_bytes, k, tensor_bytes) ||
-      overlaps(out, tensor_bytes, v, tensor_bytes))
+  if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(out)) return SLA2_EINVAL;
+  const size_t in_bytes = span_bytes(s, s.sin), out_bytes = span_bytes(s, s.sout);
+  if (overlaps(out, out_bytes, q, in_bytes) || overlaps(out, out_bytes, k, in_bytes) ||
+      overlaps(out, out_bytes, v, in_bytes))
     return SLA2_EALIAS;
   make_layout(s, &L);
   if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
@@ -266,9 +293,10 @@ int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, 
   if (rc != SLA2_OK) return rc;
   if (!q || !k || !v || !out) return SLA2_EINVAL;
   if (!s.bf16) return SLA2_EUNSUPPORTED;
-  size_t tensor_bytes = (size_t)s.BH * s.N * s.d * 2;
-  if (overlaps(out, tensor_bytes, q, tensor_bytes) || overlaps(out, tensor_bytes, k, tensor_bytes) ||
-      overlaps(out, tensor_bytes, v, tensor_bytes))
+  if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(out)) return SLA2_EINVAL;
+  const size_t in_bytes = span_bytes(s, s.sin), out_bytes = span_bytes(s, s.sout);
+  if (overlaps(out, out_bytes, q, in_bytes) || overlaps(out, out_bytes, k, in_bytes) ||
+      overlaps(out, out_bytes, v, in_bytes))
     return SLA2_EALIAS;
   hipStream_t st = (hipStream_t)hip_stream;
   g_prof.calls++;

@@ -21,7 +21,8 @@ template <int D>
 __global__ __launch_bounds__(256) void kv_state_f32_kernel(const float* __restrict__ k, const float* __restrict__ v,
                                                            const double* __restrict__ k_mean,
                                                            float* __restrict__ k_stats, float* __restrict__ partial,
-                                                           int N, int Tn, int chunks, int blocks_per_chunk) {
+                                                           Strides sin, int H, int N, int Tn, int chunks,
+                                                           int blocks_per_chunk) {
   constexpr int LD = D + 1;       // odd stride: a column of tokens falls into distinct banks
   constexpr int MT = D / 16;      // micro-tile edge: each thread owns MT x MT entries of h
   extern __shared__ float smem[];
@@ -32,8 +33,8 @@ __global__ __launch_bounds__(256) void kv_state_f32_kernel(const float* __restri
   if (threadIdx.x < D) mu_s[threadIdx.x] = (float)k_mean[(size_t)bh * D + threadIdx.x];
   __syncthreads();
   const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
-  const float* kh = k + (size_t)bh * N * D;
-  const float* vh = v + (size_t)bh * N * D;
+  const float* kh = k + head_offset(sin, bh, H);
+  const float* vh = v + head_offset(sin, bh, H);
   const int j0 = chunk * blocks_per_chunk, j1 = min(Tn, j0 + blocks_per_chunk);
 
   float hacc[MT][MT];
@@ -48,8 +49,8 @@ __global__ __launch_bounds__(256) void kv_state_f32_kernel(const float* __restri
     for (int idx = tid; idx < kBK * D; idx += 256) {
       int t = idx / D, c = idx % D;
       bool ok = t < valid;
-      ks[t * LD + c] = ok ? kh[(size_t)(t0 + t) * D + c] - mu_s[c] : 0.f;
-      vs[t * LD + c] = ok ? vh[(size_t)(t0 + t) * D + c] : 0.f;
+      ks[t * LD + c] = ok ? kh[(size_t)(t0 + t) * sin.n + c] - mu_s[c] : 0.f;
+      vs[t * LD + c] = ok ? vh[(size_t)(t0 + t) * sin.n + c] : 0.f;
     }
     __syncthreads();
     {  // softmax over the channels of each token, 4 threads per token
@@ -138,10 +139,10 @@ hipError_t launch_kv_state_f32(const Shape& s, const float* k, const float* v, c
     configured = true;
   }
   if (s.d == 128)
-    kv_state_f32_kernel<128><<<grid, 256, smem, stream>>>(k, v, k_mean, k_stats, partial, s.N, s.Tn, s.chunks,
+    kv_state_f32_kernel<128><<<grid, 256, smem, stream>>>(k, v, k_mean, k_stats, partial, s.sin, s.H, s.N, s.Tn, s.chunks,
                                                           s.blocks_per_chunk);
   else
-    kv_state_f32_kernel<64><<<grid, 256, smem, stream>>>(k, v, k_mean, k_stats, partial, s.N, s.Tn, s.chunks,
+    kv_state_f32_kernel<64><<<grid, 256, smem, stream>>>(k, v, k_mean, k_stats, partial, s.sin, s.H, s.N, s.Tn, s.chunks,
                                                          s.blocks_per_chunk);
   return hipGetLastError();
 }
@@ -161,8 +162,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
                                                        const float* __restrict__ z_total,
                                                        const int32_t* __restrict__ block_idx,
                                                        const float* __restrict__ alpha, float* __restrict__ out,
-                                                       float* __restrict__ lse, int H, int N, int bq, int Tm, int Tn,
-                                                       int ksel, int alpha_per_block) {
+                                                       float* __restrict__ lse, Strides sin, Strides sout, int H,
+                                                       int N, int bq, int Tm, int Tn, int ksel, int alpha_per_block) {
   constexpr int LD = D + 1;
   constexpr int LP = kBK + 1;
   constexpr int MT = D / 16;       // h micro-tile edge
@@ -184,16 +185,16 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
   const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
   const int row0 = i * bq + part * kRowsF32;          // first query row of this workgroup
   const int rows_valid = max(0, min(kRowsF32, min(N, (i + 1) * bq) - row0));
-  const float* qh = q + (size_t)bh * N * D;
-  const float* kh = k + (size_t)bh * N * D;
-  const float* vh = v + (size_t)bh * N * D;
+  const float* qh = q + head_offset(sin, bh, H);
+  const float* kh = k + head_offset(sin, bh, H);
+  const float* vh = v + head_offset(sin, bh, H);
   const int32_t* sel = block_idx + ((size_t)bh * Tm + i) * ksel;
   const float rscale = rsqrtf((float)D);
   if (rows_valid == 0) return;                        // second half of a short last query block
 
   for (int idx = tid; idx < kRowsF32 * D; idx += 256) {
     int r = idx / D, c = idx % D;
-    qs[r * LD + c] = r < rows_valid ? qh[(size_t)(row0 + r) * D + c] : 0.f;
+    qs[r * LD + c] = r < rows_valid ? qh[(size_t)(row0 + r) * sin.n + c] : 0.f;
   }
 
   float m_run[4], l_run[4], oacc[4][OC], hacc[MT][MT];
@@ -216,8 +217,8 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
     for (int idx = tid; idx < kBK * D; idx += 256) {
       int t = idx / D, c = idx % D;
       bool ok = t < valid;
-      ks[t * LD + c] = ok ? kh[(size_t)(t0 + t) * D + c] - (float)k_mean[(size_t)bh * D + c] : 0.f;
-      vs[t * LD + c] = ok ? vh[(size_t)(t0 + t) * D + c] : 0.f;
+      ks[t * LD + c] = ok ? kh[(size_t)(t0 + t) * sin.n + c] - (float)k_mean[(size_t)bh * D + c] : 0.f;
+      vs[t * LD + c] = ok ? vh[(size_t)(t0 + t) * sin.n + c] : 0.f;
     }
     __syncthreads();
     // S = Q K'^T / sqrt(d): rows 4 ty + a, key tokens tx + 16 b
@@ -361,7 +362,7 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
     if (r >= rows_valid) continue;
     const float inv_l = l_run[a] > 0.f ? 1.f / l_run[a] : 0.f;
     const float inv_den = all_selected ? 0.f : 1.f / den[a];
-    float* o = out + ((size_t)bh * N + row0 + r) * D;
+    float* o = out + head_offset(sout, bh, H) + (size_t)(row0 + r) * sout.n;
 #pragma unroll
     for (int b = 0; b < OC; b++) o[tx + 16 * b] = al * oacc[a][b] * inv_l + (1.f - al) * lacc[a][b] * inv_den;
     if (lse && tx == 0) lse[(size_t)bh * N + row0 + r] = l_run[a] > 0.f ? m_run[a] + __logf(l_run[a]) : -INFINITY;
@@ -383,7 +384,8 @@ static hipError_t launch_attn_f32_t(const Shape& s, const float* q, const float*
   }
   dim3 grid((unsigned)((size_t)s.BH * s.Tm * (s.bq / kRowsF32)));
   attn_f32_kernel<D><<<grid, 256, smem, stream>>>(q, k, v, k_mean, k_stats, h_total, z_total, block_idx, alpha, out,
-                                                  lse, s.H, s.N, s.bq, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
+                                                  lse, s.sin, s.sout, s.H, s.N, s.bq, s.Tm, s.Tn, s.k,
+                                                  s.alpha_per_block ? 1 : 0);
   return hipGetLastError();
 }
 

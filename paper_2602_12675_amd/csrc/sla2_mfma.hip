@@ -68,7 +68,8 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
                                                             uint16_t* __restrict__ k_phi, float* __restrict__ z_blocks,
                                                             uint8_t* __restrict__ k_codes, float* __restrict__ k_scale,
                                                             uint8_t* __restrict__ v_codes, float* __restrict__ v_scale,
-                                                            int N, int Tn, int chunks, int blocks_per_chunk) {
+                                                            Strides sin, int H, int N, int Tn, int chunks,
+                                                            int blocks_per_chunk) {
   constexpr int LD = TileGeom<D>::kLd;
   typedef HSplit<D, 4> HS;
   __shared__ __attribute__((aligned(16))) uint16_t ktile[kTileTokens * LD];
@@ -79,8 +80,8 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
   __shared__ float red_v[4];
   const int bh = blockIdx.x / chunks, chunk = blockIdx.x % chunks;
   const int tid = threadIdx.x, lane = tid % kWave, w = tid / kWave, g = lane / 32;
-  const uint16_t* kh = k + (size_t)bh * N * D;
-  const uint16_t* vh = v + (size_t)bh * N * D;
+  const uint16_t* kh = k + head_offset(sin, bh, H);
+  const uint16_t* vh = v + head_offset(sin, bh, H);
   const int j0 = chunk * blocks_per_chunk, j1 = min(Tn, j0 + blocks_per_chunk);
   const int mt0 = HS::mt0(w), nt0 = HS::nt0(w);
 
@@ -105,8 +106,8 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
   u32x4 kr[TC::kLoads], vr[TC::kLoads];
   if (j0 < j1) {
     const int valid = min(kTileTokens, N - j0 * kTileTokens);
-    TC::load(kr, kh + (size_t)j0 * kTileTokens * D, valid, tid);
-    TC::load(vr, vh + (size_t)j0 * kTileTokens * D, valid, tid);
+    TC::load(kr, kh + (size_t)j0 * kTileTokens * sin.n, sin.n, valid, tid);
+    TC::load(vr, vh + (size_t)j0 * kTileTokens * sin.n, sin.n, valid, tid);
   }
   for (int j = j0; j < j1; j++) {
     const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
@@ -116,8 +117,8 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
     TC::store(vr, vtile, tid);
     if (j + 1 < j1) {
       const int nvalid = min(kTileTokens, N - (j + 1) * kTileTokens);
-      TC::load(kr, kh + (size_t)(j + 1) * kTileTokens * D, nvalid, tid);
-      TC::load(vr, vh + (size_t)(j + 1) * kTileTokens * D, nvalid, tid);
+      TC::load(kr, kh + (size_t)(j + 1) * kTileTokens * sin.n, sin.n, nvalid, tid);
+      TC::load(vr, vh + (size_t)(j + 1) * kTileTokens * sin.n, sin.n, nvalid, tid);
     }
     __syncthreads();
     SLA2_PHASE_MARK(1)
@@ -284,7 +285,7 @@ hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_
   dim3 grid((unsigned)(s.BH * s.chunks));
 #define SLA2_KV(DD, QQ)                                                                                          \
   kv_state_bf16_kernel<DD, QQ><<<grid, 256, 0, stream>>>(k, v, k_mean, k_stats, partial, k_phi, z_blocks, k_codes, \
-                                                         k_scale, v_codes, v_scale, s.N, s.Tn, s.chunks,          \
+                                                         k_scale, v_codes, v_scale, s.sin, s.H, s.N, s.Tn, s.chunks, \
                                                          s.blocks_per_chunk)
 #define SLA2_KV_D(DD)                                                                                  \
   do {                                                                                                 \
@@ -423,8 +424,8 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     const uint8_t* __restrict__ k_codes, const float* __restrict__ k_scale, const uint8_t* __restrict__ v_codes,
     const float* __restrict__ v_scale, const float* __restrict__ h_total,
     const float* __restrict__ z_total, const int32_t* __restrict__ block_idx, const float* __restrict__ alpha,
-    uint16_t* __restrict__ out, float* __restrict__ lse, int H, int N, int Tm, int Tn, int ksel, int alpha_per_block,
-    int total_blocks) {
+    uint16_t* __restrict__ out, float* __restrict__ lse, Strides sin, Strides sout, int H, int N, int Tm, int Tn,
+    int ksel, int alpha_per_block, int total_blocks) {
   // FP8 below means "8-bit codes of Q and K": everything the two low-bit modes share.  INT8 marks the
   // places where the integer mode differs (the quantiser of Q and the Q K^T product).
   // FP8V: V is quantised too and P V runs as an FP8 product (the linear branch still reads the bf16 V).
@@ -463,9 +464,10 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   const int w = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave index, known to be uniform
   const int row0 = i * BQ;
   const int rows_valid = min(BQ, N - row0);
-  const uint16_t* qh = q + (size_t)bh * N * D;
-  const uint16_t* kh = k + (size_t)bh * N * D;
-  const uint16_t* vh = v + (size_t)bh * N * D;
+  const uint16_t* qh = q + head_offset(sin, bh, H);
+  const uint16_t* kh = k + head_offset(sin, bh, H);
+  const uint16_t* vh = v + head_offset(sin, bh, H);
+  const int tok_stride = sin.n;                      // elements between consecutive tokens of q, k, v
   const int32_t* sel = DENSE ? nullptr : block_idx + ((size_t)bh * Tm + i) * ksel;
   const int ntiles = DENSE ? Tn : ksel;
   const int mt0 = HS::mt0(w), nt0 = HS::nt0(w);
@@ -485,10 +487,10 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   auto dma = [&](int j, int buf) {
     const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
     if constexpr (FP8) dma_tile8<D, NW>(k_codes + (blk0 + j) * kTileTokens * D, kbuf(buf), w, lane);
-    else if (kManual && valid == kTileTokens) dma_tile_full<D, NW>(kh + (size_t)t0 * D, reinterpret_cast<uint16_t*>(kbuf(buf)), w, lane);
-    else dma_tile<D, NW>(kh + (size_t)t0 * D, valid, reinterpret_cast<uint16_t*>(kbuf(buf)), w, lane);
-    if (kManual && valid == kTileTokens) dma_tile_full<D, NW>(vh + (size_t)t0 * D, vbuf(buf), w, lane);
-    else dma_tile<D, NW>(vh + (size_t)t0 * D, valid, vbuf(buf), w, lane);
+    else if (kManual && valid == kTileTokens) dma_tile_full<D, NW>(kh + (size_t)t0 * tok_stride, tok_stride, reinterpret_cast<uint16_t*>(kbuf(buf)), w, lane);
+    else dma_tile<D, NW>(kh + (size_t)t0 * tok_stride, tok_stride, valid, reinterpret_cast<uint16_t*>(kbuf(buf)), w, lane);
+    if (kManual && valid == kTileTokens) dma_tile_full<D, NW>(vh + (size_t)t0 * tok_stride, tok_stride, vbuf(buf), w, lane);
+    else dma_tile<D, NW>(vh + (size_t)t0 * tok_stride, tok_stride, valid, vbuf(buf), w, lane);
     if constexpr (FP8V) dma_tile_vq<D, NW>(v_codes + (blk0 + j) * kTileTokens * D, vqbuf(buf), w, lane);
   };
 
@@ -498,7 +500,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   bf16x8 qf[KS];
   {
     const int r = min(32 * w + lane % 32, rows_valid - 1);   // rows past the end repeat the last one; never stored
-    const uint16_t* src = qh + (size_t)(row0 + r) * D;
+    const uint16_t* src = qh + (size_t)(row0 + r) * tok_stride;
     // bf16 product: fragment ks = columns 16 ks + 8 g + 0..7.  FP8 product (64 deep): the lane's
     // operand of step ks2 is columns 64 ks2 + 32 g + 0..31, held as fragments 4 ks2 + 0..3.
     // INT8 product (32 deep): columns 32 ks4 + 16 g + 0..15, fragments 2 ks4 + 0..1.
@@ -873,7 +875,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     // the bf16 Q fragments were dropped after quantisation to keep two waves per SIMD; the linear
     // branch needs them once more
     const int r = min(32 * w + lane % 32, rows_valid - 1);
-    const uint16_t* src = qh + (size_t)(row0 + r) * D + 8 * g;
+    const uint16_t* src = qh + (size_t)(row0 + r) * tok_stride + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
   }
@@ -968,10 +970,10 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       *reinterpret_cast<bf16x4*>(os + qrow * LD + 32 * et + 8 * v4 + 4 * g) = pk;
     }
   __syncthreads();
-  uint16_t* oh = out + ((size_t)bh * N + row0) * D;
+  uint16_t* oh = out + head_offset(sout, bh, H) + (size_t)row0 * sout.n;
   for (int idx = tid; idx < BQ * (D / 8); idx += NT) {
     const int r = idx / (D / 8), ch = idx % (D / 8);
-    if (r < rows_valid) *reinterpret_cast<u32x4*>(oh + (size_t)r * D + 8 * ch) = *reinterpret_cast<const u32x4*>(os + r * LD + 8 * ch);
+    if (r < rows_valid) *reinterpret_cast<u32x4*>(oh + (size_t)r * sout.n + 8 * ch) = *reinterpret_cast<const u32x4*>(os + r * LD + 8 * ch);
   }
   SLA2_PHASE_MARK(6)
 }
@@ -1007,7 +1009,7 @@ static hipError_t launch_attn_t(const Shape& s, const AttnArgs& a, hipStream_t s
   attn_mfma_kernel<D, BQ, MODE><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(
       a.q, a.k, a.v, a.k_mean, a.k_phi, a.z_blocks, a.k_fp8, a.k_scale, a.v_codes, a.v_scale, a.h_total, a.z_total,
       a.block_idx, a.alpha,
-      a.out, a.lse, s.H, s.N, Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0, total);
+      a.out, a.lse, s.sin, s.sout, s.H, s.N, Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0, total);
   return hipGetLastError();
 }
 

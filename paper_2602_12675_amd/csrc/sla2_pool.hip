@@ -67,7 +67,8 @@ __device__ void fold_router_row(const float* __restrict__ Wq, const float* __res
 template <typename T>
 __global__ __launch_bounds__(256) void block_sums_kernel(const T* __restrict__ q, const T* __restrict__ k,
                                                          double* __restrict__ q_sum, double* __restrict__ k_sum,
-                                                         int N, int d, int bq, int bk, int Tm, int Tn, int fold_blocks,
+                                                         Strides sin, int H, int N, int d, int bq, int bk, int Tm,
+                                                         int Tn, int fold_blocks,
                                                          const float* __restrict__ router_w,
                                                          double* __restrict__ router_m) {
   constexpr int EPL = Vec16<T>::kElems;
@@ -87,7 +88,7 @@ __global__ __launch_bounds__(256) void block_sums_kernel(const T* __restrict__ q
   const bool is_k = t >= Tm;
   if (is_k) t -= Tm;
   const int b = is_k ? bk : bq;
-  const T* x = (is_k ? k : q) + (size_t)bh * N * d;
+  const T* x = (is_k ? k : q) + head_offset(sin, bh, H);
   double* out = (is_k ? k_sum + ((size_t)bh * Tn + t) * d : q_sum + ((size_t)bh * Tm + t) * d);
 
   const int tpr = d / EPL;                   // threads per row
@@ -100,8 +101,8 @@ __global__ __launch_bounds__(256) void block_sums_kernel(const T* __restrict__ q
   double acc[EPL];
 #pragma unroll
   for (int e = 0; e < EPL; e++) acc[e] = 0.0;
-  const T* px = x + (size_t)(row0 + rg) * d + col;
-  const size_t pass_stride = (size_t)rpp * d;
+  const T* px = x + (size_t)(row0 + rg) * sin.n + col;
+  const size_t pass_stride = (size_t)rpp * sin.n;
   // A full block is a known number of passes: every load of the thread is issued before the first
   // sum (a loop with a run-time trip count leaves one load in flight at a time and a round trip
   // to memory per pass).
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(256) void block_sums_kernel(const T* __restrict__ q
 #pragma unroll 4
     for (int r = rg; r < rows; r += rpp) {
       float f[EPL];
-      Vec16<T>::unpack(Vec16<T>::load_raw(x + (size_t)(row0 + r) * d + col), f);
+      Vec16<T>::unpack(Vec16<T>::load_raw(x + (size_t)(row0 + r) * sin.n + col), f);
 #pragma unroll
       for (int e = 0; e < EPL; e++) acc[e] += (double)f[e];
     }
@@ -148,11 +149,12 @@ hipError_t launch_block_sums(const Shape& s, const void* q, const void* k, const
   const int fold_blocks = (s.w_per_head ? s.H : 1) * s.d;
   dim3 grid((unsigned)(s.BH * (s.Tm + s.Tn) + fold_blocks));
   if (s.bf16)
-    block_sums_kernel<uint16_t><<<grid, 256, 0, stream>>>((const uint16_t*)q, (const uint16_t*)k, q_sum, k_sum, s.N,
-                                                           s.d, s.bq, s.bk, s.Tm, s.Tn, fold_blocks, router_w, router_m);
+    block_sums_kernel<uint16_t><<<grid, 256, 0, stream>>>((const uint16_t*)q, (const uint16_t*)k, q_sum, k_sum, s.sin,
+                                                           s.H, s.N, s.d, s.bq, s.bk, s.Tm, s.Tn, fold_blocks, router_w,
+                                                           router_m);
   else
-    block_sums_kernel<float><<<grid, 256, 0, stream>>>((const float*)q, (const float*)k, q_sum, k_sum, s.N, s.d, s.bq,
-                                                        s.bk, s.Tm, s.Tn, fold_blocks, router_w, router_m);
+    block_sums_kernel<float><<<grid, 256, 0, stream>>>((const float*)q, (const float*)k, q_sum, k_sum, s.sin, s.H, s.N,
+                                                        s.d, s.bq, s.bk, s.Tm, s.Tn, fold_blocks, router_w, router_m);
   return hipGetLastError();
 }
 

@@ -36,7 +36,7 @@ def test_every_declared_symbol_is_exported(api):
 
 
 def test_struct_sizes_match_header(api):
-    assert ctypes.sizeof(api.Params) == 12 * 4
+    assert ctypes.sizeof(api.Params) == 12 * 4 + 6 * 8
     assert ctypes.sizeof(api.WsLayout) == 16 * ctypes.sizeof(ctypes.c_size_t)
 
 
@@ -93,7 +93,7 @@ def test_null_alias_and_workspace_errors(api):
     assert call(a) == api.SLA2_EINVAL
     a = list(ok_args); a[5] = None
     assert call(a) == api.SLA2_EINVAL
-    a = list(ok_args); a[5] = q + tensor - 4           # out overlaps the end of q
+    a = list(ok_args); a[5] = q + tensor - 16          # out overlaps the end of q
     assert call(a) == api.SLA2_EALIAS
     a = list(ok_args); a[5] = v
     assert call(a) == api.SLA2_EALIAS
@@ -103,3 +103,33 @@ def test_null_alias_and_workspace_errors(api):
     assert call(a) == api.SLA2_EWORKSPACE
     a = list(ok_args); a[8] = ws + 8                   # misaligned
     assert call(a) == api.SLA2_EWORKSPACE
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(in_stride=(0, 64, 64)), "EINVAL"),                       # partly set
+    (dict(in_stride=(-1, 64 * 1024, 64)), "EINVAL"),
+    (dict(in_stride=(2 * 1024 * 64, 1024 * 64, 32)), "EUNSUPPORTED"),    # token stride below d
+    (dict(in_stride=(2 * 1024 * 68, 1024 * 68, 68)), "EUNSUPPORTED"),    # 136-byte rows: not a multiple of 16 bytes
+    (dict(out_stride=(2 * 1024 * 64, 60, 2 * 64)), "EUNSUPPORTED"),      # head stride not a multiple of 16 bytes
+    (dict(in_stride=(1 << 40, 64, 1 << 24)), "EUNSUPPORTED"),            # token stride too large
+])
+def test_bad_strides_are_rejected_on_the_host(api, kw, status):
+    p = api.make_params(1, 2, 1024, 64, 64, 64, 0.125, dtype=api.SLA2_BF16, **kw)
+    assert api.sla2_workspace_bytes(p) == 0
+    rc = api.sla2_forward(p, 256, 256, 256, 256, 256, 1 << 30, workspace=None, check=False)
+    assert rc == getattr(api, "SLA2_" + status)
+
+
+def test_strided_alias_and_alignment_checks(api):
+    # [B, N, H, d] views of a packed projection: spans of q, k, v interleave, out may not touch them
+    B, H, N, d = 1, 2, 1024, 64
+    st = (N * 3 * H * d, d, 3 * H * d)
+    p = api.make_params(B, H, N, d, 64, 64, 0.125, dtype=api.SLA2_BF16, in_stride=st, out_stride=(N * H * d, d, H * d))
+    need = api.sla2_workspace_bytes(p)
+    assert need > 0
+    base, ws = 1 << 20, 64 << 20
+    q, k, v = base, base + H * d * 2, base + 2 * H * d * 2
+    span = ((N - 1) * st[2] + (H - 1) * st[1] + d) * 2
+    assert api.sla2_forward(p, q, k, v, 256, 256, q + span - 16, workspace=ws, ws_bytes=need, check=False) == api.SLA2_EALIAS
+    assert api.sla2_forward(p, q, k, v, 256, 256, q + 8, workspace=ws, ws_bytes=need, check=False) == api.SLA2_EINVAL
+    assert api.sla2_forward(p, q + 2, k, v, 256, 256, 1 << 30, workspace=ws, ws_bytes=need, check=False) == api.SLA2_EINVAL
