@@ -606,6 +606,10 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     j_cur = j_nxt;
     j_nxt = j_nn;
     const uint16_t* vt = vbuf(buf);
+    // Two waves share a SIMD.  The one that is issuing matrix products is given the higher issue priority, so
+    // that the matrix pipe is fed while the other wave's softmax fills the gaps (measured: 2 % on the
+    // sparse modes; the dense comparator, all of whose waves are in step, loses with it).
+    if constexpr (!DENSE) __builtin_amdgcn_s_setprio(2);
     // ---- S^T = K Q^T (keys x query rows), two 32-key halves ----
     f32x16 sacc[2];
 #pragma unroll
@@ -686,6 +690,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         for (int mt = 0; mt < 2; mt++)
           sacc[mt] = mfma_bf16(row_fragment<SL>(kt, 32 * mt + lane % 32, 16 * ks + 8 * g), qf[ks], sacc[mt]);
     }
+    if constexpr (!DENSE) __builtin_amdgcn_s_setprio(0);   // softmax: the other wave's matrix products go first
     SLA2_PHASE_MARK(1)
     // ---- online softmax of this lane's query row over the 64 keys ----
     const float c1 = FP8 ? c0 * s_q * sk : c0;       // dequantisation folded into the score scale
@@ -741,6 +746,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       for (int e = 0; e < 16; e++) oacc[et][e] *= corr_o;
 
     SLA2_PHASE_MARK(2)
+    if constexpr (!DENSE) __builtin_amdgcn_s_setprio(2);   // matrix products again
     if constexpr (!DENSE) {
       if constexpr (kManual) {
         // the register loads issued at the top have landed; the tile transfer may still be in flight
@@ -851,6 +857,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   }
   SLA2_PHASE_MARK(5)
 
+  if constexpr (!DENSE) __builtin_amdgcn_s_setprio(0);
   // ================= epilogue =================
   const float inv_l = l_run > 0.f ? 1.f / l_run : 0.f;
   const int qrow = 32 * w + lane % 32;               // this lane's query row inside the block
