@@ -2,8 +2,9 @@
 //
 //   kv_state_bf16   per key block j of a head: K^phi_j = softmax_d(K_j - colmean K), written out as bf16
 //                   MFMA operand fragments; z_j = colsum(K^phi_j); per-chunk partial sums of
-//                   h_j = (K^phi_j)^T V_j and z_j (reduced to the per-head totals by kv_total); in FP8
-//                   mode also the e4m3 codes of K - colmean K with one scale per key block (Sec. 5).
+//                   h_j = (K^phi_j)^T V_j and z_j (reduced to the per-head totals by kv_total); in the
+//                   low-bit modes also the e4m3 or INT8 codes of K - colmean K with one scale per key
+//                   block, and, when V is quantised too, the e4m3 codes of V in operand order (Sec. 5).
 //   attn_mfma       one workgroup per query block i:
 //                     sparse branch over the selected key/value blocks, ascending (online softmax);
 //                     the d x d state of exactly those blocks, sum_sel (K^phi_j)^T V_j, from the stored
@@ -14,8 +15,9 @@
 //                   The same kernel with the block list replaced by 0..T_n-1 and the linear branch
 //                   compiled out is the dense attention comparator.
 //
-// All products run as v_mfma_f32_32x32x16_bf16 (FP8 mode: Q K^T as v_mfma_f32_32x32x16_fp8_fp8) with
-// fp32 accumulation.  Scores are kept transposed (S^T = K Q^T) so that one lane owns one query row:
+// Products run as v_mfma_f32_32x32x16_bf16 with fp32 accumulation.  In the low-bit modes (Sec. 5) Q K^T
+// runs on 8-bit codes: 64-deep v_mfma_f32_32x32x64_f8f6f4 (e4m3) or 32-deep v_mfma_i32_32x32x32_i8 (INT8);
+// with V quantised as well, P V is a 64-deep FP8 product too.  Scores are kept transposed (S^T = K Q^T) so that one lane owns one query row:
 // row maxima and sums are in-lane reductions plus one exchange between the two lane halves, and
 // the probabilities go back into the next product as its B operand without leaving registers.
 #include "mfma_tiles.h"
@@ -305,9 +307,6 @@ hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_
 constexpr int kXcds = 8;
 enum AttnMode { kSparseBf16 = 0, kSparseFp8 = 1, kDenseBf16 = 2, kSparseInt8 = 3, kSparseFp8V = 4 };
 
-__device__ __forceinline__ f32x16 mfma_fp8(long a, long b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_fp8_fp8(a, b, c, 0, 0, 0);
-}
 
 // LDS carve-up.  Loop: two buffers, each one K tile (bf16, or 8-bit codes), one V tile (bf16) and, when
 // V is quantised for the second product, one tile of its codes,
