@@ -28,6 +28,9 @@ independently of itself) live in tests/test_oracle_pins.py:
                              complement identity; hand-worked micro case
   forward_head               N x N expanded-mask evaluation of Eq. 13-14;
                              constant-V invariance; block permutation
+  backward_head              automatic differentiation (library autograd, float64)
+                             of the N x N expanded-mask evaluation of Eq. 13-14;
+                             central differences
   e4m3_round                 nearest-with-ties-to-even search over the table of
                              all 256 codes built from the format's definition
   quant_block_int8           codes against a brute-force nearest-integer search;
@@ -445,6 +448,81 @@ def forward_head(Q, K, V, Wq, Wk, alpha, topk_frac: float, b_q: int, b_k: int,
     a_rows = np.repeat(a, b_q)[:N, None]
     O = a_rows * O_s + (1.0 - a_rows) * O_l                 # Eq. 13
     return dict(O=O, O_s=O_s, O_l=O_l, L=L, sel=sel, R=R, H=H, Z=Z)
+
+
+# --------------------------------------------------------------------------- #
+# backward pass (Alg. 3 of the appendix, plus the steps it leaves to automatic
+# differentiation: phi, the smoothing of K, the mix of Eq. 13)
+# --------------------------------------------------------------------------- #
+def backward_head(Q, K, V, sel, alpha, dO, b_q: int, b_k: int, smooth: bool = True):
+    """Gradients of one head of the un-quantised operator with respect to Q, K,
+    V and alpha, for a fixed block mask `sel` (hard Top-k passes no gradient to
+    the router; Sec. 6.1).  dO: [N, d], the gradient of the output of Eq. 13.
+    Sec. 5: the backward pass is always taken in high precision from the
+    original Q, K, V, whatever precision the forward ran in.
+
+    Steps, in the notation of Alg. 3 (P is the normalised softmax over the
+    selected positions, P = exp(S - L)):
+
+      mix         dO^s = a dO,  dO^l = (1 - a) dO,  d alpha_i = sum_rows dO . (O^s - O^l)
+      D           D^s = rowsum(dO^s (.) O^s),  D^l = rowsum(dO^l (.) O^l)
+      per i       dH_i = (Q^phi_i / (Q^phi_i Z_i))^T dO^l_i,   dZ_i = -(Q^phi_i / (Q^phi_i Z_i))^T D^l_i
+                  dQ^phi_i = (dO^l_i H_i^T - D^l_i Z_i^T) / (Q^phi_i Z_i)
+      per (i, j)  M_c = 1:  dV_j += P^T dO^s_i,  dP = dO^s_i V_j^T,  dS = P (.) (dP - D^s_i),
+                            dQ_i += dS K_j / sqrt(d),  dK_j += dS^T Q_i / sqrt(d)
+                  M_c = 0:  dH += dH_i,  dZ += dZ_i
+      per j       dK^phi_j = V_j dH^T + 1 dZ^T,   dV_j += K^phi_j dH
+      phi         y = softmax(x):  dx = y (.) (dy - rowsum(dy (.) y)), for Q^phi and K^phi
+      smoothing   K' = K - colmean(K):  dK = dK' - colmean(dK')
+
+    The 1/sqrt(d) of the score is written out (Alg. 3 leaves it inside S).  An
+    empty branch contributes nothing.  Returns dict dQ, dK, dV [N, d], dalpha [T_m]
+    (one entry per query block; a per-head alpha takes their sum) and the
+    intermediates dQphi, dKphi, Ds, Dl."""
+    N, d = Q.shape
+    T_m, T_n = num_blocks(N, b_q), num_blocks(N, b_k)
+    Ks = smooth_k(K) if smooth else K
+    O_s, L = sparse_branch(Q, Ks, V, sel, b_q, b_k)
+    O_l, H, Z = linear_branch(Q, Ks, V, sel, b_q, b_k)
+    a_blk = np.broadcast_to(np.asarray(alpha, dtype=np.float64).reshape(-1), (T_m,)) if np.ndim(alpha) \
+        else np.full((T_m,), float(alpha))
+    a_rows = np.repeat(a_blk, b_q)[:N, None]
+    dOs, dOl = a_rows * dO, (1.0 - a_rows) * dO
+    mix = (dO * (O_s - O_l)).sum(axis=1)
+    dalpha = np.array([mix[i * b_q:min(N, (i + 1) * b_q)].sum() for i in range(T_m)])
+    Ds, Dl = (dOs * O_s).sum(axis=1), (dOl * O_l).sum(axis=1)
+    Qphi, Kphi = phi(Q), phi(Ks)
+    notM = ~mask_from_sel(sel, T_n)
+    rscale = 1.0 / math.sqrt(d)
+    dQ, dKs, dV = np.zeros((N, d)), np.zeros((N, d)), np.zeros((N, d))
+    dQphi, dKphi = np.zeros((N, d)), np.zeros((N, d))
+    dH_i, dZ_i = np.zeros((T_m, d, d)), np.zeros((T_m, d))
+    for i in range(T_m):
+        r0, r1 = i * b_q, min(N, (i + 1) * b_q)
+        if notM[i].any():                                   # linear branch of this query block exists
+            w = Qphi[r0:r1] / (Qphi[r0:r1] @ Z[i])[:, None]
+            dH_i[i] = w.T @ dOl[r0:r1]
+            dZ_i[i] = -(w.T @ Dl[r0:r1])
+            dQphi[r0:r1] = (dOl[r0:r1] @ H[i].T - np.outer(Dl[r0:r1], Z[i])) / (Qphi[r0:r1] @ Z[i])[:, None]
+        for j in sel[i]:                                    # M_c[i, j] = 1
+            c0, c1 = j * b_k, min(N, (j + 1) * b_k)
+            S = Q[r0:r1] @ Ks[c0:c1].T * rscale
+            P = np.exp(S - L[r0:r1, None])
+            dV[c0:c1] += P.T @ dOs[r0:r1]
+            dP = dOs[r0:r1] @ V[c0:c1].T
+            dS = P * (dP - Ds[r0:r1, None])
+            dQ[r0:r1] += dS @ Ks[c0:c1] * rscale
+            dKs[c0:c1] += dS.T @ Q[r0:r1] * rscale
+    for j in range(T_n):
+        c0, c1 = j * b_k, min(N, (j + 1) * b_k)
+        dH = dH_i[notM[:, j]].sum(axis=0)                   # M_c[i, j] = 0
+        dZ = dZ_i[notM[:, j]].sum(axis=0)
+        dKphi[c0:c1] = V[c0:c1] @ dH.T + dZ[None, :]
+        dV[c0:c1] += Kphi[c0:c1] @ dH
+    dQ += Qphi * (dQphi - (dQphi * Qphi).sum(axis=1, keepdims=True))
+    dKs += Kphi * (dKphi - (dKphi * Kphi).sum(axis=1, keepdims=True))
+    dK = dKs - dKs.mean(axis=0, keepdims=True) if smooth else dKs
+    return dict(dQ=dQ, dK=dK, dV=dV, dalpha=dalpha, dQphi=dQphi, dKphi=dKphi, Ds=Ds, Dl=Dl)
 
 
 def forward(q, k, v, router_w, alpha, topk_frac: float, b_q: int, b_k: int,

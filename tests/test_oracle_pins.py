@@ -427,6 +427,71 @@ def test_lowbit_products_are_exact_in_float64():
     assert all(F(S[i, j]) == exact[i, j] for i in range(8) for j in range(8))
 
 
+# ---- backward pass (Alg. 3) ------------------------------------------------- #
+def _expanded_forward_torch(Q, K, V, M, a_rows, smooth):
+    """Eq. 13-14 with the N x N mask, in library tensor ops (no blocks, no online softmax)."""
+    import torch
+    d = Q.shape[1]
+    Ks = K - K.mean(dim=0, keepdim=True) if smooth else K
+    S = (Q @ Ks.T) / math.sqrt(d)
+    S = S.masked_fill(~M, float("-inf"))
+    Ps = torch.softmax(S, dim=1)
+    Ps = torch.nan_to_num(Ps, nan=0.0)                 # rows with no selected key
+    Os = Ps @ V
+    A = (torch.softmax(Q, dim=1) @ torch.softmax(Ks, dim=1).T) * (~M)
+    den = A.sum(dim=1, keepdim=True)
+    Ol = torch.where(den > 0, (A @ V) / torch.where(den > 0, den, torch.ones_like(den)), torch.zeros_like(A @ V))
+    return a_rows * Os + (1 - a_rows) * Ol
+
+
+@pytest.mark.parametrize("N,d,bq,bk,frac,smooth,per_block", [
+    (150, 8, 32, 16, 0.3, True, False), (96, 16, 32, 16, 0.34, False, True), (70, 8, 32, 16, 0.0, True, True),
+    (64, 8, 32, 16, 1.0, True, False), (130, 4, 64, 64, 0.5, True, True),
+])
+def test_backward_matches_autograd_of_the_expanded_mask_definition(N, d, bq, bk, frac, smooth, per_block):
+    import torch
+    Q, K, V, Wq, Wk = rand_head(40 + N, N, d)
+    rng = np.random.default_rng(41)
+    T_m, T_n = O.num_blocks(N, bq), O.num_blocks(N, bk)
+    alpha = rng.uniform(0.1, 0.9, size=T_m) if per_block else 0.37
+    sel = O.topk_rows(O.router_scores(Q, O.smooth_k(K) if smooth else K, Wq, Wk, bq, bk), O.num_selected(frac, T_n))
+    dO = rng.normal(size=(N, d))
+    got = O.backward_head(Q, K, V, sel, alpha, dO, bq, bk, smooth=smooth)
+
+    M = np.kron(O.mask_from_sel(sel, T_n), np.ones((bq, bk), dtype=bool))[:N, :N]
+    a_blk = np.broadcast_to(np.asarray(alpha, dtype=np.float64).reshape(-1), (T_m,))
+    tq, tk, tv = (torch.tensor(x, dtype=torch.float64, requires_grad=True) for x in (Q, K, V))
+    ta = torch.tensor(a_blk.copy(), dtype=torch.float64, requires_grad=True)
+    a_rows = ta.repeat_interleave(bq)[:N, None]
+    out = _expanded_forward_torch(tq, tk, tv, torch.tensor(M), a_rows, smooth)
+    # the oracle's forward and the expanded form agree, so the same dO is the same cotangent
+    fwd = O.forward_head(Q, K, V, Wq, Wk, alpha, frac, bq, bk, smooth=smooth, sel=sel)["O"]
+    np.testing.assert_allclose(out.detach().numpy(), fwd, rtol=0, atol=1e-12)
+    out.backward(torch.tensor(dO))
+    np.testing.assert_allclose(got["dQ"], tq.grad.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(got["dK"], tk.grad.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(got["dV"], tv.grad.numpy(), rtol=0, atol=1e-11)
+    np.testing.assert_allclose(got["dalpha"], ta.grad.numpy(), rtol=0, atol=1e-11)
+
+
+def test_backward_central_differences():
+    N, d, bq, bk = 48, 4, 16, 16
+    Q, K, V, Wq, Wk = rand_head(45, N, d)
+    rng = np.random.default_rng(46)
+    sel = O.topk_rows(O.router_scores(Q, O.smooth_k(K), Wq, Wk, bq, bk), 1)
+    dO = rng.normal(size=(N, d))
+    g = O.backward_head(Q, K, V, sel, 0.6, dO, bq, bk)
+    f = lambda q, k, v: (O.forward_head(q, k, v, Wq, Wk, 0.6, 0.3, bq, bk, sel=sel)["O"] * dO).sum()
+    eps = 1e-6
+    for name, X, idx in (("dQ", Q, (5, 2)), ("dK", K, (17, 1)), ("dV", V, (40, 3)), ("dK", K, (47, 0))):
+        Xp, Xm = X.copy(), X.copy()
+        Xp[idx] += eps; Xm[idx] -= eps
+        args_p = [Xp if A is X else A for A in (Q, K, V)]
+        args_m = [Xm if A is X else A for A in (Q, K, V)]
+        fd = (f(*args_p) - f(*args_m)) / (2 * eps)
+        assert abs(fd - g[name][idx]) < 1e-7 * max(1.0, abs(fd)), (name, idx, fd, g[name][idx])
+
+
 # ---- SoftTop-k (Sec. 6.1) ---------------------------------------------------- #
 def test_soft_topk_row_sums_range_and_order():
     rng = np.random.default_rng(30)
