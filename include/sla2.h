@@ -70,6 +70,8 @@ typedef enum { SLA2_F32 = 0, SLA2_BF16 = 1 } sla2_dtype;   /* element type of q,
 typedef enum { SLA2_QUANT_NONE = 0, SLA2_QUANT_FP8 = 1, SLA2_QUANT_INT8 = 2, SLA2_QUANT_FP8_V = 3 } sla2_quant;
 
 #define SLA2_FLAG_NO_SMOOTH_K 1u   /* skip K <- K - colmean(K) (first step of Alg. 2) */
+#define SLA2_FLAG_SAVE_FOR_BACKWARD 2u   /* sla2_forward also keeps O^s, O^l and L in the workspace, and the
+                                            workspace is sized for sla2_backward */
 
 typedef struct sla2_params {
   int B, H, N, d;          /* batch, heads, tokens, head dim.  d in {64, 128}; N >= 1;
@@ -118,6 +120,11 @@ typedef struct sla2_ws_layout {
                        (g = 0, 1; b = 0..31).  SLA2_QUANT_FP8_V only; tokens >= N are 0 */
   size_t v_scale;   /* float  [BH, T_n]      dequantisation scale of each V block (SLA2_QUANT_FP8_V only) */
   size_t partial;   /* scratch for per-chunk partial sums of h and z */
+  /* with SLA2_FLAG_SAVE_FOR_BACKWARD only (0 bytes otherwise): */
+  size_t o_s;       /* dtype  [BH, N, d]     sparse-branch output O^s, before the mix of Eq. 13   (input of Alg. 3) */
+  size_t o_l;       /* dtype  [BH, N, d]     linear-branch output O^l */
+  size_t lse;       /* float  [BH, N]        L_i of Alg. 2 (log-sum-exp of the kept scores; -inf when k = 0) */
+  size_t bwd;       /* scratch of sla2_backward */
   size_t total;     /* = sla2_workspace_bytes() */
 } sla2_ws_layout;
 
@@ -166,6 +173,22 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
                  const float* router_w, const float* alpha, void* out,
                  int32_t* block_idx_or_null, float* lse_or_null,
                  void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/* Backward pass (Alg. 3 of the appendix, plus the steps it leaves to automatic differentiation: phi,
+ * the smoothing of K, the mix of Eq. 13): gradients of q, k, v and alpha for the block mask of the
+ * matching forward call (hard Top-k passes no gradient to the router, Sec. 6.1).  Taken in fp32
+ * arithmetic from the original q, k, v whatever quant_mode the forward ran in (Sec. 5).
+ *   params     the params of the forward call, SLA2_FLAG_SAVE_FOR_BACKWARD set
+ *   workspace  the workspace of that forward call, untouched since: it holds the block lists, the
+ *              per-token and per-head statistics of K, O^s, O^l and L
+ *   q, k, v, alpha   as in the forward call;  dout: gradient of out, layout of out (out_stride)
+ *   dq, dk, dv       written; element type and layout of q, k, v (in_stride); must not overlap
+ *                    each other or any input
+ *   dalpha           DEVICE float [H] or [H, T_m] (alpha_per_block), written
+ * Deterministic (no atomics).  Errors as sla2_forward; SLA2_EINVAL without the flag. */
+int sla2_backward(const sla2_params* params, const void* q, const void* k, const void* v, const float* alpha,
+                  const void* dout, void* dq, void* dk, void* dv, float* dalpha,
+                  void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Dense attention softmax(Q K^T / sqrt(d)) V with the same tile machinery: the
  * comparator the paper measures speed-ups against (Sec. 8.1: "C = 4 N^2 d").

@@ -454,12 +454,13 @@ def forward_head(Q, K, V, Wq, Wk, alpha, topk_frac: float, b_q: int, b_k: int,
 # backward pass (Alg. 3 of the appendix, plus the steps it leaves to automatic
 # differentiation: phi, the smoothing of K, the mix of Eq. 13)
 # --------------------------------------------------------------------------- #
-def backward_head(Q, K, V, sel, alpha, dO, b_q: int, b_k: int, smooth: bool = True):
+def backward_head(Q, K, V, sel, alpha, dO, b_q: int, b_k: int, smooth: bool = True, quant: int = QUANT_NONE):
     """Gradients of one head of the un-quantised operator with respect to Q, K,
     V and alpha, for a fixed block mask `sel` (hard Top-k passes no gradient to
     the router; Sec. 6.1).  dO: [N, d], the gradient of the output of Eq. 13.
     Sec. 5: the backward pass is always taken in high precision from the
-    original Q, K, V, whatever precision the forward ran in.
+    original Q, K, V, whatever precision the forward ran in; what it takes
+    from a low-bit forward (`quant`) is that forward's O^s and L, as inputs.
 
     Steps, in the notation of Alg. 3 (P is the normalised softmax over the
     selected positions, P = exp(S - L)):
@@ -482,7 +483,12 @@ def backward_head(Q, K, V, sel, alpha, dO, b_q: int, b_k: int, smooth: bool = Tr
     N, d = Q.shape
     T_m, T_n = num_blocks(N, b_q), num_blocks(N, b_k)
     Ks = smooth_k(K) if smooth else K
-    O_s, L = sparse_branch(Q, Ks, V, sel, b_q, b_k)
+    if quant == QUANT_NONE:
+        O_s, L = sparse_branch(Q, Ks, V, sel, b_q, b_k)
+    else:
+        O_s, L = sparse_branch_lowbit(Q, K, V, sel, b_q, b_k, smooth=smooth,
+                                      quant_block=quant_block_int8 if quant == QUANT_INT8 else None,
+                                      quant_v=quant == QUANT_FP8_V)
     O_l, H, Z = linear_branch(Q, Ks, V, sel, b_q, b_k)
     a_blk = np.broadcast_to(np.asarray(alpha, dtype=np.float64).reshape(-1), (T_m,)) if np.ndim(alpha) \
         else np.full((T_m,), float(alpha))

@@ -20,10 +20,11 @@ SLA2_QUANT_NONE, SLA2_QUANT_FP8, SLA2_QUANT_INT8, SLA2_QUANT_FP8_V = 0, 1, 2, 3
 QUANT_MODES = {"none": SLA2_QUANT_NONE, "fp8": SLA2_QUANT_FP8, "int8": SLA2_QUANT_INT8,
                "fp8v": SLA2_QUANT_FP8_V}   # workload name -> sla2_quant
 SLA2_FLAG_NO_SMOOTH_K = 1
+SLA2_FLAG_SAVE_FOR_BACKWARD = 2
 SLA2_OK, SLA2_EINVAL, SLA2_EUNSUPPORTED, SLA2_EWORKSPACE, SLA2_EALIAS, SLA2_EHIP = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("sla2_workspace_bytes", "sla2_workspace_layout", "sla2_num_selected", "sla2_router",
-           "sla2_router_soft", "sla2_forward", "sla2_dense_forward", "sla2_profile_begin", "sla2_profile_begin_sampled",
+           "sla2_router_soft", "sla2_forward", "sla2_backward", "sla2_dense_forward", "sla2_profile_begin", "sla2_profile_begin_sampled",
            "sla2_profile_end",
            "sla2_strerror", "sla2_version")
 
@@ -43,7 +44,8 @@ class WsLayout(ctypes.Structure):
     """struct sla2_ws_layout"""
     _fields_ = [(n, ctypes.c_size_t) for n in
                 ("q_sum", "k_sum", "k_mean", "router_m", "block_idx", "h_total", "z_total",
-                 "k_stats", "k_phi", "z_blocks", "k_fp8", "k_scale", "v_fp8", "v_scale", "partial", "total")]
+                 "k_stats", "k_phi", "z_blocks", "k_fp8", "k_scale", "v_fp8", "v_scale", "partial",
+                 "o_s", "o_l", "lse", "bwd", "total")]
 
 
 if not os.path.exists(LIB_PATH):
@@ -63,6 +65,8 @@ _lib.sla2_router_soft.restype = ctypes.c_int
 _lib.sla2_router_soft.argtypes = [_pp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.sla2_forward.restype = ctypes.c_int
 _lib.sla2_forward.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.sla2_backward.restype = ctypes.c_int
+_lib.sla2_backward.argtypes = [_pp] + [_vp] * 10 + [ctypes.c_size_t, _vp]
 _lib.sla2_dense_forward.restype = ctypes.c_int
 _lib.sla2_dense_forward.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp]
 _lib.sla2_profile_begin.restype = ctypes.c_int
@@ -161,6 +165,15 @@ def sla2_forward(params, q, k, v, router_w, alpha, out, block_idx=None, lse=None
         ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     rc = _lib.sla2_forward(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(router_w), _ptr(alpha),
                            _ptr(out), _ptr(block_idx), _ptr(lse), _ptr(workspace), ws_bytes, _stream(stream))
+    if check and rc != SLA2_OK:
+        raise Sla2Error(rc)
+    return rc
+
+
+def sla2_backward(params, q, k, v, alpha, dout, dq, dk, dv, dalpha, workspace, stream=None, check=True) -> int:
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    rc = _lib.sla2_backward(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(dout), _ptr(dq),
+                            _ptr(dk), _ptr(dv), _ptr(dalpha), _ptr(workspace), ws_bytes, _stream(stream))
     if check and rc != SLA2_OK:
         raise Sla2Error(rc)
     return rc

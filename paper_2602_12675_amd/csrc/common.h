@@ -46,6 +46,7 @@ struct Shape {
   int B, H, N, d, bq, bk;
   int BH, Tm, Tn, k;
   bool bf16, smooth, w_per_head, alpha_per_block;
+  bool save;                                 // keep O^s, O^l, L for the backward pass
   int quant;                                 // sla2_quant: 0 none, 1 FP8 e4m3, 2 INT8 codes of Q and K, 3 FP8 with V in e4m3 too
   // kv precompute: each workgroup reduces `blocks_per_chunk` key blocks; `chunks` per head
   int blocks_per_chunk, chunks;
@@ -65,6 +66,29 @@ __device__ __forceinline__ float load_elem(const uint16_t* p, size_t i) { return
 __device__ __forceinline__ void store_elem(float* p, size_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void store_elem(uint16_t* p, size_t i, float v) { p[i] = f32_to_bf16_bits(v); }
 
+// Where sla2_forward keeps O^s, O^l ([BH, N, d], element type of out) and L ([BH, N]) for the backward
+// pass; all null when nothing is to be kept.
+struct SavedForBackward {
+  void *o_s, *o_l;
+  float* lse;
+};
+
+// Everything the backward kernels touch (device pointers).
+struct BwdArgs {
+  const void *q, *k, *v, *dout, *o_s, *o_l;
+  const float* lse;
+  const double* k_mean;
+  const float *k_stats, *h_total, *z_total;
+  const int32_t* block_idx;
+  const float* alpha;
+  void *dq, *dk, *dv;
+  float* dalpha;
+  // scratch
+  float *ds, *dh, *dz, *dh_total, *dz_total, *colsum, *dk_mean, *dalpha_part;
+  int32_t *col_ptr, *col_idx;
+};
+hipError_t launch_backward(const Shape& s, const BwdArgs& a, hipStream_t stream);
+
 // ---- launchers (one per kernel file); all enqueue on `stream` and return hipGetLastError() ----
 hipError_t launch_block_sums(const Shape& s, const void* q, const void* k, const float* router_w, double* q_sum,
                              double* k_sum, double* router_m, hipStream_t stream);
@@ -76,7 +100,7 @@ hipError_t launch_kv_state_f32(const Shape& s, const float* k, const float* v, c
                                float* partial, hipStream_t stream);
 hipError_t launch_attn_f32(const Shape& s, const float* q, const float* k, const float* v, const double* k_mean,
                            const float* k_stats, const float* h_total, const float* z_total, const int32_t* block_idx,
-                           const float* alpha, float* out, float* lse, hipStream_t stream);
+                           const float* alpha, float* out, float* lse, const SavedForBackward& sv, hipStream_t stream);
 
 hipError_t launch_kv_total(const Shape& s, const float* partial, float* h_total, float* z_total, hipStream_t stream);
 hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_t* v, const double* k_mean,
@@ -87,7 +111,7 @@ hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k
                             const float* k_scale, const uint8_t* v_codes, const float* v_scale,
                             const float* h_total, const float* z_total,
                             const int32_t* block_idx, const float* alpha, uint16_t* out, float* lse,
-                            hipStream_t stream);
+                            const SavedForBackward& sv, hipStream_t stream);
 hipError_t launch_dense_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
                              hipStream_t stream);
 

@@ -23,7 +23,7 @@ static int make_shape(const sla2_params* p, Shape* s) {
     return SLA2_EINVAL;
   if (p->router_w_per_head != 0 && p->router_w_per_head != 1) return SLA2_EINVAL;
   if (p->alpha_per_block != 0 && p->alpha_per_block != 1) return SLA2_EINVAL;
-  if (p->flags & ~SLA2_FLAG_NO_SMOOTH_K) return SLA2_EINVAL;
+  if (p->flags & ~(SLA2_FLAG_NO_SMOOTH_K | SLA2_FLAG_SAVE_FOR_BACKWARD)) return SLA2_EINVAL;
   if (p->d != 64 && p->d != 128) return SLA2_EUNSUPPORTED;
   if (!((p->block_q == 64 || p->block_q == 128) && p->block_kv == 64)) return SLA2_EUNSUPPORTED;
   if (p->quant_mode != SLA2_QUANT_NONE && p->dtype != SLA2_BF16) return SLA2_EUNSUPPORTED;
@@ -53,6 +53,7 @@ static int make_shape(const sla2_params* p, Shape* s) {
   }
   s->quant = (int)p->quant_mode;
   s->smooth = !(p->flags & SLA2_FLAG_NO_SMOOTH_K);
+  s->save = (p->flags & SLA2_FLAG_SAVE_FOR_BACKWARD) != 0;
   s->w_per_head = p->router_w_per_head != 0;
   s->alpha_per_block = p->alpha_per_block != 0;
   // Key blocks per kv-precompute workgroup.  That kernel keeps 2 workgroups resident per CU (its
@@ -68,6 +69,30 @@ static int make_shape(const sla2_params* p, Shape* s) {
   s->chunks = (s->Tn + bpc - 1) / bpc;
   return SLA2_OK;
 }
+
+// scratch of the backward pass, carved out of the `bwd` region of the workspace
+struct BwdLayout {
+  size_t ds, dh, dz, dh_total, dz_total, colsum, dk_mean, dalpha_part, col_ptr, col_idx, total;
+};
+static BwdLayout make_bwd_layout(const Shape& s) {
+  BwdLayout B;
+  size_t off = 0, BH = (size_t)s.BH, d = (size_t)s.d;
+  auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+  const size_t slots = BH * s.Tm * (size_t)(s.bq / 64);          // one per 64 query rows
+  B.ds = take(BH * (size_t)s.N * sizeof(float));
+  B.dh = take(slots * d * d * sizeof(float));
+  B.dz = take(slots * d * sizeof(float));
+  B.dh_total = take(BH * d * d * sizeof(float));
+  B.dz_total = take(BH * d * sizeof(float));
+  B.colsum = take(BH * (size_t)s.Tn * d * sizeof(float));
+  B.dk_mean = take(BH * d * sizeof(float));
+  B.dalpha_part = take(slots * sizeof(float));
+  B.col_ptr = take(BH * (size_t)(s.Tn + 1) * sizeof(int32_t));
+  B.col_idx = take(BH * s.Tm * (size_t)(s.k > 0 ? s.k : 1) * sizeof(int32_t));
+  B.total = off;
+  return B;
+}
+static size_t bwd_scratch_bytes(const Shape& s) { return make_bwd_layout(s).total; }
 
 static void make_layout(const Shape& s, sla2_ws_layout* L) {
   size_t off = 0, BH = (size_t)s.BH, d = (size_t)s.d;
@@ -87,6 +112,11 @@ static void make_layout(const Shape& s, sla2_ws_layout* L) {
   L->v_fp8 = take(s.quant == 3 ? BH * (size_t)s.Tn * s.bk * d : 0);
   L->v_scale = take(s.quant == 3 ? BH * (size_t)s.Tn * sizeof(float) : 0);
   L->partial = take(BH * (size_t)s.chunks * (d * d + d) * sizeof(float));
+  const size_t esz = s.bf16 ? 2 : 4;
+  L->o_s = take(s.save ? BH * (size_t)s.N * d * esz : 0);
+  L->o_l = take(s.save ? BH * (size_t)s.N * d * esz : 0);
+  L->lse = take(s.save ? BH * (size_t)s.N * sizeof(float) : 0);
+  L->bwd = take(s.save ? bwd_scratch_bytes(s) : 0);
   L->total = off;
 }
 
@@ -250,6 +280,8 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
     if (hipMemcpyAsync(block_idx_or_null, idx, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return SLA2_EHIP;
   }
   const double* k_mean = at<double>(workspace, L.k_mean);
+  SavedForBackward sv{nullptr, nullptr, nullptr};
+  if (s.save) sv = SavedForBackward{at<void>(workspace, L.o_s), at<void>(workspace, L.o_l), at<float>(workspace, L.lse)};
   float* k_stats = at<float>(workspace, L.k_stats);
   float* h_total = at<float>(workspace, L.h_total);
   float* z_total = at<float>(workspace, L.z_total);
@@ -262,7 +294,7 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
       return SLA2_EHIP;
     if (SLA2_STAGE(SLA2_STAGE_ATTN,
                    launch_attn_f32(s, (const float*)q, (const float*)k, (const float*)v, k_mean, k_stats, h_total,
-                                   z_total, idx, alpha, (float*)out, lse_or_null, st)) != hipSuccess)
+                                   z_total, idx, alpha, (float*)out, lse_or_null, sv, st)) != hipSuccess)
       return SLA2_EHIP;
     return SLA2_OK;
   }
@@ -281,8 +313,49 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
   if (SLA2_STAGE(SLA2_STAGE_ATTN,
                  launch_attn_bf16(s, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v, k_mean, k_phi,
                                   z_blocks, k_fp8, k_scale, v_fp8, v_scale, h_total, z_total, idx, alpha, (uint16_t*)out,
-                                  lse_or_null, st)) != hipSuccess)
+                                  lse_or_null, sv, st)) != hipSuccess)
     return SLA2_EHIP;
+  return SLA2_OK;
+}
+
+int sla2_backward(const sla2_params* params, const void* q, const void* k, const void* v, const float* alpha,
+                  const void* dout, void* dq, void* dk, void* dv, float* dalpha, void* workspace,
+                  size_t workspace_bytes, void* hip_stream) {
+  Shape s; sla2_ws_layout L;
+  int rc = make_shape(params, &s);
+  if (rc != SLA2_OK) return rc;
+  if (!s.save) return SLA2_EINVAL;                     // the forward call did not keep what Alg. 3 needs
+  if (!q || !k || !v || !alpha || !dout || !dq || !dk || !dv || !dalpha) return SLA2_EINVAL;
+  if (misaligned16(q) || misaligned16(k) || misaligned16(v) || misaligned16(dout) || misaligned16(dq) ||
+      misaligned16(dk) || misaligned16(dv))
+    return SLA2_EINVAL;
+  const size_t in_bytes = span_bytes(s, s.sin);
+  const void* ins[4] = {q, k, v, dout};
+  void* outs[3] = {dq, dk, dv};
+  for (void* o : outs)
+    for (int x = 0; x < 4; x++)
+      if (overlaps(o, in_bytes, ins[x], x == 3 ? span_bytes(s, s.sout) : in_bytes)) return SLA2_EALIAS;
+  if (overlaps(dq, in_bytes, dk, in_bytes) || overlaps(dq, in_bytes, dv, in_bytes) || overlaps(dk, in_bytes, dv, in_bytes))
+    return SLA2_EALIAS;
+  make_layout(s, &L);
+  if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
+  const BwdLayout B = make_bwd_layout(s);
+  char* bw = at<char>(workspace, L.bwd);
+  BwdArgs a;
+  a.q = q; a.k = k; a.v = v; a.dout = dout;
+  a.o_s = at<void>(workspace, L.o_s); a.o_l = at<void>(workspace, L.o_l); a.lse = at<float>(workspace, L.lse);
+  a.k_mean = at<double>(workspace, L.k_mean);
+  a.k_stats = at<float>(workspace, L.k_stats);
+  a.h_total = at<float>(workspace, L.h_total); a.z_total = at<float>(workspace, L.z_total);
+  a.block_idx = at<int32_t>(workspace, L.block_idx);
+  a.alpha = alpha;
+  a.dq = dq; a.dk = dk; a.dv = dv; a.dalpha = dalpha;
+  a.ds = (float*)(bw + B.ds); a.dh = (float*)(bw + B.dh); a.dz = (float*)(bw + B.dz);
+  a.dh_total = (float*)(bw + B.dh_total); a.dz_total = (float*)(bw + B.dz_total);
+  a.colsum = (float*)(bw + B.colsum); a.dk_mean = (float*)(bw + B.dk_mean);
+  a.dalpha_part = (float*)(bw + B.dalpha_part);
+  a.col_ptr = (int32_t*)(bw + B.col_ptr); a.col_idx = (int32_t*)(bw + B.col_idx);
+  if (launch_backward(s, a, (hipStream_t)hip_stream) != hipSuccess) return SLA2_EHIP;
   return SLA2_OK;
 }
 

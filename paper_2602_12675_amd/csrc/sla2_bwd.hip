@@ -1,0 +1,704 @@
+// Backward pass of SLA2 (Alg. 3 of the paper's appendix, with the steps it leaves to automatic
+// differentiation written out: phi = softmax over d, the smoothing of K, the mix of Eq. 13).
+// High precision throughout, from the original Q, K, V (Sec. 5: the backward pass is never quantised):
+// fp32 arithmetic on fp32 or bf16 tensors.  These are plain LDS-tiled FMA kernels - the readable,
+// deterministic statement of the data flow (no atomics, fixed summation orders); they are not tuned.
+//
+//   bwd_transpose  for every key block j, the ascending list of query blocks i with M_c[i, j] = 1
+//   bwd_q          per 64 query rows of block i:  D^s, D^l, d alpha;  over the selected blocks:
+//                  P = exp(S - L), dP = dO^s V^T, dS = P (.) (dP - D^s), dQ += dS K' / sqrt d, and the
+//                  state of the selected blocks (as in the forward pass) -> H_i, Z_i;  then
+//                  dH_i = (Q^phi / (Q^phi Z_i))^T dO^l, dZ_i, dQ^phi, dQ += softmax-backward(dQ^phi)
+//   bwd_sum        dH_total = sum_i dH_i, dZ_total = sum_i dZ_i
+//   bwd_kv         per key block j:  over the query blocks that selected it: dV += P^T dO^s,
+//                  dK' += dS^T Q / sqrt d;  dH = dH_total - sum over those same query blocks of dH_i
+//                  (the M_c[i, j] = 0 sum of Alg. 3, by complement), dZ likewise;
+//                  dK^phi = V dH^T + 1 dZ^T, dV += K^phi dH, dK' += softmax-backward(dK^phi)
+//   bwd_finish     dK = dK' - colmean(dK') (gradient of the smoothing), d alpha summed over its parts
+#include "common.h"
+
+namespace sla2 {
+
+constexpr int kBwdRows = 64;      // query rows per workgroup / per step
+constexpr int kBwdBK = 64;        // key/value block (b_kv)
+
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void bwd_transpose_kernel(const int32_t* __restrict__ block_idx,
+                                                            int32_t* __restrict__ col_ptr,
+                                                            int32_t* __restrict__ col_idx, int Tm, int Tn, int ksel) {
+  __shared__ int cnt[kMaxKeyBlocks + 1];
+  const int bh = blockIdx.x, tid = threadIdx.x;
+  const int32_t* sel = block_idx + (size_t)bh * Tm * ksel;
+  auto selected = [&](int i, int j) {                 // is j in the ascending list of row i
+    const int32_t* row = sel + (size_t)i * ksel;
+    int lo = 0, hi = ksel;
+    while (lo < hi) {
+      const int mid = (lo + hi) >> 1;
+      if (row[mid] < j) lo = mid + 1;
+      else hi = mid;
+    }
+    return lo < ksel && row[lo] == j;
+  };
+  for (int j = tid; j < Tn; j += 256) {
+    int c = 0;
+    for (int i = 0; i < Tm; i++) c += selected(i, j) ? 1 : 0;
+    cnt[j] = c;
+  }
+  __syncthreads();
+  if (tid == 0) {                                     // exclusive scan, in place
+    int run = 0;
+    for (int j = 0; j < Tn; j++) {
+      const int c = cnt[j];
+      cnt[j] = run;
+      run += c;
+    }
+    cnt[Tn] = run;
+  }
+  __syncthreads();
+  for (int j = tid; j <= Tn; j += 256) col_ptr[(size_t)bh * (Tn + 1) + j] = cnt[j];
+  for (int j = tid; j < Tn; j += 256) {
+    int pos = cnt[j];
+    for (int i = 0; i < Tm; i++)
+      if (selected(i, j)) col_idx[(size_t)bh * Tm * ksel + pos++] = i;
+  }
+}
+
+// sum over the 16 lanes that share a row (threads tx = 0..15 of one ty)
+__device__ __forceinline__ float row_sum16(float v) {
+#pragma unroll
+  for (int o = 1; o < 16; o <<= 1) v += __shfl_xor(v, o);
+  return v;
+}
+
+// ---------------------------------------------------------------------------------------------
+// bwd_q: one workgroup per 64 query rows.  Thread (tx, ty): rows 4 ty + a, key tokens / channels
+// tx + 16 b; for d x d quantities, entries (MT ty + a, tx + 16 b).
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_q_kernel(
+    const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, const T* __restrict__ dout,
+    const T* __restrict__ o_s, const T* __restrict__ o_l, const float* __restrict__ lse,
+    const double* __restrict__ k_mean, const float* __restrict__ k_stats, const float* __restrict__ h_total,
+    const float* __restrict__ z_total, const int32_t* __restrict__ block_idx, const float* __restrict__ alpha,
+    T* __restrict__ dq, float* __restrict__ ds_out, float* __restrict__ dh_out, float* __restrict__ dz_out,
+    float* __restrict__ dalpha_part, Strides sin, Strides sout, int H, int N, int bq, int Tm, int Tn, int ksel,
+    int alpha_per_block) {
+  constexpr int LD = D + 1;
+  constexpr int LP = kBwdBK + 1;
+  constexpr int MT = D / 16;
+  constexpr int OC = D / 16;
+  extern __shared__ float smem[];
+  float* qs = smem;                         // [64][LD]  Q rows, later Q^phi
+  float* dos = qs + kBwdRows * LD;          // [64][LD]  dO^s rows, later dO^l rows
+  float* ks = dos + kBwdRows * LD;          // [64][LD]  K' tile, then K^phi tile
+  float* vs = ks + kBwdBK * LD;             // [64][LD]  V tile
+  float* ps = vs + kBwdBK * LD;             // [64][LP]  dS tile
+  float* zs = ps + kBwdRows * LP;           // [D]       Z_i
+  float* rowv = zs + D;                     // [64]      1 / (Q^phi Z_i) per row
+  float* rowd = rowv + kBwdRows;            // [64]      D^l per row
+  float* red = rowd + kBwdRows;             // [256]
+  float* hst = ks;                          // [D][D]    H_i^T in the epilogue (covers ks and vs)
+
+  const int parts = bq / kBwdRows;
+  int bid = blockIdx.x;
+  const int part = bid % parts; bid /= parts;
+  const int i = bid % Tm;
+  const int bh = bid / Tm;
+  const int h = bh % H;
+  const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+  const int row0 = i * bq + part * kBwdRows;
+  const int rows_valid = max(0, min(kBwdRows, min(N, (i + 1) * bq) - row0));
+  const size_t slot = ((size_t)bh * Tm + i) * parts + part;          // where this workgroup's dH_i, dZ_i, d alpha go
+  float* dh_slot = dh_out + slot * D * D;
+  float* dz_slot = dz_out + slot * D;
+  if (rows_valid == 0) {                                              // second half of a short last query block
+    for (int e = tid; e < D * D; e += 256) dh_slot[e] = 0.f;
+    if (tid < D) dz_slot[tid] = 0.f;
+    if (tid == 0) dalpha_part[slot] = 0.f;
+    return;
+  }
+  const T* qh = q + head_offset(sin, bh, H);
+  const T* kh = k + head_offset(sin, bh, H);
+  const T* vh = v + head_offset(sin, bh, H);
+  const T* doh = dout + head_offset(sout, bh, H);
+  T* dqh = dq + head_offset(sin, bh, H);
+  const int32_t* sel = block_idx + ((size_t)bh * Tm + i) * ksel;
+  const float rscale = rsqrtf((float)D);
+  const float al = alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
+
+  // ---- prologue: Q, dO^s = alpha dO; D^s, D^l, d alpha ----
+  float Ds[4], Dl[4], Lr[4];
+  float mix_part = 0.f;
+#pragma unroll
+  for (int a = 0; a < 4; a++) {
+    const int r = 4 * ty + a;
+    const bool ok = r < rows_valid;
+    float sds = 0.f, sdl = 0.f;
+#pragma unroll
+    for (int b = 0; b < OC; b++) {
+      const int c = tx + 16 * b;
+      float qv = 0.f, go = 0.f, osv = 0.f, olv = 0.f;
+      if (ok) {
+        qv = load_elem(qh, (size_t)(row0 + r) * sin.n + c);
+        go = load_elem(doh, (size_t)(row0 + r) * sout.n + c);
+        osv = load_elem(o_s, ((size_t)bh * N + row0 + r) * D + c);
+        olv = load_elem(o_l, ((size_t)bh * N + row0 + r) * D + c);
+      }
+      qs[r * LD + c] = qv;
+      dos[r * LD + c] = al * go;
+      sds += al * go * osv;
+      sdl += (1.f - al) * go * olv;
+      mix_part += go * (osv - olv);
+    }
+    Ds[a] = row_sum16(sds);
+    Dl[a] = row_sum16(sdl);
+    Lr[a] = ok ? lse[(size_t)bh * N + row0 + r] : 0.f;
+    if (ok && tx == 0) ds_out[(size_t)bh * N + row0 + r] = Ds[a];
+    if (tx == 0) rowd[r] = Dl[a];
+  }
+  red[tid] = mix_part;
+  __syncthreads();
+  if (tid == 0) {
+    float t = 0.f;
+    for (int x = 0; x < 256; x++) t += red[x];
+    dalpha_part[slot] = t;
+  }
+
+  float dqacc[4][OC], hacc[MT][MT];
+#pragma unroll
+  for (int a = 0; a < 4; a++)
+#pragma unroll
+    for (int b = 0; b < OC; b++) dqacc[a][b] = 0.f;
+#pragma unroll
+  for (int a = 0; a < MT; a++)
+#pragma unroll
+    for (int b = 0; b < MT; b++) hacc[a][b] = 0.f;
+  float zacc = 0.f;
+
+  for (int s = 0; s < ksel; s++) {
+    const int j = sel[s];
+    const int t0 = j * kBwdBK, valid = min(kBwdBK, N - t0);
+    __syncthreads();                                  // previous tile fully consumed
+    for (int idx = tid; idx < kBwdBK * D; idx += 256) {
+      const int t = idx / D, c = idx % D;
+      const bool ok = t < valid;
+      ks[t * LD + c] = ok ? load_elem(kh, (size_t)(t0 + t) * sin.n + c) - (float)k_mean[(size_t)bh * D + c] : 0.f;
+      vs[t * LD + c] = ok ? load_elem(vh, (size_t)(t0 + t) * sin.n + c) : 0.f;
+    }
+    __syncthreads();
+    // S = Q K'^T / sqrt d and dP = dO^s V^T on rows 4 ty + a, key tokens tx + 16 b
+    float sacc[4][4], pacc[4][4];
+#pragma unroll
+    for (int a = 0; a < 4; a++)
+#pragma unroll
+      for (int b = 0; b < 4; b++) { sacc[a][b] = 0.f; pacc[a][b] = 0.f; }
+    for (int c = 0; c < D; c++) {
+      float qv[4], gv[4], kv[4], vv[4];
+#pragma unroll
+      for (int a = 0; a < 4; a++) { qv[a] = qs[(4 * ty + a) * LD + c]; gv[a] = dos[(4 * ty + a) * LD + c]; }
+#pragma unroll
+      for (int b = 0; b < 4; b++) { kv[b] = ks[(tx + 16 * b) * LD + c]; vv[b] = vs[(tx + 16 * b) * LD + c]; }
+#pragma unroll
+      for (int a = 0; a < 4; a++)
+#pragma unroll
+        for (int b = 0; b < 4; b++) { sacc[a][b] += qv[a] * kv[b]; pacc[a][b] += gv[a] * vv[b]; }
+    }
+#pragma unroll
+    for (int a = 0; a < 4; a++)
+#pragma unroll
+      for (int b = 0; b < 4; b++) {
+        const bool ok = (tx + 16 * b) < valid && (4 * ty + a) < rows_valid;
+        const float p = ok ? __expf(sacc[a][b] * rscale - Lr[a]) : 0.f;
+        ps[(4 * ty + a) * LP + tx + 16 * b] = p * (pacc[a][b] - Ds[a]);     // dS
+      }
+    __syncthreads();
+    // dQ += dS K' / sqrt d
+    for (int t = 0; t < kBwdBK; t++) {
+      float sv[4], kv[OC];
+#pragma unroll
+      for (int a = 0; a < 4; a++) sv[a] = ps[(4 * ty + a) * LP + t];
+#pragma unroll
+      for (int b = 0; b < OC; b++) kv[b] = ks[t * LD + tx + 16 * b];
+#pragma unroll
+      for (int a = 0; a < 4; a++)
+#pragma unroll
+        for (int b = 0; b < OC; b++) dqacc[a][b] += sv[a] * kv[b];
+    }
+    __syncthreads();                                  // ks no longer read as K'
+    for (int idx = tid; idx < kBwdBK * D; idx += 256) {
+      const int t = idx / D, c = idx % D;
+      float kp = 0.f;
+      if (t < valid) kp = __expf(ks[t * LD + c] - k_stats[(size_t)bh * N + t0 + t]);
+      ks[t * LD + c] = kp;
+    }
+    __syncthreads();
+    for (int t = 0; t < kBwdBK; t++) {                // state of this selected block, as in the forward pass
+      float kv[MT], vv[MT];
+#pragma unroll
+      for (int a = 0; a < MT; a++) kv[a] = ks[t * LD + MT * ty + a];
+#pragma unroll
+      for (int b = 0; b < MT; b++) vv[b] = vs[t * LD + tx + 16 * b];
+#pragma unroll
+      for (int a = 0; a < MT; a++)
+#pragma unroll
+        for (int b = 0; b < MT; b++) hacc[a][b] += kv[a] * vv[b];
+    }
+    if (tid < D)
+      for (int t = 0; t < kBwdBK; t++) zacc += ks[t * LD + tid];
+  }
+  __syncthreads();
+
+  // ---- linear branch ----
+  const bool all_selected = ksel >= Tn;               // no linear branch: it receives and passes no gradient
+  const float* ht = h_total + (size_t)bh * D * D;
+#pragma unroll
+  for (int a = 0; a < MT; a++)
+#pragma unroll
+    for (int b = 0; b < MT; b++) {
+      const int c = MT * ty + a, e = tx + 16 * b;
+      hst[e * D + c] = ht[c * D + e] - hacc[a][b];    // H_i^T: the product below runs over e
+    }
+  if (tid < D) zs[tid] = z_total[(size_t)bh * D + tid] - zacc;
+  {  // Q^phi = softmax_d(Q) in place, 4 threads per row
+    const int r = tid / 4, sub = tid % 4;
+    float m = -INFINITY;
+    for (int c = sub; c < D; c += 4) m = fmaxf(m, qs[r * LD + c]);
+    m = fmaxf(m, __shfl_xor(m, 1));
+    m = fmaxf(m, __shfl_xor(m, 2));
+    float sum = 0.f;
+    for (int c = sub; c < D; c += 4) {
+      const float e = __expf(qs[r * LD + c] - m);
+      qs[r * LD + c] = e;
+      sum += e;
+    }
+    sum += __shfl_xor(sum, 1);
+    sum += __shfl_xor(sum, 2);
+    const float inv = 1.f / sum;
+    for (int c = sub; c < D; c += 4) qs[r * LD + c] *= inv;
+  }
+  // dO^l = (1 - alpha) dO into the rows that held dO^s
+  for (int idx = tid; idx < kBwdRows * D; idx += 256) {
+    const int r = idx / D, c = idx % D;
+    dos[r * LD + c] = r < rows_valid ? (1.f - al) * load_elem(doh, (size_t)(row0 + r) * sout.n + c) : 0.f;
+  }
+  __syncthreads();
+  if (tid < kBwdRows) {                               // 1 / (Q^phi_r . Z_i)
+    float den = 0.f;
+    for (int c = 0; c < D; c++) den += qs[tid * LD + c] * zs[c];
+    rowv[tid] = (all_selected || tid >= rows_valid) ? 0.f : 1.f / den;
+  }
+  __syncthreads();
+  // dH_i[c][e] = sum_r (Q^phi[r][c] / den_r) dO^l[r][e];  dZ_i[c] = -sum_r (Q^phi[r][c] / den_r) D^l_r
+  {
+    float dh[MT][MT];
+#pragma unroll
+    for (int a = 0; a < MT; a++)
+#pragma unroll
+      for (int b = 0; b < MT; b++) dh[a][b] = 0.f;
+    for (int r = 0; r < kBwdRows; r++) {
+      const float w = rowv[r];
+      float qv[MT], gv[MT];
+#pragma unroll
+      for (int a = 0; a < MT; a++) qv[a] = qs[r * LD + MT * ty + a] * w;
+#pragma unroll
+      for (int b = 0; b < MT; b++) gv[b] = dos[r * LD + tx + 16 * b];
+#pragma unroll
+      for (int a = 0; a < MT; a++)
+#pragma unroll
+        for (int b = 0; b < MT; b++) dh[a][b] += qv[a] * gv[b];
+    }
+#pragma unroll
+    for (int a = 0; a < MT; a++)
+#pragma unroll
+      for (int b = 0; b < MT; b++) dh_slot[(MT * ty + a) * D + tx + 16 * b] = dh[a][b];
+    if (tid < D) {
+      float dzv = 0.f;
+      for (int r = 0; r < kBwdRows; r++) dzv -= qs[r * LD + tid] * rowv[r] * rowd[r];
+      dz_slot[tid] = dzv;
+    }
+  }
+  // dQ^phi[r][c] = (sum_e dO^l[r][e] H_i[c][e] - D^l_r Z_i[c]) / den_r, then back through the softmax
+  float dqp[4][OC];
+#pragma unroll
+  for (int a = 0; a < 4; a++)
+#pragma unroll
+    for (int b = 0; b < OC; b++) dqp[a][b] = 0.f;
+  for (int e = 0; e < D; e++) {
+    float gv[4], hv[OC];
+#pragma unroll
+    for (int a = 0; a < 4; a++) gv[a] = dos[(4 * ty + a) * LD + e];
+#pragma unroll
+    for (int b = 0; b < OC; b++) hv[b] = hst[e * D + tx + 16 * b];
+#pragma unroll
+    for (int a = 0; a < 4; a++)
+#pragma unroll
+      for (int b = 0; b < OC; b++) dqp[a][b] += gv[a] * hv[b];
+  }
+#pragma unroll
+  for (int a = 0; a < 4; a++) {
+    const int r = 4 * ty + a;
+    const float w = rowv[r];
+    float dot = 0.f;
+#pragma unroll
+    for (int b = 0; b < OC; b++) {
+      const int c = tx + 16 * b;
+      dqp[a][b] = (dqp[a][b] - Dl[a] * zs[c]) * w;
+      dot += dqp[a][b] * qs[r * LD + c];
+    }
+    dot = row_sum16(dot);
+    if (r < rows_valid) {
+#pragma unroll
+      for (int b = 0; b < OC; b++) {
+        const int c = tx + 16 * b;
+        const float g = dqacc[a][b] * rscale + qs[r * LD + c] * (dqp[a][b] - dot);
+        store_elem(dqh, (size_t)(row0 + r) * sin.n + c, g);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// dst[bh][e] = sum over b < count of src[bh][b][e]   (ascending b)
+__global__ __launch_bounds__(256) void bwd_sum_kernel(const float* __restrict__ src, float* __restrict__ dst, int count,
+                                                      int len) {
+  const int bh = blockIdx.y;
+  const int e = blockIdx.x * 256 + threadIdx.x;
+  if (e >= len) return;
+  const float* p = src + (size_t)bh * count * len + e;
+  float s = 0.f;
+  for (int b = 0; b < count; b++) s += p[(size_t)b * len];
+  dst[(size_t)bh * len + e] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// bwd_kv: one workgroup per key block j.  Thread (tx, ty): key tokens 4 ty + a, channels tx + 16 b;
+// for the products over the 64 query rows of a step, rows tx + 16 b.
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D>
+__global__ __launch_bounds__(256) void bwd_kv_kernel(
+    const T* __restrict__ q, const T* __restrict__ k, const T* __restrict__ v, const T* __restrict__ dout,
+    const float* __restrict__ lse, const float* __restrict__ ds_in, const double* __restrict__ k_mean,
+    const float* __restrict__ k_stats, const int32_t* __restrict__ col_ptr, const int32_t* __restrict__ col_idx,
+    const float* __restrict__ dh_in, const float* __restrict__ dz_in, const float* __restrict__ dh_total,
+    const float* __restrict__ dz_total, const float* __restrict__ alpha, T* __restrict__ dk, T* __restrict__ dv,
+    float* __restrict__ colsum, Strides sin, Strides sout, int H, int N, int bq, int Tm, int Tn, int ksel,
+    int alpha_per_block) {
+  constexpr int LD = D + 1;
+  constexpr int LP = kBwdBK + 1;
+  constexpr int MT = D / 16;
+  constexpr int OC = D / 16;
+  extern __shared__ float smem[];
+  float* ks = smem;                         // [64][LD]  K' tile, then K^phi tile
+  float* vs = ks + kBwdBK * LD;             // [64][LD]  V tile
+  float* qs = vs + kBwdBK * LD;             // [64][LD]  Q rows of the step
+  float* dos = qs + kBwdRows * LD;          // [64][LD]  dO^s rows of the step
+  float* ps = dos + kBwdRows * LD;          // [64 rows][LP]  P, then dS
+  float* rowl = ps + kBwdRows * LP;         // [64]  L per row
+  float* rowd = rowl + kBwdRows;            // [64]  D^s per row
+  float* dzs = rowd + kBwdRows;             // [D]   dZ of this key block
+  float* red = dzs + D;                     // [16][D] column sums
+  float* dhs = qs;                          // [D][D]  dH, then dH^T, after the loop (covers qs and dos)
+
+  const int j = blockIdx.x % Tn, bh = blockIdx.x / Tn, h = bh % H;
+  const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+  const int t0 = j * kBwdBK, valid = min(kBwdBK, N - t0);
+  const int parts = bq / kBwdRows;
+  const T* qh = q + head_offset(sin, bh, H);
+  const T* kh = k + head_offset(sin, bh, H);
+  const T* vh = v + head_offset(sin, bh, H);
+  const T* doh = dout + head_offset(sout, bh, H);
+  const float rscale = rsqrtf((float)D);
+
+  for (int idx = tid; idx < kBwdBK * D; idx += 256) {
+    const int t = idx / D, c = idx % D;
+    const bool ok = t < valid;
+    ks[t * LD + c] = ok ? load_elem(kh, (size_t)(t0 + t) * sin.n + c) - (float)k_mean[(size_t)bh * D + c] : 0.f;
+    vs[t * LD + c] = ok ? load_elem(vh, (size_t)(t0 + t) * sin.n + c) : 0.f;
+  }
+  float dvacc[4][OC], dkacc[4][OC];
+#pragma unroll
+  for (int a = 0; a < 4; a++)
+#pragma unroll
+    for (int b = 0; b < OC; b++) { dvacc[a][b] = 0.f; dkacc[a][b] = 0.f; }
+
+  const int32_t* cp = col_ptr + (size_t)bh * (Tn + 1);
+  const int32_t* ci = col_idx + (size_t)bh * Tm * ksel;
+  const int l0 = cp[j], l1 = cp[j + 1];
+  for (int l = l0; l < l1; l++) {
+    const int i = ci[l];
+    const float al = alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
+    for (int part = 0; part < parts; part++) {
+      const int row0 = i * bq + part * kBwdRows;
+      const int rows_valid = max(0, min(kBwdRows, min(N, (i + 1) * bq) - row0));
+      if (rows_valid == 0) continue;                  // uniform: the whole workgroup skips
+      __syncthreads();                                // previous step fully consumed (and ks, vs written)
+      for (int idx = tid; idx < kBwdRows * D; idx += 256) {
+        const int r = idx / D, c = idx % D;
+        const bool ok = r < rows_valid;
+        qs[r * LD + c] = ok ? load_elem(qh, (size_t)(row0 + r) * sin.n + c) : 0.f;
+        dos[r * LD + c] = ok ? al * load_elem(doh, (size_t)(row0 + r) * sout.n + c) : 0.f;
+      }
+      if (tid < kBwdRows) {
+        const bool ok = tid < rows_valid;
+        rowl[tid] = ok ? lse[(size_t)bh * N + row0 + tid] : 0.f;
+        rowd[tid] = ok ? ds_in[(size_t)bh * N + row0 + tid] : 0.f;
+      }
+      __syncthreads();
+      // S^T and dP^T on key tokens 4 ty + a, query rows tx + 16 b
+      float sacc[4][4], pacc[4][4];
+#pragma unroll
+      for (int a = 0; a < 4; a++)
+#pragma unroll
+        for (int b = 0; b < 4; b++) { sacc[a][b] = 0.f; pacc[a][b] = 0.f; }
+      for (int c = 0; c < D; c++) {
+        float kv[4], vv[4], qv[4], gv[4];
+#pragma unroll
+        for (int a = 0; a < 4; a++) { kv[a] = ks[(4 * ty + a) * LD + c]; vv[a] = vs[(4 * ty + a) * LD + c]; }
+#pragma unroll
+        for (int b = 0; b < 4; b++) { qv[b] = qs[(tx + 16 * b) * LD + c]; gv[b] = dos[(tx + 16 * b) * LD + c]; }
+#pragma unroll
+        for (int a = 0; a < 4; a++)
+#pragma unroll
+          for (int b = 0; b < 4; b++) { sacc[a][b] += kv[a] * qv[b]; pacc[a][b] += vv[a] * gv[b]; }
+      }
+      float pv[4][4];
+#pragma unroll
+      for (int a = 0; a < 4; a++)
+#pragma unroll
+        for (int b = 0; b < 4; b++) {
+          const int r = tx + 16 * b;
+          const bool ok = (4 * ty + a) < valid && r < rows_valid;
+          pv[a][b] = ok ? __expf(sacc[a][b] * rscale - rowl[r]) : 0.f;
+          ps[r * LP + 4 * ty + a] = pv[a][b];         // P[row][token]
+        }
+      __syncthreads();
+      // dV[token][c] += sum_rows P[row][token] dO^s[row][c]
+      for (int r = 0; r < kBwdRows; r++) {
+        float pr[4], gv[OC];
+#pragma unroll
+        for (int a = 0; a < 4; a++) pr[a] = ps[r * LP + 4 * ty + a];
+#pragma unroll
+        for (int b = 0; b < OC; b++) gv[b] = dos[r * LD + tx + 16 * b];
+#pragma unroll
+        for (int a = 0; a < 4; a++)
+#pragma unroll
+          for (int b = 0; b < OC; b++) dvacc[a][b] += pr[a] * gv[b];
+      }
+      __syncthreads();                                // P fully consumed
+#pragma unroll
+      for (int a = 0; a < 4; a++)
+#pragma unroll
+        for (int b = 0; b < 4; b++) {
+          const int r = tx + 16 * b;
+          ps[r * LP + 4 * ty + a] = pv[a][b] * (pacc[a][b] - rowd[r]);     // dS[row][token]
+        }
+      __syncthreads();
+      // dK'[token][c] += sum_rows dS[row][token] Q[row][c]   (the 1 / sqrt d is applied once at the end)
+      for (int r = 0; r < kBwdRows; r++) {
+        float sr[4], qv[OC];
+#pragma unroll
+        for (int a = 0; a < 4; a++) sr[a] = ps[r * LP + 4 * ty + a];
+#pragma unroll
+        for (int b = 0; b < OC; b++) qv[b] = qs[r * LD + tx + 16 * b];
+#pragma unroll
+        for (int a = 0; a < 4; a++)
+#pragma unroll
+          for (int b = 0; b < OC; b++) dkacc[a][b] += sr[a] * qv[b];
+      }
+    }
+  }
+  __syncthreads();
+
+  // ---- linear branch: dH = dH_total - sum over the query blocks that selected j of dH_i ----
+  const bool all_selected = ksel >= Tn;
+  float dhj[MT][MT];
+  {
+    const float* tot = dh_total + (size_t)bh * D * D;
+#pragma unroll
+    for (int a = 0; a < MT; a++)
+#pragma unroll
+      for (int b = 0; b < MT; b++) dhj[a][b] = all_selected ? 0.f : tot[(MT * ty + a) * D + tx + 16 * b];
+    float dzj = (tid < D && !all_selected) ? dz_total[(size_t)bh * D + tid] : 0.f;
+    if (!all_selected)
+      for (int l = l0; l < l1; l++)
+        for (int part = 0; part < parts; part++) {
+          const size_t slot = ((size_t)bh * Tm + ci[l]) * parts + part;
+          const float* src = dh_in + slot * D * D;
+#pragma unroll
+          for (int a = 0; a < MT; a++)
+#pragma unroll
+            for (int b = 0; b < MT; b++) dhj[a][b] -= src[(MT * ty + a) * D + tx + 16 * b];
+          if (tid < D) dzj -= dz_in[slot * D + tid];
+        }
+    if (tid < D) dzs[tid] = dzj;
+  }
+  // K' -> K^phi in place
+  for (int idx = tid; idx < kBwdBK * D; idx += 256) {
+    const int t = idx / D, c = idx % D;
+    float kp = 0.f;
+    if (t < valid) kp = __expf(ks[t * LD + c] - k_stats[(size_t)bh * N + t0 + t]);
+    ks[t * LD + c] = kp;
+  }
+#pragma unroll
+  for (int a = 0; a < MT; a++)
+#pragma unroll
+    for (int b = 0; b < MT; b++) dhs[(MT * ty + a) * D + tx + 16 * b] = dhj[a][b];      // dH[c][e]
+  __syncthreads();
+  // dV[token][e] += sum_c K^phi[token][c] dH[c][e]
+  for (int c = 0; c < D; c++) {
+    float kp[4], hv[OC];
+#pragma unroll
+    for (int a = 0; a < 4; a++) kp[a] = ks[(4 * ty + a) * LD + c];
+#pragma unroll
+    for (int b = 0; b < OC; b++) hv[b] = dhs[c * D + tx + 16 * b];
+#pragma unroll
+    for (int a = 0; a < 4; a++)
+#pragma unroll
+      for (int b = 0; b < OC; b++) dvacc[a][b] += kp[a] * hv[b];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int a = 0; a < MT; a++)
+#pragma unroll
+    for (int b = 0; b < MT; b++) dhs[(tx + 16 * b) * D + MT * ty + a] = dhj[a][b];      // dH^T[e][c]
+  __syncthreads();
+  // dK^phi[token][c] = sum_e V[token][e] dH[c][e] + dZ[c]
+  float dkp[4][OC];
+#pragma unroll
+  for (int a = 0; a < 4; a++)
+#pragma unroll
+    for (int b = 0; b < OC; b++) dkp[a][b] = dzs[tx + 16 * b];
+  for (int e = 0; e < D; e++) {
+    float vv[4], hv[OC];
+#pragma unroll
+    for (int a = 0; a < 4; a++) vv[a] = vs[(4 * ty + a) * LD + e];
+#pragma unroll
+    for (int b = 0; b < OC; b++) hv[b] = dhs[e * D + tx + 16 * b];
+#pragma unroll
+    for (int a = 0; a < 4; a++)
+#pragma unroll
+      for (int b = 0; b < OC; b++) dkp[a][b] += vv[a] * hv[b];
+  }
+  // back through the softmax, add the sparse part, store; column sums of dK' for the smoothing term
+  T* dkh = dk + head_offset(sin, bh, H);
+  T* dvh = dv + head_offset(sin, bh, H);
+  float csum[OC];
+#pragma unroll
+  for (int b = 0; b < OC; b++) csum[b] = 0.f;
+#pragma unroll
+  for (int a = 0; a < 4; a++) {
+    const int t = 4 * ty + a;
+    float dot = 0.f;
+#pragma unroll
+    for (int b = 0; b < OC; b++) dot += dkp[a][b] * ks[t * LD + tx + 16 * b];
+    dot = row_sum16(dot);
+    if (t < valid) {
+#pragma unroll
+      for (int b = 0; b < OC; b++) {
+        const int c = tx + 16 * b;
+        const float g = dkacc[a][b] * rscale + ks[t * LD + c] * (dkp[a][b] - dot);
+        csum[b] += g;
+        store_elem(dkh, (size_t)(t0 + t) * sin.n + c, g);
+        store_elem(dvh, (size_t)(t0 + t) * sin.n + c, dvacc[a][b]);
+      }
+    }
+  }
+#pragma unroll
+  for (int b = 0; b < OC; b++) red[ty * D + tx + 16 * b] = csum[b];
+  __syncthreads();
+  if (tid < D) {
+    float t = 0.f;
+    for (int g = 0; g < 16; g++) t += red[g * D + tid];
+    colsum[((size_t)bh * Tn + j) * D + tid] = t;
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// mean[bh][c] = sum_j colsum[bh][j][c] / N  (ascending j)
+__global__ __launch_bounds__(128) void bwd_colmean_kernel(const float* __restrict__ colsum, float* __restrict__ mean,
+                                                          int Tn, int N, int d) {
+  const int bh = blockIdx.x, c = threadIdx.x;
+  if (c >= d) return;
+  float s = 0.f;
+  for (int j = 0; j < Tn; j++) s += colsum[((size_t)bh * Tn + j) * d + c];
+  mean[(size_t)bh * d + c] = s / (float)N;
+}
+
+// dK = dK' - colmean(dK'): the gradient of K' = K - colmean(K)
+template <typename T>
+__global__ __launch_bounds__(256) void bwd_unsmooth_kernel(T* __restrict__ dk, const float* __restrict__ mean, Strides sin,
+                                                           int H, int N, int d) {
+  const int bh = blockIdx.y;
+  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+  if (e >= (size_t)N * d) return;
+  const int t = (int)(e / d), c = (int)(e % d);
+  T* p = dk + head_offset(sin, bh, H);
+  const size_t at = (size_t)t * sin.n + c;
+  store_elem(p, at, load_elem(p, at) - mean[(size_t)bh * d + c]);
+}
+
+// d alpha: per head [H] (sum over batch, query blocks and parts) or per query block [H, T_m] (batch and parts)
+__global__ __launch_bounds__(256) void bwd_dalpha_kernel(const float* __restrict__ part, float* __restrict__ dalpha, int B,
+                                                         int H, int Tm, int parts, int alpha_per_block) {
+  const int n = alpha_per_block ? H * Tm : H;
+  const int x = blockIdx.x * 256 + threadIdx.x;
+  if (x >= n) return;
+  const int h = alpha_per_block ? x / Tm : x;
+  float s = 0.f;
+  for (int b = 0; b < B; b++) {
+    const float* p = part + ((size_t)(b * H + h) * Tm) * parts;
+    if (alpha_per_block) {
+      const int i = x % Tm;
+      for (int y = 0; y < parts; y++) s += p[(size_t)i * parts + y];
+    } else {
+      for (int y = 0; y < Tm * parts; y++) s += p[y];
+    }
+  }
+  dalpha[x] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
+template <typename T, int D>
+static hipError_t launch_backward_t(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  const int parts = s.bq / kBwdRows;
+  const size_t smem_q = ((size_t)4 * 64 * (D + 1) + 64 * 65 + D + 64 + 64 + 256) * sizeof(float);
+  const size_t smem_kv = ((size_t)4 * 64 * (D + 1) + 64 * 65 + 64 + 64 + D + 16 * D) * sizeof(float);
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)bwd_q_kernel<T, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)smem_q);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)bwd_kv_kernel<T, D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_kv);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  // k = 0: every list is empty and the kernel writes all-zero offsets
+  bwd_transpose_kernel<<<dim3((unsigned)s.BH), 256, 0, stream>>>(a.block_idx, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
+  bwd_q_kernel<T, D><<<dim3((unsigned)((size_t)s.BH * s.Tm * parts)), 256, smem_q, stream>>>(
+      (const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.dout, (const T*)a.o_s, (const T*)a.o_l, a.lse, a.k_mean,
+      a.k_stats, a.h_total, a.z_total, a.block_idx, a.alpha, (T*)a.dq, a.ds, a.dh, a.dz, a.dalpha_part, s.sin, s.sout,
+      s.H, s.N, s.bq, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
+  bwd_sum_kernel<<<dim3((unsigned)((D * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(a.dh, a.dh_total,
+                                                                                            s.Tm * parts, D * D);
+  bwd_sum_kernel<<<dim3((unsigned)((D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(a.dz, a.dz_total, s.Tm * parts, D);
+  bwd_kv_kernel<T, D><<<dim3((unsigned)((size_t)s.BH * s.Tn)), 256, smem_kv, stream>>>(
+      (const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.dout, a.lse, a.ds, a.k_mean, a.k_stats, a.col_ptr,
+      a.col_idx, a.dh, a.dz, a.dh_total, a.dz_total, a.alpha, (T*)a.dk, (T*)a.dv, a.colsum, s.sin, s.sout, s.H, s.N,
+      s.bq, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
+  if (s.smooth) {
+    bwd_colmean_kernel<<<dim3((unsigned)s.BH), 128, 0, stream>>>(a.colsum, a.dk_mean, s.Tn, s.N, D);
+    bwd_unsmooth_kernel<T><<<dim3((unsigned)(((size_t)s.N * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
+        (T*)a.dk, a.dk_mean, s.sin, s.H, s.N, D);
+  }
+  const int n_alpha = s.alpha_per_block ? s.H * s.Tm : s.H;
+  bwd_dalpha_kernel<<<dim3((unsigned)((n_alpha + 255) / 256)), 256, 0, stream>>>(a.dalpha_part, a.dalpha, s.B, s.H, s.Tm,
+                                                                                 parts, s.alpha_per_block ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_backward(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  if (s.bf16) return s.d == 128 ? launch_backward_t<uint16_t, 128>(s, a, stream) : launch_backward_t<uint16_t, 64>(s, a, stream);
+  return s.d == 128 ? launch_backward_t<float, 128>(s, a, stream) : launch_backward_t<float, 64>(s, a, stream);
+}
+
+}  // namespace sla2

@@ -162,8 +162,10 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
                                                        const float* __restrict__ z_total,
                                                        const int32_t* __restrict__ block_idx,
                                                        const float* __restrict__ alpha, float* __restrict__ out,
-                                                       float* __restrict__ lse, Strides sin, Strides sout, int H,
-                                                       int N, int bq, int Tm, int Tn, int ksel, int alpha_per_block) {
+                                                       float* __restrict__ lse, float* __restrict__ o_s_save,
+                                                       float* __restrict__ o_l_save, float* __restrict__ lse_save,
+                                                       Strides sin, Strides sout, int H, int N, int bq, int Tm, int Tn,
+                                                       int ksel, int alpha_per_block) {
   constexpr int LD = D + 1;
   constexpr int LP = kBK + 1;
   constexpr int MT = D / 16;       // h micro-tile edge
@@ -365,7 +367,17 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float* __restrict__
     float* o = out + head_offset(sout, bh, H) + (size_t)(row0 + r) * sout.n;
 #pragma unroll
     for (int b = 0; b < OC; b++) o[tx + 16 * b] = al * oacc[a][b] * inv_l + (1.f - al) * lacc[a][b] * inv_den;
-    if (lse && tx == 0) lse[(size_t)bh * N + row0 + r] = l_run[a] > 0.f ? m_run[a] + __logf(l_run[a]) : -INFINITY;
+    const float L = l_run[a] > 0.f ? m_run[a] + __logf(l_run[a]) : -INFINITY;
+    if (lse && tx == 0) lse[(size_t)bh * N + row0 + r] = L;
+    if (o_s_save) {                                   // the two branches and L, kept for the backward pass
+      const size_t at = ((size_t)bh * N + row0 + r) * D;
+#pragma unroll
+      for (int b = 0; b < OC; b++) {
+        o_s_save[at + tx + 16 * b] = oacc[a][b] * inv_l;
+        o_l_save[at + tx + 16 * b] = lacc[a][b] * inv_den;
+      }
+      if (tx == 0) lse_save[(size_t)bh * N + row0 + r] = L;
+    }
   }
 }
 
@@ -373,7 +385,7 @@ template <int D>
 static hipError_t launch_attn_f32_t(const Shape& s, const float* q, const float* k, const float* v,
                                     const double* k_mean, const float* k_stats, const float* h_total,
                                     const float* z_total, const int32_t* block_idx, const float* alpha, float* out,
-                                    float* lse, hipStream_t stream) {
+                                    float* lse, const SavedForBackward& sv, hipStream_t stream) {
   size_t smem = ((size_t)3 * 64 * (D + 1) + 64 * 65 + D) * sizeof(float);
   static bool configured = false;
   if (!configured) {
@@ -384,17 +396,19 @@ static hipError_t launch_attn_f32_t(const Shape& s, const float* q, const float*
   }
   dim3 grid((unsigned)((size_t)s.BH * s.Tm * (s.bq / kRowsF32)));
   attn_f32_kernel<D><<<grid, 256, smem, stream>>>(q, k, v, k_mean, k_stats, h_total, z_total, block_idx, alpha, out,
-                                                  lse, s.sin, s.sout, s.H, s.N, s.bq, s.Tm, s.Tn, s.k,
+                                                  lse, (float*)sv.o_s, (float*)sv.o_l, sv.lse, s.sin, s.sout, s.H, s.N,
+                                                  s.bq, s.Tm, s.Tn, s.k,
                                                   s.alpha_per_block ? 1 : 0);
   return hipGetLastError();
 }
 
 hipError_t launch_attn_f32(const Shape& s, const float* q, const float* k, const float* v, const double* k_mean,
                            const float* k_stats, const float* h_total, const float* z_total, const int32_t* block_idx,
-                           const float* alpha, float* out, float* lse, hipStream_t stream) {
+                           const float* alpha, float* out, float* lse, const SavedForBackward& sv,
+                           hipStream_t stream) {
   if (s.d == 128)
-    return launch_attn_f32_t<128>(s, q, k, v, k_mean, k_stats, h_total, z_total, block_idx, alpha, out, lse, stream);
-  return launch_attn_f32_t<64>(s, q, k, v, k_mean, k_stats, h_total, z_total, block_idx, alpha, out, lse, stream);
+    return launch_attn_f32_t<128>(s, q, k, v, k_mean, k_stats, h_total, z_total, block_idx, alpha, out, lse, sv, stream);
+  return launch_attn_f32_t<64>(s, q, k, v, k_mean, k_stats, h_total, z_total, block_idx, alpha, out, lse, sv, stream);
 }
 
 }  // namespace sla2

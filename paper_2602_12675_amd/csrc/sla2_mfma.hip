@@ -423,8 +423,9 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     const uint8_t* __restrict__ k_codes, const float* __restrict__ k_scale, const uint8_t* __restrict__ v_codes,
     const float* __restrict__ v_scale, const float* __restrict__ h_total,
     const float* __restrict__ z_total, const int32_t* __restrict__ block_idx, const float* __restrict__ alpha,
-    uint16_t* __restrict__ out, float* __restrict__ lse, Strides sin, Strides sout, int H, int N, int Tm, int Tn,
-    int ksel, int alpha_per_block, int total_blocks) {
+    uint16_t* __restrict__ out, float* __restrict__ lse, uint16_t* __restrict__ o_s_save,
+    uint16_t* __restrict__ o_l_save, float* __restrict__ lse_save, Strides sin, Strides sout, int H, int N, int Tm,
+    int Tn, int ksel, int alpha_per_block, int total_blocks) {
   // FP8 below means "8-bit codes of Q and K": everything the two low-bit modes share.  INT8 marks the
   // places where the integer mode differs (the quantiser of Q and the Q K^T product).
   // FP8V: V is quantised too and P V runs as an FP8 product (the linear branch still reads the bf16 V).
@@ -860,7 +861,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   // ================= epilogue =================
   const float inv_l = l_run > 0.f ? 1.f / l_run : 0.f;
   const int qrow = 32 * w + lane % 32;               // this lane's query row inside the block
-  if (lse != nullptr) {
+  if (lse != nullptr || lse_save != nullptr) {
     // Alg. 2 defines L on the smoothed keys.  The bf16 products above use the raw K, whose scores
     // are larger by q . colmean(K) / sqrt(d) in every column of a row (the softmax cancels it);
     // the FP8 codes are those of the smoothed K already.
@@ -872,9 +873,12 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         for (int e = 0; e < 8; e++) qmu += (float)qf[ks][e] * (float)k_mean[(size_t)bh * D + 16 * ks + 8 * g + e];
       qmu = half_sum(qmu);
     }
-    if (g == 0 && qrow < rows_valid)
-      lse[(size_t)bh * N + row0 + qrow] =
+    if (g == 0 && qrow < rows_valid) {
+      const float L =
           l_run > 0.f ? (m_run - kPShift + __log2f(l_run)) * 0.6931471805599453f - qmu * rsqrtf((float)D) : -INFINITY;
+      if (lse != nullptr) lse[(size_t)bh * N + row0 + qrow] = L;
+      if (lse_save != nullptr) lse_save[(size_t)bh * N + row0 + qrow] = L;
+    }
   }
 
   if constexpr (FP8) {
@@ -981,6 +985,34 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     const int r = idx / (D / 8), ch = idx % (D / 8);
     if (r < rows_valid) *reinterpret_cast<u32x4*>(oh + (size_t)r * sout.n + 8 * ch) = *reinterpret_cast<const u32x4*>(os + r * LD + 8 * ch);
   }
+  if (o_s_save != nullptr) {
+    // the two branches on their own ([BH, N, d] contiguous), kept for the backward pass: same route
+    // through the transposing tile as the mixed output
+    for (int which = 0; which < 2; which++) {
+      __syncthreads();                                 // the tile has been read out
+#pragma unroll
+      for (int et = 0; et < ET; et++)
+#pragma unroll
+        for (int v4 = 0; v4 < 4; v4++) {
+          bf16x4 pk;
+#pragma unroll
+          for (int r = 0; r < 4; r++) {
+            float o = which == 0 ? oacc[et][4 * v4 + r] * inv_l * (FP8V ? sv_prev : 1.f) : 0.f;
+            if constexpr (!DENSE) {
+              if (which == 1) o = lacc[et][4 * v4 + r] * inv_den;
+            }
+            pk[r] = (__bf16)o;
+          }
+          *reinterpret_cast<bf16x4*>(os + qrow * LD + 32 * et + 8 * v4 + 4 * g) = pk;
+        }
+      __syncthreads();
+      uint16_t* dst = (which == 0 ? o_s_save : o_l_save) + ((size_t)bh * N + row0) * D;
+      for (int idx = tid; idx < BQ * (D / 8); idx += NT) {
+        const int r = idx / (D / 8), ch = idx % (D / 8);
+        if (r < rows_valid) *reinterpret_cast<u32x4*>(dst + (size_t)r * D + 8 * ch) = *reinterpret_cast<const u32x4*>(os + r * LD + 8 * ch);
+      }
+    }
+  }
   SLA2_PHASE_MARK(6)
 }
 
@@ -997,6 +1029,7 @@ struct AttnArgs {
   const float* alpha;
   uint16_t* out;
   float* lse;
+  SavedForBackward sv;
 };
 
 template <int D, int BQ, int MODE>
@@ -1015,7 +1048,8 @@ static hipError_t launch_attn_t(const Shape& s, const AttnArgs& a, hipStream_t s
   attn_mfma_kernel<D, BQ, MODE><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(
       a.q, a.k, a.v, a.k_mean, a.k_phi, a.z_blocks, a.k_fp8, a.k_scale, a.v_codes, a.v_scale, a.h_total, a.z_total,
       a.block_idx, a.alpha,
-      a.out, a.lse, s.sin, s.sout, s.H, s.N, Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0, total);
+      a.out, a.lse, (uint16_t*)a.sv.o_s, (uint16_t*)a.sv.o_l, a.sv.lse, s.sin, s.sout, s.H, s.N, Tm, s.Tn, s.k,
+      s.alpha_per_block ? 1 : 0, total);
   return hipGetLastError();
 }
 
@@ -1024,8 +1058,8 @@ hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k
                             const float* k_scale, const uint8_t* v_codes, const float* v_scale,
                             const float* h_total, const float* z_total,
                             const int32_t* block_idx, const float* alpha, uint16_t* out, float* lse,
-                            hipStream_t stream) {
-  AttnArgs a{q, k, v, k_mean, k_phi, z_blocks, k_fp8, k_scale, v_codes, v_scale, h_total, z_total, block_idx, alpha, out, lse};
+                            const SavedForBackward& sv, hipStream_t stream) {
+  AttnArgs a{q, k, v, k_mean, k_phi, z_blocks, k_fp8, k_scale, v_codes, v_scale, h_total, z_total, block_idx, alpha, out, lse, sv};
 #define SLA2_ATTN(DD, QQ)                                                  \
   return s.quant == 3 ? launch_attn_t<DD, QQ, kSparseFp8V>(s, a, stream)   \
        : s.quant == 2 ? launch_attn_t<DD, QQ, kSparseInt8>(s, a, stream)   \
@@ -1040,7 +1074,8 @@ hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k
 
 hipError_t launch_dense_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
                              hipStream_t stream) {
-  AttnArgs a{q, k, v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, out, nullptr};
+  AttnArgs a{q, k, v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, out, nullptr,
+             SavedForBackward{nullptr, nullptr, nullptr}};
   if (s.d == 128) return launch_attn_t<128, 128, kDenseBf16>(s, a, stream);
   return launch_attn_t<64, 128, kDenseBf16>(s, a, stream);
 }

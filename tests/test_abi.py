@@ -37,7 +37,7 @@ def test_every_declared_symbol_is_exported(api):
 
 def test_struct_sizes_match_header(api):
     assert ctypes.sizeof(api.Params) == 12 * 4 + 6 * 8
-    assert ctypes.sizeof(api.WsLayout) == 16 * ctypes.sizeof(ctypes.c_size_t)
+    assert ctypes.sizeof(api.WsLayout) == 20 * ctypes.sizeof(ctypes.c_size_t)
 
 
 def test_num_selected_and_workspace(api):
