@@ -67,10 +67,14 @@ __device__ __forceinline__ void store_elem(float* p, size_t i, float v) { p[i] =
 __device__ __forceinline__ void store_elem(uint16_t* p, size_t i, float v) { p[i] = f32_to_bf16_bits(v); }
 
 // Where sla2_forward keeps O^s, O^l ([BH, N, d], element type of out) and L ([BH, N]) for the backward
-// pass; all null when nothing is to be kept.
+// pass; all null when nothing is to be kept.  The bf16 kernels also keep the state of the linear branch
+// per query block: H_i^T as bf16 [BH, T_m, d(e), d(c)] and Z_i [BH, T_m, d] (null for fp32 tensors, whose
+// backward pass rebuilds them).
 struct SavedForBackward {
   void *o_s, *o_l;
   float* lse;
+  uint16_t* h_i;
+  float* z_i;
 };
 
 // Everything the backward kernels touch (device pointers).
@@ -83,11 +87,17 @@ struct BwdArgs {
   const float* alpha;
   void *dq, *dk, *dv;
   float* dalpha;
-  // scratch
-  float *ds, *dh, *dz, *dh_total, *dz_total, *colsum, *dk_mean, *dalpha_part;
+  // kept by the bf16 forward kernel: H_i^T as bf16 [BH, T_m, d, d], Z_i [BH, T_m, d]
+  const uint16_t* h_i;
+  const float* z_i;
+  // scratch.  dh: one d x d slot per query block as bf16 (bf16 tensors) or per 64 query rows as fp32
+  float *ds, *lraw, *dz, *dh_total, *dz_total, *colsum, *dk_mean, *dalpha_part;
+  void* dh;
   int32_t *col_ptr, *col_idx;
 };
 hipError_t launch_backward(const Shape& s, const BwdArgs& a, hipStream_t stream);
+hipError_t launch_bwd_q_bf16(const Shape& s, const BwdArgs& a, hipStream_t stream);   // matrix-core kernels, bf16 tensors
+hipError_t launch_bwd_kv_bf16(const Shape& s, const BwdArgs& a, hipStream_t stream);
 
 // ---- launchers (one per kernel file); all enqueue on `stream` and return hipGetLastError() ----
 hipError_t launch_block_sums(const Shape& s, const void* q, const void* k, const float* router_w, double* q_sum,

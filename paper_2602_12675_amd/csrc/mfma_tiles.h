@@ -14,6 +14,16 @@
 namespace sla2 {
 
 constexpr int kTileTokens = 64;                    // b_kv
+constexpr int kXcds = 8;                           // L2 domains; workgroups are dealt to them round-robin
+constexpr int kVmcnt0 = 0x0F70;                    // s_waitcnt vmcnt(0), other counters untouched
+
+// lanes l and l ^ 32 combine their values; both get the same bits
+__device__ __forceinline__ float half_sum(float x) { return x + __shfl_xor(x, 32); }
+__device__ __forceinline__ float half_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
+
+__device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
+  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
 
 // ---- LDS layouts of a 64-token tile of bf16 rows --------------------------------------------------
 // Padded: rows of D + 8 elements (written with ordinary LDS stores).

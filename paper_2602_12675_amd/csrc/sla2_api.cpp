@@ -72,15 +72,16 @@ static int make_shape(const sla2_params* p, Shape* s) {
 
 // scratch of the backward pass, carved out of the `bwd` region of the workspace
 struct BwdLayout {
-  size_t ds, dh, dz, dh_total, dz_total, colsum, dk_mean, dalpha_part, col_ptr, col_idx, total;
+  size_t ds, dh, dz, dh_total, dz_total, colsum, dk_mean, dalpha_part, col_ptr, col_idx, h_i, z_i, lraw, total;
 };
 static BwdLayout make_bwd_layout(const Shape& s) {
   BwdLayout B;
   size_t off = 0, BH = (size_t)s.BH, d = (size_t)s.d;
   auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
-  const size_t slots = BH * s.Tm * (size_t)(s.bq / 64);          // one per 64 query rows
+  // dH_i, dZ_i, d alpha parts: one slot per query block (bf16 tensors; dH_i as bf16) or per 64 query rows (fp32)
+  const size_t slots = BH * s.Tm * (size_t)(s.bf16 ? 1 : s.bq / 64);
   B.ds = take(BH * (size_t)s.N * sizeof(float));
-  B.dh = take(slots * d * d * sizeof(float));
+  B.dh = take(slots * d * d * (s.bf16 ? 2 : sizeof(float)));
   B.dz = take(slots * d * sizeof(float));
   B.dh_total = take(BH * d * d * sizeof(float));
   B.dz_total = take(BH * d * sizeof(float));
@@ -89,6 +90,10 @@ static BwdLayout make_bwd_layout(const Shape& s) {
   B.dalpha_part = take(slots * sizeof(float));
   B.col_ptr = take(BH * (size_t)(s.Tn + 1) * sizeof(int32_t));
   B.col_idx = take(BH * s.Tm * (size_t)(s.k > 0 ? s.k : 1) * sizeof(int32_t));
+  // bf16 tensors: the forward kernel leaves H_i^T (bf16) and Z_i per query block here; L on the raw keys
+  B.h_i = take(s.bf16 ? BH * s.Tm * d * d * 2 : 0);
+  B.z_i = take(s.bf16 ? BH * s.Tm * d * sizeof(float) : 0);
+  B.lraw = take(s.bf16 ? BH * (size_t)s.N * sizeof(float) : 0);
   B.total = off;
   return B;
 }
@@ -280,8 +285,15 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
     if (hipMemcpyAsync(block_idx_or_null, idx, bytes, hipMemcpyDeviceToDevice, st) != hipSuccess) return SLA2_EHIP;
   }
   const double* k_mean = at<double>(workspace, L.k_mean);
-  SavedForBackward sv{nullptr, nullptr, nullptr};
-  if (s.save) sv = SavedForBackward{at<void>(workspace, L.o_s), at<void>(workspace, L.o_l), at<float>(workspace, L.lse)};
+  SavedForBackward sv{nullptr, nullptr, nullptr, nullptr, nullptr};
+  if (s.save) {
+    sv = SavedForBackward{at<void>(workspace, L.o_s), at<void>(workspace, L.o_l), at<float>(workspace, L.lse), nullptr, nullptr};
+    if (s.bf16) {
+      const BwdLayout B = make_bwd_layout(s);
+      sv.h_i = (uint16_t*)(at<char>(workspace, L.bwd) + B.h_i);
+      sv.z_i = (float*)(at<char>(workspace, L.bwd) + B.z_i);
+    }
+  }
   float* k_stats = at<float>(workspace, L.k_stats);
   float* h_total = at<float>(workspace, L.h_total);
   float* z_total = at<float>(workspace, L.z_total);
@@ -350,7 +362,8 @@ int sla2_backward(const sla2_params* params, const void* q, const void* k, const
   a.block_idx = at<int32_t>(workspace, L.block_idx);
   a.alpha = alpha;
   a.dq = dq; a.dk = dk; a.dv = dv; a.dalpha = dalpha;
-  a.ds = (float*)(bw + B.ds); a.dh = (float*)(bw + B.dh); a.dz = (float*)(bw + B.dz);
+  a.h_i = (const uint16_t*)(bw + B.h_i); a.z_i = (const float*)(bw + B.z_i); a.lraw = (float*)(bw + B.lraw);
+  a.ds = (float*)(bw + B.ds); a.dh = (void*)(bw + B.dh); a.dz = (float*)(bw + B.dz);
   a.dh_total = (float*)(bw + B.dh_total); a.dz_total = (float*)(bw + B.dz_total);
   a.colsum = (float*)(bw + B.colsum); a.dk_mean = (float*)(bw + B.dk_mean);
   a.dalpha_part = (float*)(bw + B.dalpha_part);

@@ -359,14 +359,15 @@ __global__ __launch_bounds__(256) void bwd_q_kernel(
 
 // ---------------------------------------------------------------------------------------------
 // dst[bh][e] = sum over b < count of src[bh][b][e]   (ascending b)
-__global__ __launch_bounds__(256) void bwd_sum_kernel(const float* __restrict__ src, float* __restrict__ dst, int count,
+template <typename S>
+__global__ __launch_bounds__(256) void bwd_sum_kernel(const S* __restrict__ src, float* __restrict__ dst, int count,
                                                       int len) {
   const int bh = blockIdx.y;
   const int e = blockIdx.x * 256 + threadIdx.x;
   if (e >= len) return;
-  const float* p = src + (size_t)bh * count * len + e;
+  const S* p = src + (size_t)bh * count * len + e;
   float s = 0.f;
-  for (int b = 0; b < count; b++) s += p[(size_t)b * len];
+  for (int b = 0; b < count; b++) s += load_elem(p, (size_t)b * len);
   dst[(size_t)bh * len + e] = s;
 }
 
@@ -676,15 +677,16 @@ static hipError_t launch_backward_t(const Shape& s, const BwdArgs& a, hipStream_
   bwd_transpose_kernel<<<dim3((unsigned)s.BH), 256, 0, stream>>>(a.block_idx, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
   bwd_q_kernel<T, D><<<dim3((unsigned)((size_t)s.BH * s.Tm * parts)), 256, smem_q, stream>>>(
       (const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.dout, (const T*)a.o_s, (const T*)a.o_l, a.lse, a.k_mean,
-      a.k_stats, a.h_total, a.z_total, a.block_idx, a.alpha, (T*)a.dq, a.ds, a.dh, a.dz, a.dalpha_part, s.sin, s.sout,
-      s.H, s.N, s.bq, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
-  bwd_sum_kernel<<<dim3((unsigned)((D * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(a.dh, a.dh_total,
-                                                                                            s.Tm * parts, D * D);
-  bwd_sum_kernel<<<dim3((unsigned)((D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(a.dz, a.dz_total, s.Tm * parts, D);
+      a.k_stats, a.h_total, a.z_total, a.block_idx, a.alpha, (T*)a.dq, a.ds, (float*)a.dh, a.dz, a.dalpha_part, s.sin,
+      s.sout, s.H, s.N, s.bq, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
+  bwd_sum_kernel<float><<<dim3((unsigned)((D * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
+      (const float*)a.dh, a.dh_total, s.Tm * parts, D * D);
+  bwd_sum_kernel<float><<<dim3((unsigned)((D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(a.dz, a.dz_total,
+                                                                                             s.Tm * parts, D);
   bwd_kv_kernel<T, D><<<dim3((unsigned)((size_t)s.BH * s.Tn)), 256, smem_kv, stream>>>(
       (const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.dout, a.lse, a.ds, a.k_mean, a.k_stats, a.col_ptr,
-      a.col_idx, a.dh, a.dz, a.dh_total, a.dz_total, a.alpha, (T*)a.dk, (T*)a.dv, a.colsum, s.sin, s.sout, s.H, s.N,
-      s.bq, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
+      a.col_idx, (const float*)a.dh, a.dz, a.dh_total, a.dz_total, a.alpha, (T*)a.dk, (T*)a.dv, a.colsum, s.sin, s.sout,
+      s.H, s.N, s.bq, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
   if (s.smooth) {
     bwd_colmean_kernel<<<dim3((unsigned)s.BH), 128, 0, stream>>>(a.colsum, a.dk_mean, s.Tn, s.N, D);
     bwd_unsmooth_kernel<T><<<dim3((unsigned)(((size_t)s.N * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
@@ -696,8 +698,31 @@ static hipError_t launch_backward_t(const Shape& s, const BwdArgs& a, hipStream_
   return hipGetLastError();
 }
 
+// bf16 tensors: the two heavy kernels run on the matrix cores (one dH_i slot per query block, kept as
+// bf16); the small ones above are shared.
+static hipError_t launch_backward_bf16(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  const int D = s.d;
+  bwd_transpose_kernel<<<dim3((unsigned)s.BH), 256, 0, stream>>>(a.block_idx, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
+  hipError_t e = launch_bwd_q_bf16(s, a, stream);
+  if (e != hipSuccess) return e;
+  bwd_sum_kernel<uint16_t><<<dim3((unsigned)((D * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
+      (const uint16_t*)a.dh, a.dh_total, s.Tm, D * D);
+  bwd_sum_kernel<float><<<dim3((unsigned)((D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(a.dz, a.dz_total, s.Tm, D);
+  e = launch_bwd_kv_bf16(s, a, stream);
+  if (e != hipSuccess) return e;
+  if (s.smooth) {
+    bwd_colmean_kernel<<<dim3((unsigned)s.BH), 128, 0, stream>>>(a.colsum, a.dk_mean, s.Tn, s.N, D);
+    bwd_unsmooth_kernel<uint16_t><<<dim3((unsigned)(((size_t)s.N * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
+        (uint16_t*)a.dk, a.dk_mean, s.sin, s.H, s.N, D);
+  }
+  const int n_alpha = s.alpha_per_block ? s.H * s.Tm : s.H;
+  bwd_dalpha_kernel<<<dim3((unsigned)((n_alpha + 255) / 256)), 256, 0, stream>>>(a.dalpha_part, a.dalpha, s.B, s.H, s.Tm, 1,
+                                                                                 s.alpha_per_block ? 1 : 0);
+  return hipGetLastError();
+}
+
 hipError_t launch_backward(const Shape& s, const BwdArgs& a, hipStream_t stream) {
-  if (s.bf16) return s.d == 128 ? launch_backward_t<uint16_t, 128>(s, a, stream) : launch_backward_t<uint16_t, 64>(s, a, stream);
+  if (s.bf16) return launch_backward_bf16(s, a, stream);
   return s.d == 128 ? launch_backward_t<float, 128>(s, a, stream) : launch_backward_t<float, 64>(s, a, stream);
 }
 

@@ -1,0 +1,710 @@
+// Backward pass of SLA2 on the matrix cores, for bf16 tensors (Alg. 3 of the paper's appendix with the
+// steps it leaves to automatic differentiation written out; Sec. 5: the backward pass is never
+// quantised).  Products run as v_mfma_f32_32x32x16_bf16 with fp32 accumulation; everything between
+// them (exp, the D^s / D^l terms, both softmax-backward steps) is fp32.
+//
+// Both kernels keep the scores transposed, S^T = K Q^T (keys x query rows), as the forward kernel does:
+// one lane owns one query row, so L and D^s of the row are per-lane scalars and dS^T can go straight
+// back into the next product as its B operand.
+//
+//   bwd_q_mfma   one workgroup per query block i (b_q rows, one wave per 32 rows).  Over the selected
+//                key blocks: P^T = exp(S^T - L), dP^T = V dO^s^T, dS^T = P^T (.) (dP^T - D^s),
+//                dQ^T += K^T dS^T.  Then the linear branch from the H_i^T, Z_i the forward pass kept:
+//                dQ^phi^T = H_i dO^l^T - Z_i D^l^T (over Q^phi Z_i), dQ += softmax-backward(dQ^phi),
+//                dH_i = (Q^phi / (Q^phi Z_i))^T dO^l, dZ_i.
+//   bwd_kv_mfma  one workgroup per key block j, over the query blocks that selected it, 64 rows a
+//                step: P^T and dS^T as above, written to LDS as [row][key] tiles, then
+//                dV^T += dO^T (alpha P), dK'^T += Q^T dS.  Then the linear branch:
+//                dH = dH_total - sum over those query blocks of dH_i (Alg. 3's M_c[i, j] = 0 sum, by
+//                complement), dK^phi^T = dH V^T + dZ 1^T, dV^T += dH^T K^phi^T,
+//                dK' += softmax-backward(dK^phi).
+#include "mfma_tiles.h"
+
+namespace sla2 {
+
+// ---------------------------------------------------------------------------------------------
+template <int D, int BQ> struct BwdQSmem {
+  static constexpr int kLd = D + 8;
+  static constexpr int kTile = SwizzledLayout<D>::kTileBytes;                  // one 64 x D bf16 tile
+  static constexpr int kLoopBytes = 4 * kTile;                                 // two buffers of (K, V)
+  static constexpr int kEpiA = (D > BQ ? D : BQ) * kLd * 2;                    // H_i^T [D][kLd], later w [BQ][kLd]
+  static constexpr int kEpiB = BQ * kLd * 2;                                   // dQ tile, later dO^l [BQ][kLd]
+  static constexpr int kTiles = kLoopBytes > kEpiA + kEpiB ? kLoopBytes : kEpiA + kEpiB;
+  static constexpr int kZsOff = kTiles;                                        // float [D]   Z_i
+  static constexpr int kMuOff = kZsOff + D * 4;                                // float [D]   colmean(K)
+  static constexpr int kDlOff = kMuOff + D * 4;                                // float [BQ]  D^l per row
+  static constexpr int kRedOff = kDlOff + BQ * 4;                              // float [8]
+  static constexpr int kBytes = kRedOff + 32;
+};
+
+template <int D, int BQ>
+__global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const uint16_t* __restrict__ dout, const uint16_t* __restrict__ o_s, const uint16_t* __restrict__ o_l,
+    const float* __restrict__ lse, const double* __restrict__ k_mean, const uint16_t* __restrict__ h_i,
+    const float* __restrict__ z_i, const int32_t* __restrict__ block_idx, const float* __restrict__ alpha,
+    uint16_t* __restrict__ dq, float* __restrict__ ds_out, float* __restrict__ lraw_out, uint16_t* __restrict__ dh_out,
+    float* __restrict__ dz_out, float* __restrict__ dalpha_part, Strides sin, Strides sout, int H, int N, int Tm, int Tn,
+    int ksel, int alpha_per_block, int total_blocks) {
+  constexpr int NW = BQ / 32, NT = NW * kWave;
+  constexpr int LD = D + 8, KS = D / 16, ET = D / 32;
+  typedef SwizzledLayout<D> SL;
+  typedef PaddedLayout<D> PL;
+  typedef BwdQSmem<D, BQ> SM;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  float* zs = reinterpret_cast<float*>(smem + SM::kZsOff);
+  float* mus = reinterpret_cast<float*>(smem + SM::kMuOff);
+  float* dls = reinterpret_cast<float*>(smem + SM::kDlOff);
+  float* red = reinterpret_cast<float*>(smem + SM::kRedOff);
+  auto kbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + buf * 2 * SM::kTile); };
+  auto vbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + buf * 2 * SM::kTile + SM::kTile); };
+
+  // consecutive query blocks of a head share key/value tiles: keep them on one XCD
+  const int per_xcd = (total_blocks + kXcds - 1) / kXcds;
+  const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  if (logical >= total_blocks) return;
+  const int bh = logical / Tm, i = logical % Tm, h = bh % H;
+  const int tid = threadIdx.x, lane = tid % kWave, g = lane / 32;
+  const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int row0 = i * BQ;
+  const int rows_valid = min(BQ, N - row0);
+  const int qrow = 32 * w + lane % 32;               // this lane's query row inside the block
+  const bool row_ok = qrow < rows_valid;
+  const int r_ld = min(qrow, rows_valid - 1);        // rows past the end repeat the last one; never stored
+  const uint16_t* qh = q + head_offset(sin, bh, H);
+  const uint16_t* kh = k + head_offset(sin, bh, H);
+  const uint16_t* vh = v + head_offset(sin, bh, H);
+  const uint16_t* doh = dout + head_offset(sout, bh, H);
+  const int tok_stride = sin.n;
+  const int32_t* sel = block_idx + ((size_t)bh * Tm + i) * ksel;
+  const int ntiles = ksel;
+  const float al = alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
+  const float rscale = rsqrtf((float)D);
+  const size_t slot = (size_t)bh * Tm + i;
+
+  auto dma = [&](int j, int buf) {
+    const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
+    dma_tile<D, NW>(kh + (size_t)t0 * tok_stride, tok_stride, valid, kbuf(buf), w, lane);
+    dma_tile<D, NW>(vh + (size_t)t0 * tok_stride, tok_stride, valid, vbuf(buf), w, lane);
+  };
+  int j_cur = ntiles > 0 ? sel[0] : 0, j_nxt = ntiles > 1 ? sel[1] : 0;
+  if (ntiles > 0) dma(j_cur, 0);
+  if (tid < D) mus[tid] = (float)k_mean[(size_t)bh * D + tid];
+
+  // ---- prologue: Q and dO^s = alpha dO as B-operand fragments; D^s, D^l, the d alpha part ----
+  bf16x8 qf[KS], dof[KS];
+  float Ds = 0.f, Dl = 0.f, mix = 0.f;
+  {
+    const uint16_t* qsrc = qh + (size_t)(row0 + r_ld) * tok_stride + 8 * g;
+    const uint16_t* gsrc = doh + (size_t)(row0 + r_ld) * sout.n + 8 * g;
+    const uint16_t* ossrc = o_s + ((size_t)bh * N + row0 + r_ld) * D + 8 * g;
+    const uint16_t* olsrc = o_l + ((size_t)bh * N + row0 + r_ld) * D + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      qf[ks] = *reinterpret_cast<const bf16x8*>(qsrc + 16 * ks);
+      const bf16x8 go = *reinterpret_cast<const bf16x8*>(gsrc + 16 * ks);
+      const bf16x8 os = *reinterpret_cast<const bf16x8*>(ossrc + 16 * ks);
+      const bf16x8 ol = *reinterpret_cast<const bf16x8*>(olsrc + 16 * ks);
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        const float gv = (float)go[e], osv = (float)os[e], olv = (float)ol[e];
+        Ds += al * gv * osv;
+        Dl += (1.f - al) * gv * olv;
+        mix += gv * (osv - olv);
+        dof[ks][e] = (__bf16)(al * gv);
+      }
+    }
+  }
+  Ds = half_sum(Ds);
+  Dl = half_sum(Dl);
+  if (!row_ok) mix = 0.f;
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) mix += __shfl_xor(mix, o);
+  if (lane == 0) red[w] = mix;
+  const float L = lse[(size_t)bh * N + row0 + r_ld];
+  __builtin_amdgcn_s_waitcnt(kVmcnt0);               // tile 0 and everything above have landed
+  __syncthreads();                                   // ... for everyone; mus and red are visible
+  if (tid == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int x = 0; x < NW; x++) t += red[x];
+    dalpha_part[slot] = t;
+  }
+  // The forward pass defines L on the smoothed keys; the products below use the raw K, whose scores are
+  // larger by q . colmean(K) / sqrt(d) in every column of a row.
+  float qmu = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) {
+    const f32x4 m0 = *reinterpret_cast<const f32x4*>(mus + 16 * ks + 8 * g);
+    const f32x4 m1 = *reinterpret_cast<const f32x4*>(mus + 16 * ks + 8 * g + 4);
+#pragma unroll
+    for (int e = 0; e < 8; e++) qmu += (float)qf[ks][e] * (e < 4 ? m0[e] : m1[e - 4]);
+  }
+  qmu = half_sum(qmu);
+  const float Lraw = L + qmu * rscale;
+  const float L2 = Lraw * kLog2e;
+  if (g == 0 && row_ok) {
+    ds_out[(size_t)bh * N + row0 + qrow] = Ds;
+    lraw_out[(size_t)bh * N + row0 + qrow] = Lraw;
+  }
+
+  f32x16 dqacc[ET];
+#pragma unroll
+  for (int et = 0; et < ET; et++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) dqacc[et][e] = 0.f;
+  float sumds = 0.f;
+  const float c0 = kLog2e * rscale;
+
+  for (int s = 0; s < ntiles; s++) {
+    const int buf = s & 1;
+    const int valid = min(kTileTokens, N - j_cur * kTileTokens);
+    const int j_nn = sel[min(s + 2, ntiles - 1)];
+    if (s + 1 < ntiles) dma(j_nxt, buf ^ 1);
+    j_cur = j_nxt;
+    j_nxt = j_nn;
+    const uint16_t* kt = kbuf(buf);
+    const uint16_t* vt = vbuf(buf);
+    f32x16 sacc[2], dpacc[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) { sacc[mt][e] = 0.f; dpacc[mt][e] = 0.f; }
+    // S^T = K Q^T and dP^T = V dO^s^T (keys x query rows), two 32-key halves
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int mt = 0; mt < 2; mt++)
+        sacc[mt] = mfma_bf16(row_fragment<SL>(kt, 32 * mt + lane % 32, 16 * ks + 8 * g), qf[ks], sacc[mt]);
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int mt = 0; mt < 2; mt++)
+        dpacc[mt] = mfma_bf16(row_fragment<SL>(vt, 32 * mt + lane % 32, 16 * ks + 8 * g), dof[ks], dpacc[mt]);
+    // dS^T = P^T (.) (dP^T - D^s), as B-operand fragments in token order
+    bf16x8 dsf[4];
+#pragma unroll
+    for (int mt = 0; mt < 2; mt++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        float p = fast_exp2(sacc[mt][e] * c0 - L2);
+        if (32 * mt + 8 * (e / 4) + 4 * g + e % 4 >= valid) p = 0.f;
+        const float dsv = p * (dpacc[mt][e] - Ds);
+        sumds += dsv;
+        dsf[2 * mt + e / 8][e % 8] = (__bf16)dsv;
+      }
+    // dQ^T += K^T dS^T
+#pragma unroll
+    for (int ks = 0; ks < kTileTokens / 16; ks++)
+#pragma unroll
+      for (int et = 0; et < ET; et++) dqacc[et] = mfma_bf16(v_fragment<SL>(kt, ks, 32 * et, lane), dsf[ks], dqacc[et]);
+    __builtin_amdgcn_s_waitcnt(kVmcnt0);             // the next tile has landed in LDS ...
+    __syncthreads();                                 // ... for everyone, and this tile's buffer is free
+  }
+
+  // ================= epilogue =================
+  uint16_t* ta = reinterpret_cast<uint16_t*>(smem);                 // H_i^T [e][c], later w [row][c]
+  uint16_t* tb = reinterpret_cast<uint16_t*>(smem + SM::kEpiA);     // dQ [row][c], later dO^l [row][e]
+  // dS K' = dS K - rowsum(dS) colmean(K)^T
+  sumds = half_sum(sumds);
+#pragma unroll
+  for (int et = 0; et < ET; et++)
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      const f32x4 m = *reinterpret_cast<const f32x4*>(mus + 32 * et + 8 * v4 + 4 * g);
+#pragma unroll
+      for (int r = 0; r < 4; r++) dqacc[et][4 * v4 + r] = (dqacc[et][4 * v4 + r] - sumds * m[r]) * rscale;
+    }
+  {
+    const uint16_t* hsrc = h_i + slot * D * D;
+    for (int idx = tid; idx < D * (D / 8); idx += NT) {
+      const int e = idx / (D / 8), ch = idx % (D / 8);
+      *reinterpret_cast<u32x4*>(ta + e * LD + 8 * ch) = *reinterpret_cast<const u32x4*>(hsrc + e * D + 8 * ch);
+    }
+    if (tid < D) zs[tid] = z_i[slot * D + tid];
+  }
+  // Q^phi = softmax_d(Q) of this lane's row in the layout of the accumulators: channel
+  // 32 et + 8 (v / 4) + 4 g + v % 4 at [et][v]
+  f32x16 qp[ET];
+  {
+    const uint16_t* qsrc = qh + (size_t)(row0 + r_ld) * tok_stride + 4 * g;
+    float qm = -INFINITY;
+#pragma unroll
+    for (int et = 0; et < ET; et++)
+#pragma unroll
+      for (int v4 = 0; v4 < 4; v4++) {
+        const bf16x4 x = *reinterpret_cast<const bf16x4*>(qsrc + 32 * et + 8 * v4);
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          qp[et][4 * v4 + r] = (float)x[r];
+          qm = fmaxf(qm, qp[et][4 * v4 + r]);
+        }
+      }
+    qm = half_max(qm);
+    float qs = 0.f;
+#pragma unroll
+    for (int et = 0; et < ET; et++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) {
+        qp[et][e] = fast_exp2((qp[et][e] - qm) * kLog2e);
+        qs += qp[et][e];
+      }
+    qs = half_sum(qs);
+    const float qinv = 1.f / qs;
+#pragma unroll
+    for (int et = 0; et < ET; et++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) qp[et][e] *= qinv;
+  }
+  __syncthreads();                                   // H_i^T and Z_i visible
+  float den = 0.f;
+#pragma unroll
+  for (int et = 0; et < ET; et++)
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      const f32x4 z = *reinterpret_cast<const f32x4*>(zs + 32 * et + 8 * v4 + 4 * g);
+#pragma unroll
+      for (int r = 0; r < 4; r++) den += qp[et][4 * v4 + r] * z[r];
+    }
+  den = half_sum(den);
+  // every block selected: the linear branch receives and passes no gradient
+  const float inv_den = (ksel >= Tn || !row_ok) ? 0.f : 1.f / den;
+  // dQ^phi^T = H_i dO^l^T: A = H_i read transposed out of the H_i^T tile (contraction index e in token
+  // order), B = dO^l of this lane's row in that same order
+  f32x16 dqp[ET];
+#pragma unroll
+  for (int ct = 0; ct < ET; ct++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) dqp[ct][e] = 0.f;
+  {
+    const uint16_t* gsrc = doh + (size_t)(row0 + r_ld) * sout.n + 4 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      const bf16x4 lo = *reinterpret_cast<const bf16x4*>(gsrc + 16 * ks);
+      const bf16x4 hi = *reinterpret_cast<const bf16x4*>(gsrc + 16 * ks + 8);
+      bf16x8 dol;
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        dol[r] = (__bf16)((1.f - al) * (float)lo[r]);
+        dol[4 + r] = (__bf16)((1.f - al) * (float)hi[r]);
+      }
+#pragma unroll
+      for (int ct = 0; ct < ET; ct++) dqp[ct] = mfma_bf16(v_fragment<PL>(ta, ks, 32 * ct, lane), dol, dqp[ct]);
+    }
+  }
+  float dot = 0.f;
+#pragma unroll
+  for (int ct = 0; ct < ET; ct++)
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      const f32x4 z = *reinterpret_cast<const f32x4*>(zs + 32 * ct + 8 * v4 + 4 * g);
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        dqp[ct][4 * v4 + r] = (dqp[ct][4 * v4 + r] - Dl * z[r]) * inv_den;
+        dot += dqp[ct][4 * v4 + r] * qp[ct][4 * v4 + r];
+      }
+    }
+  dot = half_sum(dot);
+  // dQ = sparse part + softmax-backward(dQ^phi); transposed through LDS for a coalesced store
+#pragma unroll
+  for (int et = 0; et < ET; et++)
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      bf16x4 pk;
+#pragma unroll
+      for (int r = 0; r < 4; r++)
+        pk[r] = (__bf16)(dqacc[et][4 * v4 + r] + qp[et][4 * v4 + r] * (dqp[et][4 * v4 + r] - dot));
+      *reinterpret_cast<bf16x4*>(tb + qrow * LD + 32 * et + 8 * v4 + 4 * g) = pk;
+    }
+  __syncthreads();                                   // dQ tile complete; nobody reads H_i^T any more
+  {
+    uint16_t* dst = dq + head_offset(sin, bh, H) + (size_t)row0 * tok_stride;
+    for (int idx = tid; idx < BQ * (D / 8); idx += NT) {
+      const int r = idx / (D / 8), ch = idx % (D / 8);
+      if (r < rows_valid)
+        *reinterpret_cast<u32x4*>(dst + (size_t)r * tok_stride + 8 * ch) = *reinterpret_cast<const u32x4*>(tb + r * LD + 8 * ch);
+    }
+  }
+  // w = Q^phi / (Q^phi Z_i) as a [row][c] tile (zero rows past the end)
+#pragma unroll
+  for (int et = 0; et < ET; et++)
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      bf16x4 pk;
+#pragma unroll
+      for (int r = 0; r < 4; r++) pk[r] = (__bf16)(qp[et][4 * v4 + r] * inv_den);
+      *reinterpret_cast<bf16x4*>(ta + qrow * LD + 32 * et + 8 * v4 + 4 * g) = pk;
+    }
+  if (g == 0) dls[qrow] = Dl;
+  __syncthreads();                                   // the dQ tile has been read out
+  for (int idx = tid; idx < BQ * (D / 8); idx += NT) {   // dO^l = (1 - alpha) dO as a [row][e] tile
+    const int r = idx / (D / 8), ch = idx % (D / 8);
+    const bf16x8 x = *reinterpret_cast<const bf16x8*>(doh + (size_t)(row0 + min(r, rows_valid - 1)) * sout.n + 8 * ch);
+    bf16x8 y;
+#pragma unroll
+    for (int e = 0; e < 8; e++) y[e] = (__bf16)((1.f - al) * (float)x[e]);
+    *reinterpret_cast<bf16x8*>(tb + r * LD + 8 * ch) = y;
+  }
+  __syncthreads();
+  // dH_i[c][e] = sum_r w[r][c] dO^l[r][e]: both operands read transposed, contraction over the rows
+  constexpr int kTilesPerWave = ET * ET / NW;
+  static_assert(kTilesPerWave >= 1, "unsupported split");
+  uint16_t* dh_slot = dh_out + slot * D * D;
+#pragma unroll 1
+  for (int x = 0; x < kTilesPerWave; x++) {
+    const int t = w * kTilesPerWave + x, ct = t / ET, et = t % ET;
+    f32x16 acc;
+#pragma unroll
+    for (int e = 0; e < 16; e++) acc[e] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < BQ / 16; ks++)
+      acc = mfma_bf16(v_fragment<PL>(ta, ks, 32 * ct, lane), v_fragment<PL>(tb, ks, 32 * et, lane), acc);
+#pragma unroll
+    for (int e = 0; e < 16; e++)
+      dh_slot[(32 * ct + 8 * (e / 4) + 4 * g + e % 4) * D + 32 * et + lane % 32] = f32_to_bf16_bits(acc[e]);
+  }
+  if (tid < D) {                                     // dZ_i[c] = -sum_r w[r][c] D^l_r
+    float dz = 0.f;
+    for (int r = 0; r < BQ; r++) dz -= bf16_bits_to_f32(ta[r * LD + tid]) * dls[r];
+    dz_out[slot * D + tid] = dz;
+  }
+}
+
+template <int D, int BQ>
+static hipError_t launch_bwd_q_mfma(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  constexpr int smem = BwdQSmem<D, BQ>::kBytes;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)bwd_q_mfma_kernel<D, BQ>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int total = s.BH * s.Tm;
+  const int grid = ((total + kXcds - 1) / kXcds) * kXcds;
+  bwd_q_mfma_kernel<D, BQ><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(
+      (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.dout, (const uint16_t*)a.o_s,
+      (const uint16_t*)a.o_l, a.lse, a.k_mean, a.h_i, a.z_i, a.block_idx, a.alpha, (uint16_t*)a.dq, a.ds, a.lraw,
+      (uint16_t*)a.dh, a.dz, a.dalpha_part, s.sin, s.sout, s.H, s.N, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0, total);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+template <int D> struct BwdKvSmem {
+  static constexpr int kLd = D + 8;
+  static constexpr int kTile = SwizzledLayout<D>::kTileBytes;                  // one 64 x D bf16 tile
+  static constexpr int kKOff = 0, kVOff = kTile;                               // K_j, V_j (K_j becomes K^phi_j at the end)
+  static constexpr int kStepOff = 2 * kTile;                                   // two buffers of (Q rows, dO rows);
+  static constexpr int kStepBytes = 4 * kTile;                                 // after the loop: dH, then the output tiles
+  static constexpr int kPOff = kStepOff + kStepBytes;                          // alpha P [64 rows][64 keys] bf16
+  static constexpr int kDsOff = kPOff + SwizzledLayout<64>::kTileBytes;        // dS, same shape
+  static constexpr int kMuOff = kDsOff + SwizzledLayout<64>::kTileBytes;       // float [D]  colmean(K)
+  static constexpr int kDzOff = kMuOff + D * 4;                                // float [D]  dZ of this key block
+  static constexpr int kDotOff = kDzOff + D * 4;                               // float [D / 32][64]
+  static constexpr int kBytes = kDotOff + (D / 32) * 64 * 4;
+  static_assert(D * kLd * 2 <= kStepBytes && 2 * 64 * kLd * 2 <= kStepBytes, "epilogue tiles reuse the step buffers");
+};
+
+template <int D, int BQ>
+__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_kv_mfma_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const uint16_t* __restrict__ dout, const float* __restrict__ lraw, const float* __restrict__ ds_in,
+    const double* __restrict__ k_mean, const float* __restrict__ k_stats, const int32_t* __restrict__ col_ptr,
+    const int32_t* __restrict__ col_idx, const uint16_t* __restrict__ dh_in, const float* __restrict__ dz_in,
+    const float* __restrict__ dh_total, const float* __restrict__ dz_total, const float* __restrict__ alpha,
+    uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, float* __restrict__ colsum, Strides sin, Strides sout, int H,
+    int N, int Tm, int Tn, int ksel, int alpha_per_block, int total_blocks) {
+  constexpr int NW = 4, NT = 256;
+  constexpr int LD = D + 8, KS = D / 16, ET = D / 32;
+  constexpr int HP = BQ / 64;                        // 64-row steps per query block
+  constexpr int TPW = 2 * ET / NW;                   // 32 x 32 tiles of dV^T / dK^T (channels x keys) per wave
+  static_assert(TPW == 1 || TPW == 2, "unsupported split");
+  typedef SwizzledLayout<D> SL;
+  typedef SwizzledLayout<64> SP;
+  typedef PaddedLayout<D> PL;
+  typedef BwdKvSmem<D> SM;
+  extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
+  uint16_t* ktile = reinterpret_cast<uint16_t*>(smem + SM::kKOff);
+  uint16_t* vtile = reinterpret_cast<uint16_t*>(smem + SM::kVOff);
+  auto qbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + SM::kStepOff + buf * 2 * SM::kTile); };
+  auto gbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + SM::kStepOff + buf * 2 * SM::kTile + SM::kTile); };
+  uint16_t* ptile = reinterpret_cast<uint16_t*>(smem + SM::kPOff);
+  uint16_t* dstile = reinterpret_cast<uint16_t*>(smem + SM::kDsOff);
+  float* mus = reinterpret_cast<float*>(smem + SM::kMuOff);
+  float* dzs = reinterpret_cast<float*>(smem + SM::kDzOff);
+  float* dred = reinterpret_cast<float*>(smem + SM::kDotOff);
+
+  // consecutive key blocks of a head were selected by overlapping sets of query blocks: one XCD
+  const int per_xcd = (total_blocks + kXcds - 1) / kXcds;
+  const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+  if (logical >= total_blocks) return;
+  const int bh = logical / Tn, j = logical % Tn, h = bh % H;
+  const int tid = threadIdx.x, lane = tid % kWave, g = lane / 32;
+  const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
+  const int rw = w & 1, kw = w >> 1;                 // scores: query rows 32 rw.., keys 32 kw..
+  const int ct = TPW == 2 ? w : w >> 1;              // accumulators: channels 32 ct.., keys 32 kh(x)..
+  auto kh_of = [&](int x) { return TPW == 2 ? x : (w & 1); };
+  const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
+  const uint16_t* qh = q + head_offset(sin, bh, H);
+  const uint16_t* kh = k + head_offset(sin, bh, H);
+  const uint16_t* vh = v + head_offset(sin, bh, H);
+  const uint16_t* doh = dout + head_offset(sout, bh, H);
+  const int tok_stride = sin.n;
+  const float rscale = rsqrtf((float)D);
+  const float c0 = kLog2e * rscale;
+
+  dma_tile<D, NW>(kh + (size_t)t0 * tok_stride, tok_stride, valid, ktile, w, lane);
+  dma_tile<D, NW>(vh + (size_t)t0 * tok_stride, tok_stride, valid, vtile, w, lane);
+  if (tid < D) mus[tid] = (float)k_mean[(size_t)bh * D + tid];
+
+  const int32_t* cp = col_ptr + (size_t)bh * (Tn + 1);
+  const int32_t* ci = col_idx + (size_t)bh * Tm * ksel;
+  const int l0 = cp[j], l1 = cp[j + 1];
+  const int nsteps = (l1 - l0) * HP;
+  const int myrow = 32 * rw + lane % 32;             // this lane's query row inside a step
+
+  // Step t covers rows [64 (t % HP), +64) of query block ci[l0 + t / HP].  A half block with no rows
+  // (short last query block) still runs, on the block's first rows with every probability masked.
+  struct Step { int src0, rows; float al, L2, Ds; };
+  auto fetch = [&](int t, int buf) {
+    Step st;
+    const int i = ci[l0 + t / HP];
+    const int row0 = i * BQ + 64 * (t % HP);
+    st.rows = max(0, min(64, N - row0));
+    st.src0 = st.rows > 0 ? row0 : i * BQ;
+    const int dma_rows = max(st.rows, 1);
+    dma_tile<D, NW>(qh + (size_t)st.src0 * tok_stride, tok_stride, dma_rows, qbuf(buf), w, lane);
+    dma_tile<D, NW>(doh + (size_t)st.src0 * sout.n, sout.n, dma_rows, gbuf(buf), w, lane);
+    st.al = alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
+    const size_t at = (size_t)bh * N + st.src0 + min(myrow, dma_rows - 1);
+    st.L2 = lraw[at] * kLog2e;
+    st.Ds = ds_in[at];
+    return st;
+  };
+
+  f32x16 dvacc[TPW], dkacc[TPW];
+#pragma unroll
+  for (int x = 0; x < TPW; x++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) { dvacc[x][e] = 0.f; dkacc[x][e] = 0.f; }
+
+  Step cur{0, 0, 0.f, 0.f, 0.f};
+  if (nsteps > 0) cur = fetch(0, 0);
+  __builtin_amdgcn_s_waitcnt(kVmcnt0);
+  __syncthreads();                                   // K_j, V_j, step 0 and mus are in LDS for everyone
+
+  for (int t = 0; t < nsteps; t++) {
+    const int buf = t & 1;
+    Step nxt = cur;
+    if (t + 1 < nsteps) nxt = fetch(t + 1, buf ^ 1);
+    const uint16_t* qt = qbuf(buf);
+    const uint16_t* gt = gbuf(buf);
+    const bool row_ok = myrow < cur.rows;
+    // S^T = K Q^T and dP^T = V dO^T on keys 32 kw.., query rows 32 rw..
+    f32x16 sacc, dpacc;
+#pragma unroll
+    for (int e = 0; e < 16; e++) { sacc[e] = 0.f; dpacc[e] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+      sacc = mfma_bf16(row_fragment<SL>(ktile, 32 * kw + lane % 32, 16 * ks + 8 * g),
+                       row_fragment<SL>(qt, myrow, 16 * ks + 8 * g), sacc);
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++)
+      dpacc = mfma_bf16(row_fragment<SL>(vtile, 32 * kw + lane % 32, 16 * ks + 8 * g),
+                        row_fragment<SL>(gt, myrow, 16 * ks + 8 * g), dpacc);
+    // alpha P and dS = P (.) (alpha dP - D^s) as [row][key] tiles
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      bf16x4 pa, dsv;
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        float p = fast_exp2(sacc[4 * v4 + r] * c0 - cur.L2);
+        if (!row_ok || 32 * kw + 8 * v4 + 4 * g + r >= valid) p = 0.f;
+        pa[r] = (__bf16)(cur.al * p);
+        dsv[r] = (__bf16)(p * (cur.al * dpacc[4 * v4 + r] - cur.Ds));
+      }
+      const int off = SP::offset(myrow, 32 * kw + 8 * v4 + 4 * g);
+      *reinterpret_cast<bf16x4*>(ptile + off) = pa;
+      *reinterpret_cast<bf16x4*>(dstile + off) = dsv;
+    }
+    __syncthreads();
+    // dV^T += dO^T (alpha P), dK'^T += Q^T dS: contraction over the 64 rows of the step
+#pragma unroll
+    for (int ks = 0; ks < 4; ks++) {
+      const bf16x8 ag = v_fragment<SL>(gt, ks, 32 * ct, lane);
+      const bf16x8 aq = v_fragment<SL>(qt, ks, 32 * ct, lane);
+#pragma unroll
+      for (int x = 0; x < TPW; x++) {
+        dvacc[x] = mfma_bf16(ag, v_fragment<SP>(ptile, ks, 32 * kh_of(x), lane), dvacc[x]);
+        dkacc[x] = mfma_bf16(aq, v_fragment<SP>(dstile, ks, 32 * kh_of(x), lane), dkacc[x]);
+      }
+    }
+    cur = nxt;
+    __builtin_amdgcn_s_waitcnt(kVmcnt0);             // the next step's rows have landed ...
+    __syncthreads();                                 // ... for everyone; this step's tiles are free
+  }
+
+  // ================= linear branch =================
+  uint16_t* dht = reinterpret_cast<uint16_t*>(smem + SM::kStepOff);      // dH [c][e] as bf16, row stride LD
+  const bool all_selected = ksel >= Tn;
+  {
+    // dH = dH_total - sum over the query blocks that selected j of dH_i (Alg. 3's M_c[i, j] = 0 sum)
+    constexpr int NCH = D * D / 8 / NT;              // 16-byte chunks per thread
+    float acc[NCH][8];
+#pragma unroll
+    for (int n = 0; n < NCH; n++) {
+      const int idx = tid + NT * n;
+      const float* tot = dh_total + (size_t)bh * D * D + (size_t)idx * 8;
+      const f32x4 a = *reinterpret_cast<const f32x4*>(tot), b = *reinterpret_cast<const f32x4*>(tot + 4);
+#pragma unroll
+      for (int e = 0; e < 4; e++) { acc[n][e] = all_selected ? 0.f : a[e]; acc[n][4 + e] = all_selected ? 0.f : b[e]; }
+    }
+    float dzj = (tid < D && !all_selected) ? dz_total[(size_t)bh * D + tid] : 0.f;
+    if (!all_selected)
+      for (int l = l0; l < l1; l++) {
+        const size_t slot = (size_t)bh * Tm + ci[l];
+        const uint16_t* src = dh_in + slot * D * D;
+#pragma unroll
+        for (int n = 0; n < NCH; n++) {
+          const bf16x8 x = *reinterpret_cast<const bf16x8*>(src + (size_t)(tid + NT * n) * 8);
+#pragma unroll
+          for (int e = 0; e < 8; e++) acc[n][e] -= (float)x[e];
+        }
+        if (tid < D) dzj -= dz_in[slot * D + tid];
+      }
+#pragma unroll
+    for (int n = 0; n < NCH; n++) {
+      const int idx = tid + NT * n, c = idx / (D / 8), ch = idx % (D / 8);
+      bf16x8 y;
+#pragma unroll
+      for (int e = 0; e < 8; e++) y[e] = (__bf16)acc[n][e];
+      *reinterpret_cast<bf16x8*>(dht + c * LD + 8 * ch) = y;
+    }
+    if (tid < D) dzs[tid] = dzj;
+  }
+  // K_j -> K^phi_j = exp(K - colmean(K) - lnZ) in place (rows past the end: 0)
+  for (int idx = tid; idx < kTileTokens * (D / 8); idx += NT) {
+    const int t = idx / (D / 8), pc = idx % (D / 8);
+    const int c = 8 * (pc ^ SL::swz(t));             // the channels held by physical chunk pc of row t
+    const float lnz = k_stats[(size_t)bh * N + t0 + min(t, valid - 1)];
+    bf16x8 x = *reinterpret_cast<const bf16x8*>(ktile + t * D + 8 * pc);
+#pragma unroll
+    for (int e = 0; e < 8; e++) {
+      const float kp = t < valid ? fast_exp2(((float)x[e] - mus[c + e] - lnz) * kLog2e) : 0.f;
+      x[e] = (__bf16)kp;
+    }
+    *reinterpret_cast<bf16x8*>(ktile + t * D + 8 * pc) = x;
+  }
+  __syncthreads();
+  // dK^phi^T = dH V^T (+ dZ 1^T below) and dV^T += dH^T K^phi^T, both channels x keys
+  f32x16 dkp[TPW];
+#pragma unroll
+  for (int x = 0; x < TPW; x++)
+#pragma unroll
+    for (int e = 0; e < 16; e++) dkp[x][e] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) {
+    const bf16x8 ah = row_fragment<PL>(dht, 32 * ct + lane % 32, 16 * ks + 8 * g);   // dH[c][e..]: contraction over e
+    const bf16x8 aht = v_fragment<PL>(dht, ks, 32 * ct, lane);                       // dH^T[e][c..], c in token order
+#pragma unroll
+    for (int x = 0; x < TPW; x++) {
+      const int key = 32 * kh_of(x) + lane % 32;
+      dkp[x] = mfma_bf16(ah, row_fragment<SL>(vtile, key, 16 * ks + 8 * g), dkp[x]);
+      const bf16x4 lo = *reinterpret_cast<const bf16x4*>(ktile + SL::offset(key, 16 * ks + 4 * g));
+      const bf16x4 hi = *reinterpret_cast<const bf16x4*>(ktile + SL::offset(key, 16 * ks + 8 + 4 * g));
+      const bf16x8 bk = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      dvacc[x] = mfma_bf16(aht, bk, dvacc[x]);
+    }
+  }
+  // back through phi: dK' += K^phi (.) (dK^phi - rowsum(dK^phi (.) K^phi)); the row sum spans all channels
+  float kp[TPW][16];
+#pragma unroll
+  for (int x = 0; x < TPW; x++) {
+    const int key = 32 * kh_of(x) + lane % 32;
+    float part = 0.f;
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      const bf16x4 kk = *reinterpret_cast<const bf16x4*>(ktile + SL::offset(key, 32 * ct + 8 * v4 + 4 * g));
+      const f32x4 dz = *reinterpret_cast<const f32x4*>(dzs + 32 * ct + 8 * v4 + 4 * g);
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        kp[x][4 * v4 + r] = (float)kk[r];
+        dkp[x][4 * v4 + r] += dz[r];
+        part += dkp[x][4 * v4 + r] * kp[x][4 * v4 + r];
+      }
+    }
+    part = half_sum(part);
+    if (g == 0) dred[ct * 64 + key] = part;
+  }
+  __syncthreads();                                   // row sums complete; every wave is done with the dH and K^phi tiles
+  uint16_t* okt = dht;                               // dK' [key][c], then dV [key][e] behind it
+  uint16_t* ovt = dht + 64 * LD;
+#pragma unroll
+  for (int x = 0; x < TPW; x++) {
+    const int key = 32 * kh_of(x) + lane % 32;
+    float dot = 0.f;
+#pragma unroll
+    for (int c2 = 0; c2 < ET; c2++) dot += dred[c2 * 64 + key];
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      bf16x4 pk, pv;
+#pragma unroll
+      for (int r = 0; r < 4; r++) {
+        pk[r] = (__bf16)(dkacc[x][4 * v4 + r] * rscale + kp[x][4 * v4 + r] * (dkp[x][4 * v4 + r] - dot));
+        pv[r] = (__bf16)dvacc[x][4 * v4 + r];
+      }
+      *reinterpret_cast<bf16x4*>(okt + key * LD + 32 * ct + 8 * v4 + 4 * g) = pk;
+      *reinterpret_cast<bf16x4*>(ovt + key * LD + 32 * ct + 8 * v4 + 4 * g) = pv;
+    }
+  }
+  __syncthreads();
+  {
+    uint16_t* dkh = dk + head_offset(sin, bh, H) + (size_t)t0 * tok_stride;
+    uint16_t* dvh = dv + head_offset(sin, bh, H) + (size_t)t0 * tok_stride;
+    for (int idx = tid; idx < kTileTokens * (D / 8); idx += NT) {
+      const int t = idx / (D / 8), ch = idx % (D / 8);
+      if (t < valid) {
+        *reinterpret_cast<u32x4*>(dkh + (size_t)t * tok_stride + 8 * ch) = *reinterpret_cast<const u32x4*>(okt + t * LD + 8 * ch);
+        *reinterpret_cast<u32x4*>(dvh + (size_t)t * tok_stride + 8 * ch) = *reinterpret_cast<const u32x4*>(ovt + t * LD + 8 * ch);
+      }
+    }
+    if (tid < D) {                                   // column sums of dK' (as stored) for the smoothing term
+      float sum = 0.f;
+      for (int t = 0; t < valid; t++) sum += bf16_bits_to_f32(okt[t * LD + tid]);
+      colsum[((size_t)bh * Tn + j) * D + tid] = sum;
+    }
+  }
+}
+
+template <int D, int BQ>
+static hipError_t launch_bwd_kv_mfma(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  constexpr int smem = BwdKvSmem<D>::kBytes;
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)bwd_kv_mfma_kernel<D, BQ>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+    if (e != hipSuccess) return e;
+    configured = true;
+  }
+  const int total = s.BH * s.Tn;
+  const int grid = ((total + kXcds - 1) / kXcds) * kXcds;
+  bwd_kv_mfma_kernel<D, BQ><<<dim3((unsigned)grid), 256, smem, stream>>>(
+      (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.dout, a.lraw, a.ds, a.k_mean,
+      a.k_stats, a.col_ptr, a.col_idx, (const uint16_t*)a.dh, a.dz, a.dh_total, a.dz_total, a.alpha, (uint16_t*)a.dk,
+      (uint16_t*)a.dv, a.colsum, s.sin, s.sout, s.H, s.N, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0, total);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_kv_bf16(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  if (s.d == 128 && s.bq == 128) return launch_bwd_kv_mfma<128, 128>(s, a, stream);
+  if (s.d == 128 && s.bq == 64) return launch_bwd_kv_mfma<128, 64>(s, a, stream);
+  if (s.d == 64 && s.bq == 128) return launch_bwd_kv_mfma<64, 128>(s, a, stream);
+  return launch_bwd_kv_mfma<64, 64>(s, a, stream);
+}
+
+hipError_t launch_bwd_q_bf16(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  if (s.d == 128 && s.bq == 128) return launch_bwd_q_mfma<128, 128>(s, a, stream);
+  if (s.d == 128 && s.bq == 64) return launch_bwd_q_mfma<128, 64>(s, a, stream);
+  if (s.d == 64 && s.bq == 128) return launch_bwd_q_mfma<64, 128>(s, a, stream);
+  return launch_bwd_q_mfma<64, 64>(s, a, stream);
+}
+
+}  // namespace sla2

@@ -24,14 +24,6 @@
 
 namespace sla2 {
 
-// lanes l and l ^ 32 combine their values; both get the same bits
-__device__ __forceinline__ float half_sum(float x) { return x + __shfl_xor(x, 32); }
-__device__ __forceinline__ float half_max(float x) { return fmaxf(x, __shfl_xor(x, 32)); }
-
-__device__ __forceinline__ f32x16 mfma_bf16(bf16x8 a, bf16x8 b, f32x16 c) {
-  return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-
 // four values already scaled into [-127, 127] -> their nearest integers (ties to even), one per byte
 __device__ __forceinline__ int pack_int8(float a, float b, float c, float d) {
   const int ia = (int)__builtin_rintf(a), ib = (int)__builtin_rintf(b), ic = (int)__builtin_rintf(c), id = (int)__builtin_rintf(d);
@@ -304,7 +296,6 @@ hipError_t launch_kv_state_bf16(const Shape& s, const uint16_t* k, const uint16_
 // =============================================================================================
 // attn_mfma
 // =============================================================================================
-constexpr int kXcds = 8;
 enum AttnMode { kSparseBf16 = 0, kSparseFp8 = 1, kDenseBf16 = 2, kSparseInt8 = 3, kSparseFp8V = 4 };
 
 
@@ -326,7 +317,6 @@ template <int D, int BQ, bool FP8, bool VQ = false> struct AttnSmem {
   static constexpr int kBytes = kRedOff + 16;
 };
 
-constexpr int kVmcnt0 = 0x0F70;   // s_waitcnt vmcnt(0), other counters untouched
 
 // A global load the compiler does not track: no wait is generated for it, the caller waits with
 // wait_vmcnt<>() and then passes every loaded value through settle() before using it.
@@ -424,7 +414,8 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     const float* __restrict__ v_scale, const float* __restrict__ h_total,
     const float* __restrict__ z_total, const int32_t* __restrict__ block_idx, const float* __restrict__ alpha,
     uint16_t* __restrict__ out, float* __restrict__ lse, uint16_t* __restrict__ o_s_save,
-    uint16_t* __restrict__ o_l_save, float* __restrict__ lse_save, Strides sin, Strides sout, int H, int N, int Tm,
+    uint16_t* __restrict__ o_l_save, float* __restrict__ lse_save, uint16_t* __restrict__ h_save,
+    float* __restrict__ z_save, Strides sin, Strides sout, int H, int N, int Tm,
     int Tn, int ksel, int alpha_per_block, int total_blocks) {
   // FP8 below means "8-bit codes of Q and K": everything the two low-bit modes share.  INT8 marks the
   // places where the integer mode differs (the quantiser of Q and the Q K^T product).
@@ -985,6 +976,17 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     const int r = idx / (D / 8), ch = idx % (D / 8);
     if (r < rows_valid) *reinterpret_cast<u32x4*>(oh + (size_t)r * sout.n + 8 * ch) = *reinterpret_cast<const u32x4*>(os + r * LD + 8 * ch);
   }
+  if constexpr (!DENSE) {
+    if (h_save != nullptr) {
+      // H_i^T (bf16 [e][c], as the product above consumed it) and Z_i, kept for the backward pass
+      uint16_t* dst = h_save + ((size_t)bh * Tm + i) * D * D;
+      for (int idx = tid; idx < D * (D / 8); idx += NT) {
+        const int e = idx / (D / 8), ch = idx % (D / 8);
+        *reinterpret_cast<u32x4*>(dst + e * D + 8 * ch) = *reinterpret_cast<const u32x4*>(ht + e * LD + 8 * ch);
+      }
+      if (tid < D) z_save[((size_t)bh * Tm + i) * D + tid] = zs[tid];
+    }
+  }
   if (o_s_save != nullptr) {
     // the two branches on their own ([BH, N, d] contiguous), kept for the backward pass: same route
     // through the transposing tile as the mixed output
@@ -1048,7 +1050,7 @@ static hipError_t launch_attn_t(const Shape& s, const AttnArgs& a, hipStream_t s
   attn_mfma_kernel<D, BQ, MODE><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(
       a.q, a.k, a.v, a.k_mean, a.k_phi, a.z_blocks, a.k_fp8, a.k_scale, a.v_codes, a.v_scale, a.h_total, a.z_total,
       a.block_idx, a.alpha,
-      a.out, a.lse, (uint16_t*)a.sv.o_s, (uint16_t*)a.sv.o_l, a.sv.lse, s.sin, s.sout, s.H, s.N, Tm, s.Tn, s.k,
+      a.out, a.lse, (uint16_t*)a.sv.o_s, (uint16_t*)a.sv.o_l, a.sv.lse, a.sv.h_i, a.sv.z_i, s.sin, s.sout, s.H, s.N, Tm, s.Tn, s.k,
       s.alpha_per_block ? 1 : 0, total);
   return hipGetLastError();
 }
@@ -1075,7 +1077,7 @@ hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k
 hipError_t launch_dense_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
                              hipStream_t stream) {
   AttnArgs a{q, k, v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, out, nullptr,
-             SavedForBackward{nullptr, nullptr, nullptr}};
+             SavedForBackward{nullptr, nullptr, nullptr, nullptr, nullptr}};
   if (s.d == 128) return launch_attn_t<128, 128, kDenseBf16>(s, a, stream);
   return launch_attn_t<64, 128, kDenseBf16>(s, a, stream);
 }
