@@ -94,6 +94,7 @@ struct BwdArgs {
   float *ds, *lraw, *dz, *dh_total, *dz_total, *colsum, *dk_mean, *dalpha_part;
   void* dh;
   int32_t *col_ptr, *col_idx;
+  uint32_t* mask_bits;                       // M_c as bits, [BH, T_m, ceil(T_n / 32)]
 };
 hipError_t launch_backward(const Shape& s, const BwdArgs& a, hipStream_t stream);
 hipError_t launch_bwd_q_bf16(const Shape& s, const BwdArgs& a, hipStream_t stream);   // matrix-core kernels, bf16 tensors

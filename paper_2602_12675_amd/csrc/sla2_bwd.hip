@@ -23,43 +23,77 @@ constexpr int kBwdRows = 64;      // query rows per workgroup / per step
 constexpr int kBwdBK = 64;        // key/value block (b_kv)
 
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void bwd_transpose_kernel(const int32_t* __restrict__ block_idx,
-                                                            int32_t* __restrict__ col_ptr,
-                                                            int32_t* __restrict__ col_idx, int Tm, int Tn, int ksel) {
+// M_c as bits: row (bh, i) -> ceil(T_n / 32) words, bit j % 32 of word j / 32 set iff block j is selected
+__global__ __launch_bounds__(64) void bwd_mask_bits_kernel(const int32_t* __restrict__ block_idx,
+                                                           uint32_t* __restrict__ bits, int Tn, int ksel) {
+  __shared__ uint32_t words[kMaxKeyBlocks / 32];
+  const int W = (Tn + 31) / 32, tid = threadIdx.x;
+  for (int x = tid; x < W; x += 64) words[x] = 0u;
+  __syncthreads();
+  const int32_t* row = block_idx + (size_t)blockIdx.x * ksel;
+  for (int s = tid; s < ksel; s += 64) {
+    const int j = row[s];
+    atomicOr(&words[j >> 5], 1u << (j & 31));         // OR: the result does not depend on the order
+  }
+  __syncthreads();
+  for (int x = tid; x < W; x += 64) bits[(size_t)blockIdx.x * W + x] = words[x];
+}
+
+// For every key block j of head bh: the ascending list of query blocks i with M_c[i, j] = 1, as
+// offsets col_ptr[bh][0..T_n] into col_idx[bh][.].  One workgroup per head, one thread per column
+// (two passes over the bit rows, whose words are shared by 32 neighbouring threads).
+constexpr int kTransposeThreads = 1024;
+__global__ __launch_bounds__(kTransposeThreads) void bwd_transpose_kernel(const uint32_t* __restrict__ bits,
+                                                                          int32_t* __restrict__ col_ptr,
+                                                                          int32_t* __restrict__ col_idx, int Tm, int Tn,
+                                                                          int ksel) {
+  constexpr int CPT = kMaxKeyBlocks / kTransposeThreads;   // columns per thread
   __shared__ int cnt[kMaxKeyBlocks + 1];
   const int bh = blockIdx.x, tid = threadIdx.x;
-  const int32_t* sel = block_idx + (size_t)bh * Tm * ksel;
-  auto selected = [&](int i, int j) {                 // is j in the ascending list of row i
-    const int32_t* row = sel + (size_t)i * ksel;
-    int lo = 0, hi = ksel;
-    while (lo < hi) {
-      const int mid = (lo + hi) >> 1;
-      if (row[mid] < j) lo = mid + 1;
-      else hi = mid;
+  const int W = (Tn + 31) / 32;
+  const uint32_t* rows = bits + (size_t)bh * Tm * W;
+  int c[CPT];
+#pragma unroll
+  for (int x = 0; x < CPT; x++) c[x] = 0;
+#pragma unroll 8
+  for (int i = 0; i < Tm; i++) {
+#pragma unroll
+    for (int x = 0; x < CPT; x++) {
+      const int j = tid + kTransposeThreads * x;
+      if (j < Tn) c[x] += (rows[(size_t)i * W + (j >> 5)] >> (j & 31)) & 1u;
     }
-    return lo < ksel && row[lo] == j;
-  };
-  for (int j = tid; j < Tn; j += 256) {
-    int c = 0;
-    for (int i = 0; i < Tm; i++) c += selected(i, j) ? 1 : 0;
-    cnt[j] = c;
+  }
+#pragma unroll
+  for (int x = 0; x < CPT; x++) {
+    const int j = tid + kTransposeThreads * x;
+    if (j < Tn) cnt[j] = c[x];
   }
   __syncthreads();
   if (tid == 0) {                                     // exclusive scan, in place
     int run = 0;
     for (int j = 0; j < Tn; j++) {
-      const int c = cnt[j];
+      const int v = cnt[j];
       cnt[j] = run;
-      run += c;
+      run += v;
     }
     cnt[Tn] = run;
   }
   __syncthreads();
-  for (int j = tid; j <= Tn; j += 256) col_ptr[(size_t)bh * (Tn + 1) + j] = cnt[j];
-  for (int j = tid; j < Tn; j += 256) {
-    int pos = cnt[j];
-    for (int i = 0; i < Tm; i++)
-      if (selected(i, j)) col_idx[(size_t)bh * Tm * ksel + pos++] = i;
+  for (int j = tid; j <= Tn; j += kTransposeThreads) col_ptr[(size_t)bh * (Tn + 1) + j] = cnt[j];
+  int pos[CPT];
+#pragma unroll
+  for (int x = 0; x < CPT; x++) {
+    const int j = tid + kTransposeThreads * x;
+    pos[x] = j < Tn ? cnt[j] : 0;
+  }
+  int32_t* out = col_idx + (size_t)bh * Tm * ksel;
+#pragma unroll 8
+  for (int i = 0; i < Tm; i++) {
+#pragma unroll
+    for (int x = 0; x < CPT; x++) {
+      const int j = tid + kTransposeThreads * x;
+      if (j < Tn && ((rows[(size_t)i * W + (j >> 5)] >> (j & 31)) & 1u)) out[pos[x]++] = i;
+    }
   }
 }
 
@@ -358,17 +392,45 @@ __global__ __launch_bounds__(256) void bwd_q_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// dst[bh][e] = sum over b < count of src[bh][b][e]   (ascending b)
+// dst[bh][e] = sum over b < count of src[bh][b][e].  A workgroup covers 256 consecutive e: 32 threads
+// of 8 elements each, times 8 interleaved subsets of b that are combined in a fixed order.
 template <typename S>
 __global__ __launch_bounds__(256) void bwd_sum_kernel(const S* __restrict__ src, float* __restrict__ dst, int count,
                                                       int len) {
-  const int bh = blockIdx.y;
-  const int e = blockIdx.x * 256 + threadIdx.x;
-  if (e >= len) return;
-  const S* p = src + (size_t)bh * count * len + e;
-  float s = 0.f;
-  for (int b = 0; b < count; b++) s += load_elem(p, (size_t)b * len);
-  dst[(size_t)bh * len + e] = s;
+  __shared__ float part[8][256];
+  const int bh = blockIdx.y, tid = threadIdx.x, col = tid % 32, sub = tid / 32;
+  const int e0 = blockIdx.x * 256 + 8 * col;
+  float acc[8];
+#pragma unroll
+  for (int x = 0; x < 8; x++) acc[x] = 0.f;
+  if (e0 < len) {
+    const S* p = src + (size_t)bh * count * len + e0;
+#pragma unroll 4
+    for (int b = sub; b < count; b += 8) {
+      float v[8];
+      if constexpr (sizeof(S) == 2) {
+        const bf16x8 x = *reinterpret_cast<const bf16x8*>(p + (size_t)b * len);
+#pragma unroll
+        for (int y = 0; y < 8; y++) v[y] = (float)x[y];
+      } else {
+        const f32x4 x0 = *reinterpret_cast<const f32x4*>(p + (size_t)b * len), x1 = *reinterpret_cast<const f32x4*>(p + (size_t)b * len + 4);
+#pragma unroll
+        for (int y = 0; y < 4; y++) { v[y] = x0[y]; v[4 + y] = x1[y]; }
+      }
+#pragma unroll
+      for (int y = 0; y < 8; y++) acc[y] += v[y];
+    }
+  }
+#pragma unroll
+  for (int x = 0; x < 8; x++) part[sub][8 * col + x] = acc[x];
+  __syncthreads();
+  const int e = blockIdx.x * 256 + tid;
+  if (e < len) {
+    float t = 0.f;
+#pragma unroll
+    for (int g = 0; g < 8; g++) t += part[g][tid];
+    dst[(size_t)bh * len + e] = t;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -615,27 +677,42 @@ __global__ __launch_bounds__(256) void bwd_kv_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// mean[bh][c] = sum_j colsum[bh][j][c] / N  (ascending j)
-__global__ __launch_bounds__(128) void bwd_colmean_kernel(const float* __restrict__ colsum, float* __restrict__ mean,
-                                                          int Tn, int N, int d) {
-  const int bh = blockIdx.x, c = threadIdx.x;
-  if (c >= d) return;
+// mean[bh][c] = sum_j colsum[bh][j][c] / N: 1024 / d interleaved subsets of j, combined in a fixed order
+__global__ __launch_bounds__(1024) void bwd_colmean_kernel(const float* __restrict__ colsum, float* __restrict__ mean,
+                                                           int Tn, int N, int d) {
+  __shared__ float part[1024];
+  const int bh = blockIdx.x, tid = threadIdx.x, c = tid % d, sub = tid / d, subs = 1024 / d;
   float s = 0.f;
-  for (int j = 0; j < Tn; j++) s += colsum[((size_t)bh * Tn + j) * d + c];
-  mean[(size_t)bh * d + c] = s / (float)N;
+#pragma unroll 4
+  for (int j = sub; j < Tn; j += subs) s += colsum[((size_t)bh * Tn + j) * d + c];
+  part[tid] = s;
+  __syncthreads();
+  if (tid < d) {
+    float t = 0.f;
+    for (int g = 0; g < subs; g++) t += part[g * d + tid];
+    mean[(size_t)bh * d + tid] = t / (float)N;
+  }
 }
 
-// dK = dK' - colmean(dK'): the gradient of K' = K - colmean(K)
+// dK = dK' - colmean(dK'): the gradient of K' = K - colmean(K); 8 elements (of one row) per thread
 template <typename T>
 __global__ __launch_bounds__(256) void bwd_unsmooth_kernel(T* __restrict__ dk, const float* __restrict__ mean, Strides sin,
                                                            int H, int N, int d) {
   const int bh = blockIdx.y;
-  const size_t e = (size_t)blockIdx.x * 256 + threadIdx.x;
+  const size_t e = ((size_t)blockIdx.x * 256 + threadIdx.x) * 8;
   if (e >= (size_t)N * d) return;
   const int t = (int)(e / d), c = (int)(e % d);
-  T* p = dk + head_offset(sin, bh, H);
-  const size_t at = (size_t)t * sin.n + c;
-  store_elem(p, at, load_elem(p, at) - mean[(size_t)bh * d + c]);
+  T* p = dk + head_offset(sin, bh, H) + (size_t)t * sin.n + c;
+  const float* m = mean + (size_t)bh * d + c;
+  if constexpr (sizeof(T) == 2) {
+    bf16x8 x = *reinterpret_cast<const bf16x8*>(p);
+#pragma unroll
+    for (int y = 0; y < 8; y++) x[y] = (__bf16)((float)x[y] - m[y]);
+    *reinterpret_cast<bf16x8*>(p) = x;
+  } else {
+#pragma unroll
+    for (int y = 0; y < 8; y++) p[y] -= m[y];
+  }
 }
 
 // d alpha: per head [H] (sum over batch, query blocks and parts) or per query block [H, T_m] (batch and parts)
@@ -674,7 +751,8 @@ static hipError_t launch_backward_t(const Shape& s, const BwdArgs& a, hipStream_
     configured = true;
   }
   // k = 0: every list is empty and the kernel writes all-zero offsets
-  bwd_transpose_kernel<<<dim3((unsigned)s.BH), 256, 0, stream>>>(a.block_idx, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
+  bwd_mask_bits_kernel<<<dim3((unsigned)(s.BH * s.Tm)), 64, 0, stream>>>(a.block_idx, a.mask_bits, s.Tn, s.k);
+  bwd_transpose_kernel<<<dim3((unsigned)s.BH), kTransposeThreads, 0, stream>>>(a.mask_bits, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
   bwd_q_kernel<T, D><<<dim3((unsigned)((size_t)s.BH * s.Tm * parts)), 256, smem_q, stream>>>(
       (const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.dout, (const T*)a.o_s, (const T*)a.o_l, a.lse, a.k_mean,
       a.k_stats, a.h_total, a.z_total, a.block_idx, a.alpha, (T*)a.dq, a.ds, (float*)a.dh, a.dz, a.dalpha_part, s.sin,
@@ -688,8 +766,8 @@ static hipError_t launch_backward_t(const Shape& s, const BwdArgs& a, hipStream_
       a.col_idx, (const float*)a.dh, a.dz, a.dh_total, a.dz_total, a.alpha, (T*)a.dk, (T*)a.dv, a.colsum, s.sin, s.sout,
       s.H, s.N, s.bq, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
   if (s.smooth) {
-    bwd_colmean_kernel<<<dim3((unsigned)s.BH), 128, 0, stream>>>(a.colsum, a.dk_mean, s.Tn, s.N, D);
-    bwd_unsmooth_kernel<T><<<dim3((unsigned)(((size_t)s.N * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
+    bwd_colmean_kernel<<<dim3((unsigned)s.BH), 1024, 0, stream>>>(a.colsum, a.dk_mean, s.Tn, s.N, D);
+    bwd_unsmooth_kernel<T><<<dim3((unsigned)(((size_t)s.N * D / 8 + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
         (T*)a.dk, a.dk_mean, s.sin, s.H, s.N, D);
   }
   const int n_alpha = s.alpha_per_block ? s.H * s.Tm : s.H;
@@ -702,7 +780,8 @@ static hipError_t launch_backward_t(const Shape& s, const BwdArgs& a, hipStream_
 // bf16); the small ones above are shared.
 static hipError_t launch_backward_bf16(const Shape& s, const BwdArgs& a, hipStream_t stream) {
   const int D = s.d;
-  bwd_transpose_kernel<<<dim3((unsigned)s.BH), 256, 0, stream>>>(a.block_idx, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
+  bwd_mask_bits_kernel<<<dim3((unsigned)(s.BH * s.Tm)), 64, 0, stream>>>(a.block_idx, a.mask_bits, s.Tn, s.k);
+  bwd_transpose_kernel<<<dim3((unsigned)s.BH), kTransposeThreads, 0, stream>>>(a.mask_bits, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
   hipError_t e = launch_bwd_q_bf16(s, a, stream);
   if (e != hipSuccess) return e;
   bwd_sum_kernel<uint16_t><<<dim3((unsigned)((D * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
@@ -711,8 +790,8 @@ static hipError_t launch_backward_bf16(const Shape& s, const BwdArgs& a, hipStre
   e = launch_bwd_kv_bf16(s, a, stream);
   if (e != hipSuccess) return e;
   if (s.smooth) {
-    bwd_colmean_kernel<<<dim3((unsigned)s.BH), 128, 0, stream>>>(a.colsum, a.dk_mean, s.Tn, s.N, D);
-    bwd_unsmooth_kernel<uint16_t><<<dim3((unsigned)(((size_t)s.N * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
+    bwd_colmean_kernel<<<dim3((unsigned)s.BH), 1024, 0, stream>>>(a.colsum, a.dk_mean, s.Tn, s.N, D);
+    bwd_unsmooth_kernel<uint16_t><<<dim3((unsigned)(((size_t)s.N * D / 8 + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
         (uint16_t*)a.dk, a.dk_mean, s.sin, s.H, s.N, D);
   }
   const int n_alpha = s.alpha_per_block ? s.H * s.Tm : s.H;

@@ -393,8 +393,8 @@ template <int D> struct BwdKvSmem {
   static constexpr int kLd = D + 8;
   static constexpr int kTile = SwizzledLayout<D>::kTileBytes;                  // one 64 x D bf16 tile
   static constexpr int kKOff = 0, kVOff = kTile;                               // K_j, V_j (K_j becomes K^phi_j at the end)
-  static constexpr int kStepOff = 2 * kTile;                                   // two buffers of (Q rows, dO rows);
-  static constexpr int kStepBytes = 4 * kTile;                                 // after the loop: dH, then the output tiles
+  static constexpr int kStepOff = 2 * kTile;                                   // three buffers of (Q rows, dO rows);
+  static constexpr int kStepBytes = 6 * kTile;                                 // after the loop: dH, then the output tiles
   static constexpr int kPOff = kStepOff + kStepBytes;                          // alpha P [64 rows][64 keys] bf16
   static constexpr int kDsOff = kPOff + SwizzledLayout<64>::kTileBytes;        // dS, same shape
   static constexpr int kMuOff = kDsOff + SwizzledLayout<64>::kTileBytes;       // float [D]  colmean(K)
@@ -405,7 +405,7 @@ template <int D> struct BwdKvSmem {
 };
 
 template <int D, int BQ>
-__global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_kv_mfma_kernel(
+__global__ __launch_bounds__(256, 1) void bwd_kv_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const uint16_t* __restrict__ dout, const float* __restrict__ lraw, const float* __restrict__ ds_in,
     const double* __restrict__ k_mean, const float* __restrict__ k_stats, const int32_t* __restrict__ col_ptr,
@@ -458,27 +458,41 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_kv_mfma_kernel(
 
   const int32_t* cp = col_ptr + (size_t)bh * (Tn + 1);
   const int32_t* ci = col_idx + (size_t)bh * Tm * ksel;
-  const int l0 = cp[j], l1 = cp[j + 1];
+  const int l0 = __builtin_amdgcn_readfirstlane(cp[j]), l1 = __builtin_amdgcn_readfirstlane(cp[j + 1]);
+#ifdef SLA2_EXP_NO_LOOP
+  const int nsteps = 0;
+#else
   const int nsteps = (l1 - l0) * HP;
+#endif
   const int myrow = 32 * rw + lane % 32;             // this lane's query row inside a step
 
   // Step t covers rows [64 (t % HP), +64) of query block ci[l0 + t / HP].  A half block with no rows
   // (short last query block) still runs, on the block's first rows with every probability masked.
-  struct Step { int src0, rows; float al, L2, Ds; };
-  auto fetch = [&](int t, int buf) {
-    Step st;
-    const int i = ci[l0 + t / HP];
+  // The rows of a step are requested two steps ahead (three row buffers) and its query block index
+  // three steps ahead: a transfer takes longer than a step, and an index read right before its use
+  // would stall the wave for a full memory round trip.  L and D^s of this lane's row are loaded one
+  // step ahead, untracked and before that step's transfer request: vmcnt retires in order, so the
+  // counted wait at the end of a step (which leaves only the newest transfer in flight) covers them.
+  constexpr int kDmaOps = 2 * (kTileTokens * D * 2 / 1024 / NW);
+  struct Step { int rows, src0; float al, L, Ds; };
+  auto block_of = [&](int t) { return ci[l0 + min(t, nsteps - 1) / HP]; };
+  auto place = [&](int t, int i) {                   // where the rows of step t come from
+    Step st{0, 0, 0.f, 0.f, 0.f};
     const int row0 = i * BQ + 64 * (t % HP);
     st.rows = max(0, min(64, N - row0));
     st.src0 = st.rows > 0 ? row0 : i * BQ;
+    return st;
+  };
+  auto request_rows = [&](const Step& st, int buf) {
     const int dma_rows = max(st.rows, 1);
     dma_tile<D, NW>(qh + (size_t)st.src0 * tok_stride, tok_stride, dma_rows, qbuf(buf), w, lane);
     dma_tile<D, NW>(doh + (size_t)st.src0 * sout.n, sout.n, dma_rows, gbuf(buf), w, lane);
+  };
+  auto request_scalars = [&](Step& st, int i) {
+    const size_t at = (size_t)bh * N + st.src0 + min(myrow, max(st.rows, 1) - 1);
+    st.L = load_untracked<float>(lraw + at);
+    st.Ds = load_untracked<float>(ds_in + at);
     st.al = alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
-    const size_t at = (size_t)bh * N + st.src0 + min(myrow, dma_rows - 1);
-    st.L2 = lraw[at] * kLog2e;
-    st.Ds = ds_in[at];
-    return st;
   };
 
   f32x16 dvacc[TPW], dkacc[TPW];
@@ -488,37 +502,94 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_kv_mfma_kernel(
     for (int e = 0; e < 16; e++) { dvacc[x][e] = 0.f; dkacc[x][e] = 0.f; }
 
   Step cur{0, 0, 0.f, 0.f, 0.f};
-  if (nsteps > 0) cur = fetch(0, 0);
-  __builtin_amdgcn_s_waitcnt(kVmcnt0);
-  __syncthreads();                                   // K_j, V_j, step 0 and mus are in LDS for everyone
+  int i_nxt = 0, i_far = 0;                          // query blocks of steps t + 1 and t + 2
+  if (nsteps > 0) {
+    const int i0 = block_of(0);
+    i_nxt = block_of(1);
+    i_far = block_of(2);
+    cur = place(0, i0);
+    request_scalars(cur, i0);
+    request_rows(cur, 0);
+    if (nsteps > 1) request_rows(place(1, i_nxt), 1);
+  }
+  wait_vmcnt<0>();
+  settle(cur.L);
+  settle(cur.Ds);
+  __syncthreads();                                   // K_j, V_j, the first steps and mus are in LDS for everyone
 
+  // K_j and V_j rows 32 kw + l % 32 as A-operand fragments, for the whole loop
+  bf16x8 kfr[KS], vfr[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ks++) {
+    kfr[ks] = row_fragment<SL>(ktile, 32 * kw + lane % 32, 16 * ks + 8 * g);
+    vfr[ks] = row_fragment<SL>(vtile, 32 * kw + lane % 32, 16 * ks + 8 * g);
+  }
+  // LDS byte addresses of this lane's transposing reads (cf. read_tr4); the row swizzle depends on
+  // row % 8 only, so the reads of contraction step ks sit at fixed offsets from those of step 0
+  const int tr_row = 4 * g + (lane % 16) / 4, tr_col = 16 * ((lane / 16) % 2) + 4 * (lane % 4);
+  const unsigned a_off = (unsigned)SL::offset(tr_row, 32 * ct + tr_col) * 2;          // inside a Q or dO tile
+  // row-wise reads of this lane's Q / dO row: channel step ks sits at (address of step 0) ^ 32 ks
+  const unsigned b_off = (unsigned)SL::offset(myrow, 8 * g) * 2;
+  unsigned p_addr[TPW], s_addr[TPW];
+#pragma unroll
+  for (int x = 0; x < TPW; x++) {
+    p_addr[x] = lds_address(ptile + SP::offset(tr_row, 32 * kh_of(x) + tr_col));
+    s_addr[x] = lds_address(dstile + SP::offset(tr_row, 32 * kh_of(x) + tr_col));
+  }
+
+  int b_cur = 0, b_nxt = 1, b_far = 2;               // row buffers of steps t, t + 1, t + 2
   for (int t = 0; t < nsteps; t++) {
-    const int buf = t & 1;
-    Step nxt = cur;
-    if (t + 1 < nsteps) nxt = fetch(t + 1, buf ^ 1);
-    const uint16_t* qt = qbuf(buf);
-    const uint16_t* gt = gbuf(buf);
+    const bool more = t + 2 < nsteps;
+    Step nxt = place(t + 1, i_nxt);
+    if (t + 1 < nsteps) request_scalars(nxt, i_nxt);
+    if (more) request_rows(place(t + 2, i_far), b_far);
+    const int i_pf = block_of(t + 3);
+    const uint16_t* qt = qbuf(b_cur);
+    const uint16_t* gt = gbuf(b_cur);
     const bool row_ok = myrow < cur.rows;
-    // S^T = K Q^T and dP^T = V dO^T on keys 32 kw.., query rows 32 rw..
+    const float L2 = cur.L * kLog2e;
+    // S^T = K Q^T and dP^T = V dO^T on keys 32 kw.., query rows 32 rw..  The B operands (this lane's
+    // row of Q and dO, 16 bytes per 16-channel step) are read untracked, up to 12 in flight.
     f32x16 sacc, dpacc;
 #pragma unroll
     for (int e = 0; e < 16; e++) { sacc[e] = 0.f; dpacc[e] = 0.f; }
+    {
+      const unsigned qa = lds_address(qt) + b_off, ga = lds_address(gt) + b_off;
+      u32x4 qb[KS], gb[KS];
+      constexpr int H1 = KS / 2;
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++)
-      sacc = mfma_bf16(row_fragment<SL>(ktile, 32 * kw + lane % 32, 16 * ks + 8 * g),
-                       row_fragment<SL>(qt, myrow, 16 * ks + 8 * g), sacc);
+      for (int ks = 0; ks < KS; ks++) qb[ks] = lds_read16_untracked<0>(qa ^ (32u * ks));
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++)
-      dpacc = mfma_bf16(row_fragment<SL>(vtile, 32 * kw + lane % 32, 16 * ks + 8 * g),
-                        row_fragment<SL>(gt, myrow, 16 * ks + 8 * g), dpacc);
-    // alpha P and dS = P (.) (alpha dP - D^s) as [row][key] tiles
+      for (int ks = 0; ks < H1; ks++) gb[ks] = lds_read16_untracked<0>(ga ^ (32u * ks));
+#pragma unroll
+      for (int ks = 0; ks < H1; ks++) {
+        wait_lgkmcnt(KS + H1 - 1 - ks);
+        settle(qb[ks]);
+        sacc = mfma_bf16(kfr[ks], __builtin_bit_cast(bf16x8, qb[ks]), sacc);
+      }
+#pragma unroll
+      for (int ks = H1; ks < KS; ks++) gb[ks] = lds_read16_untracked<0>(ga ^ (32u * ks));
+#pragma unroll
+      for (int ks = H1; ks < KS; ks++) {
+        wait_lgkmcnt(KS + H1 - 1 - (ks - H1));
+        settle(qb[ks]);
+        sacc = mfma_bf16(kfr[ks], __builtin_bit_cast(bf16x8, qb[ks]), sacc);
+      }
+#pragma unroll
+      for (int ks = 0; ks < KS; ks++) {
+        wait_lgkmcnt(KS - 1 - ks);
+        settle(gb[ks]);
+        dpacc = mfma_bf16(vfr[ks], __builtin_bit_cast(bf16x8, gb[ks]), dpacc);
+      }
+    }
+    // alpha P and dS = P (.) (alpha dP - D^s) as [row][key] tiles; masked entries get exp2(-inf) = 0
 #pragma unroll
     for (int v4 = 0; v4 < 4; v4++) {
       bf16x4 pa, dsv;
 #pragma unroll
       for (int r = 0; r < 4; r++) {
-        float p = fast_exp2(sacc[4 * v4 + r] * c0 - cur.L2);
-        if (!row_ok || 32 * kw + 8 * v4 + 4 * g + r >= valid) p = 0.f;
+        const bool off_end = !row_ok || 32 * kw + 8 * v4 + 4 * g + r >= valid;
+        const float p = fast_exp2(off_end ? -INFINITY : sacc[4 * v4 + r] * c0 - L2);
         pa[r] = (__bf16)(cur.al * p);
         dsv[r] = (__bf16)(p * (cur.al * dpacc[4 * v4 + r] - cur.Ds));
       }
@@ -526,22 +597,62 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_kv_mfma_kernel(
       *reinterpret_cast<bf16x4*>(ptile + off) = pa;
       *reinterpret_cast<bf16x4*>(dstile + off) = dsv;
     }
-    __syncthreads();
-    // dV^T += dO^T (alpha P), dK'^T += Q^T dS: contraction over the 64 rows of the step
+    // the two tiles are complete for everyone (no fence: that would wait for the transfers in flight)
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    // dV^T += dO^T (alpha P), dK'^T += Q^T dS: contraction over the 64 rows of the step.  The operand
+    // reads of the next 16-row step are in flight while the products of this one run.
+    {
+      const unsigned ga = lds_address(gt) + a_off, qa = lds_address(qt) + a_off;
+      constexpr int kReads = 4 + 4 * TPW;
+      u32x2 rg[2][2], rq[2][2], rp[2][TPW][2], rs[2][TPW][2];
+      auto issue = [&](int ks, int slot) {
 #pragma unroll
-    for (int ks = 0; ks < 4; ks++) {
-      const bf16x8 ag = v_fragment<SL>(gt, ks, 32 * ct, lane);
-      const bf16x8 aq = v_fragment<SL>(qt, ks, 32 * ct, lane);
+        for (int hi = 0; hi < 2; hi++) {
+          rg[slot][hi] = lds_read_tr_untracked_at<16 * D>(ga, 2 * ks + hi);
+          rq[slot][hi] = lds_read_tr_untracked_at<16 * D>(qa, 2 * ks + hi);
+        }
 #pragma unroll
-      for (int x = 0; x < TPW; x++) {
-        dvacc[x] = mfma_bf16(ag, v_fragment<SP>(ptile, ks, 32 * kh_of(x), lane), dvacc[x]);
-        dkacc[x] = mfma_bf16(aq, v_fragment<SP>(dstile, ks, 32 * kh_of(x), lane), dkacc[x]);
+        for (int x = 0; x < TPW; x++)
+#pragma unroll
+          for (int hi = 0; hi < 2; hi++) {
+            rp[slot][x][hi] = lds_read_tr_untracked_at<1024>(p_addr[x], 2 * ks + hi);
+            rs[slot][x][hi] = lds_read_tr_untracked_at<1024>(s_addr[x], 2 * ks + hi);
+          }
+      };
+      auto frag = [&](u32x2 (&r)[2]) {
+        settle(r[0]);
+        settle(r[1]);
+        const u32x4 v4 = {r[0][0], r[0][1], r[1][0], r[1][1]};
+        return __builtin_bit_cast(bf16x8, v4);
+      };
+      issue(0, 0);
+#pragma unroll
+      for (int ks = 0; ks < 4; ks++) {
+        const int slot = ks & 1;
+        if (ks + 1 < 4) issue(ks + 1, slot ^ 1);
+        wait_lgkmcnt(ks + 1 < 4 ? kReads : 0);
+        const bf16x8 ag = frag(rg[slot]), aq = frag(rq[slot]);
+#pragma unroll
+        for (int x = 0; x < TPW; x++) {
+          dvacc[x] = mfma_bf16(ag, frag(rp[slot][x]), dvacc[x]);
+          dkacc[x] = mfma_bf16(aq, frag(rs[slot][x]), dkacc[x]);
+        }
       }
     }
+    if (more) wait_vmcnt<kDmaOps>();                 // step t + 1 has landed; t + 2 may still be in flight
+    else wait_vmcnt<0>();
     cur = nxt;
-    __builtin_amdgcn_s_waitcnt(kVmcnt0);             // the next step's rows have landed ...
-    __syncthreads();                                 // ... for everyone; this step's tiles are free
+    settle(cur.L);
+    settle(cur.Ds);
+    asm volatile("s_barrier" ::: "memory");          // ... for everyone; this step's tiles are free
+    const int b = b_cur;
+    b_cur = b_nxt;
+    b_nxt = b_far;
+    b_far = b;
+    i_nxt = i_far;
+    i_far = i_pf;
   }
+  __syncthreads();
 
   // ================= linear branch =================
   uint16_t* dht = reinterpret_cast<uint16_t*>(smem + SM::kStepOff);      // dH [c][e] as bf16, row stride LD
@@ -559,7 +670,11 @@ __global__ __launch_bounds__(256, D == 64 ? 2 : 1) void bwd_kv_mfma_kernel(
       for (int e = 0; e < 4; e++) { acc[n][e] = all_selected ? 0.f : a[e]; acc[n][4 + e] = all_selected ? 0.f : b[e]; }
     }
     float dzj = (tid < D && !all_selected) ? dz_total[(size_t)bh * D + tid] : 0.f;
+#ifndef SLA2_EXP_NO_GATHER
     if (!all_selected)
+#else
+    if (false)
+#endif
       for (int l = l0; l < l1; l++) {
         const size_t slot = (size_t)bh * Tm + ci[l];
         const uint16_t* src = dh_in + slot * D * D;

@@ -318,94 +318,6 @@ template <int D, int BQ, bool FP8, bool VQ = false> struct AttnSmem {
 };
 
 
-// A global load the compiler does not track: no wait is generated for it, the caller waits with
-// wait_vmcnt<>() and then passes every loaded value through settle() before using it.
-template <class T>
-__device__ __forceinline__ T load_untracked(const void* p) {
-  T r;
-  if constexpr (sizeof(T) == 16) asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(p));
-  else asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p));
-  return r;
-}
-template <class T, bool UNTRACKED>
-__device__ __forceinline__ T load_maybe_tracked(const void* p) {
-  if constexpr (UNTRACKED) return load_untracked<T>(p);
-  else return *reinterpret_cast<const T*>(p);
-}
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N));
-}
-// Orders every later use of x after the preceding wait (volatile statements keep their order).
-template <class T>
-__device__ __forceinline__ void settle(T& x) { asm volatile("" : "+v"(x)); }
-
-// LDS operand reads issued the same way.  The compiler's scheduler keeps a tracked read, its wait
-// and the product that consumes it back to back, so the LDS latency is paid once per product; with
-// the reads untracked the kernel keeps several in flight and waits with the count it knows.  The
-// LDS counter retires in order, so "at most n outstanding" settles everything but the n youngest.
-// Another benefit: a tracked transposing read is treated as a possible alias of the tile transfer
-// in flight and is preceded by vmcnt(0).
-__device__ __forceinline__ unsigned lds_address(const void* p) {
-  return (unsigned)(size_t)(const __attribute__((address_space(3))) void*)p;
-}
-template <int OFF1>   // 8 bytes at addr and 8 bytes at addr + 512 OFF1
-__device__ __forceinline__ u32x4 lds_read2_untracked(unsigned addr) {
-  u32x4 r;
-  asm volatile("ds_read2st64_b64 %0, %1 offset1:%2" : "=v"(r) : "v"(addr), "n"(OFF1));
-  return r;
-}
-template <int OFF>    // 16 bytes at addr + OFF
-__device__ __forceinline__ u32x4 lds_read16_untracked(unsigned addr) {
-  u32x4 r;
-  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-  return r;
-}
-template <int UNIT>   // 16 bytes at addr + n UNIT, the offset in the instruction (n constant after unrolling)
-__device__ __forceinline__ u32x4 lds_read16_untracked_at(unsigned addr, int n) {
-  switch (n) {
-    case 0: return lds_read16_untracked<0>(addr);
-    case 1: return lds_read16_untracked<UNIT>(addr);
-    case 2: return lds_read16_untracked<2 * UNIT>(addr);
-    default: return lds_read16_untracked<3 * UNIT>(addr);
-  }
-}
-template <int OFF>    // transposing read, see read_tr4
-__device__ __forceinline__ u32x2 lds_read_tr_untracked(unsigned addr) {
-  u32x2 r;
-  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFF));
-  return r;
-}
-// at addr + n UNIT with the offset in the instruction; n is a constant after unrolling
-template <int UNIT>
-__device__ __forceinline__ u32x2 lds_read_tr_untracked_at(unsigned addr, int n) {
-  switch (n) {
-    case 0: return lds_read_tr_untracked<0>(addr);
-    case 1: return lds_read_tr_untracked<UNIT>(addr);
-    case 2: return lds_read_tr_untracked<2 * UNIT>(addr);
-    case 3: return lds_read_tr_untracked<3 * UNIT>(addr);
-    case 4: return lds_read_tr_untracked<4 * UNIT>(addr);
-    case 5: return lds_read_tr_untracked<5 * UNIT>(addr);
-    case 6: return lds_read_tr_untracked<6 * UNIT>(addr);
-    default: return lds_read_tr_untracked<7 * UNIT>(addr);
-  }
-}
-// n is a constant once the calling loop is unrolled; only the matching statement survives
-__device__ __forceinline__ void wait_lgkmcnt(int n) {
-  switch (n) {
-    case 0: asm volatile("s_waitcnt lgkmcnt(0)"); break;
-    case 1: asm volatile("s_waitcnt lgkmcnt(1)"); break;
-    case 2: asm volatile("s_waitcnt lgkmcnt(2)"); break;
-    case 3: asm volatile("s_waitcnt lgkmcnt(3)"); break;
-    case 4: asm volatile("s_waitcnt lgkmcnt(4)"); break;
-    case 5: asm volatile("s_waitcnt lgkmcnt(5)"); break;
-    case 6: asm volatile("s_waitcnt lgkmcnt(6)"); break;
-    case 7: asm volatile("s_waitcnt lgkmcnt(7)"); break;
-    default: asm volatile("s_waitcnt lgkmcnt(0)"); break;
-  }
-}
-
 template <int D, int BQ, int MODE>
 __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
