@@ -74,6 +74,17 @@ __device__ __forceinline__ bf16x8 v_fragment(const uint16_t* vtile, int ks, int 
   return __builtin_bit_cast(bf16x8, r);
 }
 
+// The same read with the contraction index in natural order: lane l <- tile[16 ks + 8 (l/32) + 0..7][col0 + l % 32]
+template <class L>
+__device__ __forceinline__ bf16x8 nat_fragment(const uint16_t* tile, int ks, int col0, int lane) {
+  const int g = lane / 32;
+  s16x4 lo = read_tr4<L>(tile, 16 * ks + 8 * g, col0, lane);
+  s16x4 hi = read_tr4<L>(tile, 16 * ks + 8 * g + 4, col0, lane);
+  typedef __attribute__((ext_vector_type(8))) short s16x8;
+  s16x8 r = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+  return __builtin_bit_cast(bf16x8, r);
+}
+
 // Row-wise operand fragment: lane l <- tile[row][col .. col + 7]  (one 16-byte read)
 template <class L>
 __device__ __forceinline__ bf16x8 row_fragment(const uint16_t* tile, int row, int col) {

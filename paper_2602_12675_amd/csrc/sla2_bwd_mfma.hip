@@ -13,8 +13,8 @@
 //                dQ^phi^T = H_i dO^l^T - Z_i D^l^T (over Q^phi Z_i), dQ += softmax-backward(dQ^phi),
 //                dH_i = (Q^phi / (Q^phi Z_i))^T dO^l, dZ_i.
 //   bwd_kv_mfma  one workgroup per key block j, over the query blocks that selected it, 64 rows a
-//                step: P^T and dS^T as above, written to LDS as [row][key] tiles, then
-//                dV^T += dO^T (alpha P), dK'^T += Q^T dS.  Then the linear branch:
+//                step: here S = Q K^T (rows x keys), so that P and dS are already laid out as the
+//                B operands of dV^T += dO^T (alpha P), dK'^T += Q^T dS.  Then the linear branch:
 //                dH = dH_total - sum over those query blocks of dH_i (Alg. 3's M_c[i, j] = 0 sum, by
 //                complement), dK^phi^T = dH V^T + dZ 1^T, dV^T += dH^T K^phi^T,
 //                dK' += softmax-backward(dK^phi).
@@ -145,7 +145,7 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
   const float L2 = Lraw * kLog2e;
   if (g == 0 && row_ok) {
     ds_out[(size_t)bh * N + row0 + qrow] = Ds;
-    lraw_out[(size_t)bh * N + row0 + qrow] = Lraw;
+    lraw_out[(size_t)bh * N + row0 + qrow] = L2;      // as the key-side kernel uses it: L on the raw keys, times log2(e)
   }
 
   f32x16 dqacc[ET];
@@ -392,22 +392,26 @@ static hipError_t launch_bwd_q_mfma(const Shape& s, const BwdArgs& a, hipStream_
 template <int D> struct BwdKvSmem {
   static constexpr int kLd = D + 8;
   static constexpr int kTile = SwizzledLayout<D>::kTileBytes;                  // one 64 x D bf16 tile
-  static constexpr int kKOff = 0, kVOff = kTile;                               // K_j, V_j (K_j becomes K^phi_j at the end)
-  static constexpr int kStepOff = 2 * kTile;                                   // three buffers of (Q rows, dO rows);
-  static constexpr int kStepBytes = 6 * kTile;                                 // after the loop: dH, then the output tiles
-  static constexpr int kPOff = kStepOff + kStepBytes;                          // alpha P [64 rows][64 keys] bf16
-  static constexpr int kDsOff = kPOff + SwizzledLayout<64>::kTileBytes;        // dS, same shape
-  static constexpr int kMuOff = kDsOff + SwizzledLayout<64>::kTileBytes;       // float [D]  colmean(K)
+  static constexpr int kStepBytes = 4 * kTile;                                 // two buffers of (Q rows, dO rows);
+                                                                               // after the loop: dH and K^phi, then the outputs
+  static constexpr int kStatOff = kStepBytes;                                  // float [2][2][64]: L log2(e) and D^s of a step's rows
+  static constexpr int kMuOff = kStatOff + 2 * 2 * 64 * 4;                     // float [D]  colmean(K)
   static constexpr int kDzOff = kMuOff + D * 4;                                // float [D]  dZ of this key block
   static constexpr int kDotOff = kDzOff + D * 4;                               // float [D / 32][64]
   static constexpr int kBytes = kDotOff + (D / 32) * 64 * 4;
-  static_assert(D * kLd * 2 <= kStepBytes && 2 * 64 * kLd * 2 <= kStepBytes, "epilogue tiles reuse the step buffers");
+  static_assert((D + 64) * kLd * 2 <= kStepBytes && 2 * 64 * kLd * 2 <= kStepBytes, "epilogue tiles reuse the step buffers");
 };
 
+// Scores are computed as S = Q K^T (query rows x keys) here: a lane of the result then owns one key
+// and 16 of the 32 query rows of the tile, which is the B-operand layout of the products that contract
+// over query rows (dV^T += dO^T P, dK^T += Q^T dS) - P and dS never leave registers.  Wave w owns the
+// key half kh = w % 2 and the channel tiles of group w / 2; it computes the scores of all 64 rows of a
+// step against its 32 keys (the two waves of a key half repeat that work: cheaper than passing P and dS
+// through LDS with a barrier in between).  K_j and V_j live in registers as operand fragments.
 template <int D, int BQ>
-__global__ __launch_bounds__(256, 1) void bwd_kv_mfma_kernel(
+__global__ __launch_bounds__(256, 2) void bwd_kv_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const uint16_t* __restrict__ dout, const float* __restrict__ lraw, const float* __restrict__ ds_in,
+    const uint16_t* __restrict__ dout, const float* __restrict__ lraw2, const float* __restrict__ ds_in,
     const double* __restrict__ k_mean, const float* __restrict__ k_stats, const int32_t* __restrict__ col_ptr,
     const int32_t* __restrict__ col_idx, const uint16_t* __restrict__ dh_in, const float* __restrict__ dz_in,
     const float* __restrict__ dh_total, const float* __restrict__ dz_total, const float* __restrict__ alpha,
@@ -416,19 +420,14 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_mfma_kernel(
   constexpr int NW = 4, NT = 256;
   constexpr int LD = D + 8, KS = D / 16, ET = D / 32;
   constexpr int HP = BQ / 64;                        // 64-row steps per query block
-  constexpr int TPW = 2 * ET / NW;                   // 32 x 32 tiles of dV^T / dK^T (channels x keys) per wave
-  static_assert(TPW == 1 || TPW == 2, "unsupported split");
+  constexpr int CT = ET / 2;                         // 32-channel tiles of dV^T / dK^T per wave
   typedef SwizzledLayout<D> SL;
-  typedef SwizzledLayout<64> SP;
   typedef PaddedLayout<D> PL;
   typedef BwdKvSmem<D> SM;
   extern __shared__ __attribute__((aligned(1024))) unsigned char smem[];
-  uint16_t* ktile = reinterpret_cast<uint16_t*>(smem + SM::kKOff);
-  uint16_t* vtile = reinterpret_cast<uint16_t*>(smem + SM::kVOff);
-  auto qbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + SM::kStepOff + buf * 2 * SM::kTile); };
-  auto gbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + SM::kStepOff + buf * 2 * SM::kTile + SM::kTile); };
-  uint16_t* ptile = reinterpret_cast<uint16_t*>(smem + SM::kPOff);
-  uint16_t* dstile = reinterpret_cast<uint16_t*>(smem + SM::kDsOff);
+  auto qbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + buf * 2 * SM::kTile); };
+  auto gbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + buf * 2 * SM::kTile + SM::kTile); };
+  float* stat = reinterpret_cast<float*>(smem + SM::kStatOff);
   float* mus = reinterpret_cast<float*>(smem + SM::kMuOff);
   float* dzs = reinterpret_cast<float*>(smem + SM::kDzOff);
   float* dred = reinterpret_cast<float*>(smem + SM::kDotOff);
@@ -440,20 +439,28 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_mfma_kernel(
   const int bh = logical / Tn, j = logical % Tn, h = bh % H;
   const int tid = threadIdx.x, lane = tid % kWave, g = lane / 32;
   const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
-  const int rw = w & 1, kw = w >> 1;                 // scores: query rows 32 rw.., keys 32 kw..
-  const int ct = TPW == 2 ? w : w >> 1;              // accumulators: channels 32 ct.., keys 32 kh(x)..
-  auto kh_of = [&](int x) { return TPW == 2 ? x : (w & 1); };
+  const int kh = w & 1, cgrp = w >> 1;
   const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
+  const int mykey = 32 * kh + lane % 32;             // this lane's key inside the block
+  const bool key_ok = mykey < valid;
   const uint16_t* qh = q + head_offset(sin, bh, H);
-  const uint16_t* kh = k + head_offset(sin, bh, H);
+  const uint16_t* kh_ = k + head_offset(sin, bh, H);
   const uint16_t* vh = v + head_offset(sin, bh, H);
   const uint16_t* doh = dout + head_offset(sout, bh, H);
   const int tok_stride = sin.n;
   const float rscale = rsqrtf((float)D);
   const float c0 = kLog2e * rscale;
 
-  dma_tile<D, NW>(kh + (size_t)t0 * tok_stride, tok_stride, valid, ktile, w, lane);
-  dma_tile<D, NW>(vh + (size_t)t0 * tok_stride, tok_stride, valid, vtile, w, lane);
+  // K_j and V_j rows of this lane's key as operand fragments (rows past the end repeat the last one)
+  bf16x8 kfr[KS], vfr[KS];
+  {
+    const size_t row = (size_t)(t0 + min(mykey, valid - 1)) * tok_stride + 8 * g;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      kfr[ks] = *reinterpret_cast<const bf16x8*>(kh_ + row + 16 * ks);
+      vfr[ks] = *reinterpret_cast<const bf16x8*>(vh + row + 16 * ks);
+    }
+  }
   if (tid < D) mus[tid] = (float)k_mean[(size_t)bh * D + tid];
 
   const int32_t* cp = col_ptr + (size_t)bh * (Tn + 1);
@@ -464,159 +471,133 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_mfma_kernel(
 #else
   const int nsteps = (l1 - l0) * HP;
 #endif
-  const int myrow = 32 * rw + lane % 32;             // this lane's query row inside a step
 
   // Step t covers rows [64 (t % HP), +64) of query block ci[l0 + t / HP].  A half block with no rows
   // (short last query block) still runs, on the block's first rows with every probability masked.
-  // The rows of a step are requested two steps ahead (three row buffers) and its query block index
-  // three steps ahead: a transfer takes longer than a step, and an index read right before its use
-  // would stall the wave for a full memory round trip.  L and D^s of this lane's row are loaded one
-  // step ahead, untracked and before that step's transfer request: vmcnt retires in order, so the
-  // counted wait at the end of a step (which leaves only the newest transfer in flight) covers them.
-  constexpr int kDmaOps = 2 * (kTileTokens * D * 2 / 1024 / NW);
-  struct Step { int rows, src0; float al, L, Ds; };
+  // The rows of step t + 1 (and L log2 e, D^s of those rows) are requested at the start of step t,
+  // straight into LDS; the query block index is read one step before that.
+  struct Step { int rows, src0; float al; };
   auto block_of = [&](int t) { return ci[l0 + min(t, nsteps - 1) / HP]; };
-  auto place = [&](int t, int i) {                   // where the rows of step t come from
-    Step st{0, 0, 0.f, 0.f, 0.f};
+  auto place = [&](int t, int i) {
+    Step st;
     const int row0 = i * BQ + 64 * (t % HP);
     st.rows = max(0, min(64, N - row0));
     st.src0 = st.rows > 0 ? row0 : i * BQ;
+    st.al = alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
     return st;
   };
-  auto request_rows = [&](const Step& st, int buf) {
+  auto request = [&](const Step& st, int buf) {
     const int dma_rows = max(st.rows, 1);
     dma_tile<D, NW>(qh + (size_t)st.src0 * tok_stride, tok_stride, dma_rows, qbuf(buf), w, lane);
     dma_tile<D, NW>(doh + (size_t)st.src0 * sout.n, sout.n, dma_rows, gbuf(buf), w, lane);
-  };
-  auto request_scalars = [&](Step& st, int i) {
-    const size_t at = (size_t)bh * N + st.src0 + min(myrow, max(st.rows, 1) - 1);
-    st.L = load_untracked<float>(lraw + at);
-    st.Ds = load_untracked<float>(ds_in + at);
-    st.al = alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
+    // every wave fetches the same 2 x 64 floats (same values to the same place: the counts of
+    // outstanding transfers stay equal across the waves)
+    const size_t at = (size_t)bh * N + st.src0 + min(lane, dma_rows - 1);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(lraw2 + at),
+                                     (__attribute__((address_space(3))) void*)(stat + buf * 128), 4, 0, 0);
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(ds_in + at),
+                                     (__attribute__((address_space(3))) void*)(stat + buf * 128 + 64), 4, 0, 0);
   };
 
-  f32x16 dvacc[TPW], dkacc[TPW];
+  f32x16 dvacc[CT], dkacc[CT];
 #pragma unroll
-  for (int x = 0; x < TPW; x++)
+  for (int x = 0; x < CT; x++)
 #pragma unroll
     for (int e = 0; e < 16; e++) { dvacc[x][e] = 0.f; dkacc[x][e] = 0.f; }
 
-  Step cur{0, 0, 0.f, 0.f, 0.f};
-  int i_nxt = 0, i_far = 0;                          // query blocks of steps t + 1 and t + 2
+  Step cur{0, 0, 0.f};
+  int i_nxt = 0;
   if (nsteps > 0) {
-    const int i0 = block_of(0);
+    cur = place(0, block_of(0));
     i_nxt = block_of(1);
-    i_far = block_of(2);
-    cur = place(0, i0);
-    request_scalars(cur, i0);
-    request_rows(cur, 0);
-    if (nsteps > 1) request_rows(place(1, i_nxt), 1);
+    request(cur, 0);
   }
   wait_vmcnt<0>();
-  settle(cur.L);
-  settle(cur.Ds);
-  __syncthreads();                                   // K_j, V_j, the first steps and mus are in LDS for everyone
-
-  // K_j and V_j rows 32 kw + l % 32 as A-operand fragments, for the whole loop
-  bf16x8 kfr[KS], vfr[KS];
 #pragma unroll
-  for (int ks = 0; ks < KS; ks++) {
-    kfr[ks] = row_fragment<SL>(ktile, 32 * kw + lane % 32, 16 * ks + 8 * g);
-    vfr[ks] = row_fragment<SL>(vtile, 32 * kw + lane % 32, 16 * ks + 8 * g);
-  }
-  // LDS byte addresses of this lane's transposing reads (cf. read_tr4); the row swizzle depends on
-  // row % 8 only, so the reads of contraction step ks sit at fixed offsets from those of step 0
+  for (int ks = 0; ks < KS; ks++) { settle(kfr[ks]); settle(vfr[ks]); }
+  __syncthreads();                                   // step 0 and mus are in LDS for everyone
+
+  // LDS byte offsets of this lane's operand reads inside a Q or dO tile.  Row-wise reads: row
+  // l % 32 (+ 32 for the second row half), channel step ks at (offset of step 0) ^ 32 ks.
+  // Transposing reads (cf. read_tr4): the row swizzle depends on row % 8 only, so 16-row step ks
+  // sits at a fixed distance from step 0.
+  const unsigned b_off = (unsigned)SL::offset(lane % 32, 8 * g) * 2;
   const int tr_row = 4 * g + (lane % 16) / 4, tr_col = 16 * ((lane / 16) % 2) + 4 * (lane % 4);
-  const unsigned a_off = (unsigned)SL::offset(tr_row, 32 * ct + tr_col) * 2;          // inside a Q or dO tile
-  // row-wise reads of this lane's Q / dO row: channel step ks sits at (address of step 0) ^ 32 ks
-  const unsigned b_off = (unsigned)SL::offset(myrow, 8 * g) * 2;
-  unsigned p_addr[TPW], s_addr[TPW];
+  unsigned a_off[CT];
 #pragma unroll
-  for (int x = 0; x < TPW; x++) {
-    p_addr[x] = lds_address(ptile + SP::offset(tr_row, 32 * kh_of(x) + tr_col));
-    s_addr[x] = lds_address(dstile + SP::offset(tr_row, 32 * kh_of(x) + tr_col));
-  }
+  for (int x = 0; x < CT; x++) a_off[x] = (unsigned)SL::offset(tr_row, 32 * (CT * cgrp + x) + tr_col) * 2;
 
-  int b_cur = 0, b_nxt = 1, b_far = 2;               // row buffers of steps t, t + 1, t + 2
   for (int t = 0; t < nsteps; t++) {
-    const bool more = t + 2 < nsteps;
-    Step nxt = place(t + 1, i_nxt);
-    if (t + 1 < nsteps) request_scalars(nxt, i_nxt);
-    if (more) request_rows(place(t + 2, i_far), b_far);
-    const int i_pf = block_of(t + 3);
-    const uint16_t* qt = qbuf(b_cur);
-    const uint16_t* gt = gbuf(b_cur);
-    const bool row_ok = myrow < cur.rows;
-    const float L2 = cur.L * kLog2e;
-    // S^T = K Q^T and dP^T = V dO^T on keys 32 kw.., query rows 32 rw..  The B operands (this lane's
-    // row of Q and dO, 16 bytes per 16-channel step) are read untracked, up to 12 in flight.
-    f32x16 sacc, dpacc;
+    const int buf = t & 1;
+    Step nxt = cur;
+    if (t + 1 < nsteps) {
+      nxt = place(t + 1, i_nxt);
+#ifndef SLA2_EXP_NO_DMA
+      request(nxt, buf ^ 1);
+#endif
+    }
+    i_nxt = block_of(t + 2);
+    const unsigned qa = lds_address(qbuf(buf)), ga = lds_address(gbuf(buf));
+    const float* st_l = stat + buf * 128;
+    // S = Q K^T and dP = dO V^T: rows 32 rh.. x this wave's 32 keys.  32 operand reads (this lane's
+    // rows of Q and dO), each feeding one product; 8 are kept in flight.
+    f32x16 sacc[2], dpacc[2];
 #pragma unroll
-    for (int e = 0; e < 16; e++) { sacc[e] = 0.f; dpacc[e] = 0.f; }
+    for (int rh = 0; rh < 2; rh++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) { sacc[rh][e] = 0.f; dpacc[rh][e] = 0.f; }
     {
-      const unsigned qa = lds_address(qt) + b_off, ga = lds_address(gt) + b_off;
-      u32x4 qb[KS], gb[KS];
-      constexpr int H1 = KS / 2;
+      constexpr int kItems = 4 * KS, kAhead = 8, kSlots = kAhead + 1;
+      u32x4 ring[kSlots];
+      auto issue = [&](int n) {                      // item n: (Q | dO, row half, channel step)
+        const int grp = n / KS, ks = n % KS;
+        const unsigned base = (grp < 2 ? qa : ga) + b_off;
+        if (grp % 2 == 0) ring[n % kSlots] = lds_read16_untracked<0>(base ^ (32u * ks));
+        else ring[n % kSlots] = lds_read16_untracked<32 * D * 2>(base ^ (32u * ks));
+      };
 #pragma unroll
-      for (int ks = 0; ks < KS; ks++) qb[ks] = lds_read16_untracked<0>(qa ^ (32u * ks));
+      for (int n = 0; n < kAhead; n++) issue(n);
 #pragma unroll
-      for (int ks = 0; ks < H1; ks++) gb[ks] = lds_read16_untracked<0>(ga ^ (32u * ks));
-#pragma unroll
-      for (int ks = 0; ks < H1; ks++) {
-        wait_lgkmcnt(KS + H1 - 1 - ks);
-        settle(qb[ks]);
-        sacc = mfma_bf16(kfr[ks], __builtin_bit_cast(bf16x8, qb[ks]), sacc);
-      }
-#pragma unroll
-      for (int ks = H1; ks < KS; ks++) gb[ks] = lds_read16_untracked<0>(ga ^ (32u * ks));
-#pragma unroll
-      for (int ks = H1; ks < KS; ks++) {
-        wait_lgkmcnt(KS + H1 - 1 - (ks - H1));
-        settle(qb[ks]);
-        sacc = mfma_bf16(kfr[ks], __builtin_bit_cast(bf16x8, qb[ks]), sacc);
-      }
-#pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
-        wait_lgkmcnt(KS - 1 - ks);
-        settle(gb[ks]);
-        dpacc = mfma_bf16(vfr[ks], __builtin_bit_cast(bf16x8, gb[ks]), dpacc);
+      for (int n = 0; n < kItems; n++) {
+        if (n + kAhead < kItems) issue(n + kAhead);
+        wait_lgkmcnt(n + kAhead < kItems ? kAhead : kItems - 1 - n);
+        settle(ring[n % kSlots]);
+        const bf16x8 a = __builtin_bit_cast(bf16x8, ring[n % kSlots]);
+        const int grp = n / KS, ks = n % KS;
+        if (grp < 2) sacc[grp] = mfma_bf16(a, kfr[ks], sacc[grp]);
+        else dpacc[grp - 2] = mfma_bf16(a, vfr[ks], dpacc[grp - 2]);
       }
     }
-    // alpha P and dS = P (.) (alpha dP - D^s) as [row][key] tiles; masked entries get exp2(-inf) = 0
+    // alpha P and dS = P (.) (alpha dP - D^s), as B-operand fragments over the 64 rows (token order);
+    // masked entries get exp2(-inf) = 0
+    bf16x8 pf[4], dsf[4];
 #pragma unroll
-    for (int v4 = 0; v4 < 4; v4++) {
-      bf16x4 pa, dsv;
+    for (int rh = 0; rh < 2; rh++)
 #pragma unroll
-      for (int r = 0; r < 4; r++) {
-        const bool off_end = !row_ok || 32 * kw + 8 * v4 + 4 * g + r >= valid;
-        const float p = fast_exp2(off_end ? -INFINITY : sacc[4 * v4 + r] * c0 - L2);
-        pa[r] = (__bf16)(cur.al * p);
-        dsv[r] = (__bf16)(p * (cur.al * dpacc[4 * v4 + r] - cur.Ds));
+      for (int v4 = 0; v4 < 4; v4++) {
+        const f32x4 l4 = *reinterpret_cast<const f32x4*>(st_l + 32 * rh + 8 * v4 + 4 * g);
+        const f32x4 d4 = *reinterpret_cast<const f32x4*>(st_l + 64 + 32 * rh + 8 * v4 + 4 * g);
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          const bool off_end = !key_ok || 32 * rh + 8 * v4 + 4 * g + r >= cur.rows;
+          const float p = fast_exp2(off_end ? -INFINITY : sacc[rh][4 * v4 + r] * c0 - l4[r]);
+          pf[2 * rh + v4 / 2][4 * (v4 % 2) + r] = (__bf16)(cur.al * p);
+          dsf[2 * rh + v4 / 2][4 * (v4 % 2) + r] = (__bf16)(p * (cur.al * dpacc[rh][4 * v4 + r] - d4[r]));
+        }
       }
-      const int off = SP::offset(myrow, 32 * kw + 8 * v4 + 4 * g);
-      *reinterpret_cast<bf16x4*>(ptile + off) = pa;
-      *reinterpret_cast<bf16x4*>(dstile + off) = dsv;
-    }
-    // the two tiles are complete for everyone (no fence: that would wait for the transfers in flight)
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    // dV^T += dO^T (alpha P), dK'^T += Q^T dS: contraction over the 64 rows of the step.  The operand
-    // reads of the next 16-row step are in flight while the products of this one run.
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // nothing tracked is in flight when the counted reads below start
+    // dV^T += dO^T (alpha P), dK'^T += Q^T dS: contraction over the 64 rows of the step; the operand
+    // reads of the next 16-row step are in flight while the products of this one run
     {
-      const unsigned ga = lds_address(gt) + a_off, qa = lds_address(qt) + a_off;
-      constexpr int kReads = 4 + 4 * TPW;
-      u32x2 rg[2][2], rq[2][2], rp[2][TPW][2], rs[2][TPW][2];
+      constexpr int kReads = 4 * CT;
+      u32x2 rg[2][CT][2], rq[2][CT][2];
       auto issue = [&](int ks, int slot) {
 #pragma unroll
-        for (int hi = 0; hi < 2; hi++) {
-          rg[slot][hi] = lds_read_tr_untracked_at<16 * D>(ga, 2 * ks + hi);
-          rq[slot][hi] = lds_read_tr_untracked_at<16 * D>(qa, 2 * ks + hi);
-        }
-#pragma unroll
-        for (int x = 0; x < TPW; x++)
+        for (int x = 0; x < CT; x++)
 #pragma unroll
           for (int hi = 0; hi < 2; hi++) {
-            rp[slot][x][hi] = lds_read_tr_untracked_at<1024>(p_addr[x], 2 * ks + hi);
-            rs[slot][x][hi] = lds_read_tr_untracked_at<1024>(s_addr[x], 2 * ks + hi);
+            rg[slot][x][hi] = lds_read_tr_untracked_at<16 * D>(ga + a_off[x], 2 * ks + hi);
+            rq[slot][x][hi] = lds_read_tr_untracked_at<16 * D>(qa + a_off[x], 2 * ks + hi);
           }
       };
       auto frag = [&](u32x2 (&r)[2]) {
@@ -631,31 +612,22 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_mfma_kernel(
         const int slot = ks & 1;
         if (ks + 1 < 4) issue(ks + 1, slot ^ 1);
         wait_lgkmcnt(ks + 1 < 4 ? kReads : 0);
-        const bf16x8 ag = frag(rg[slot]), aq = frag(rq[slot]);
 #pragma unroll
-        for (int x = 0; x < TPW; x++) {
-          dvacc[x] = mfma_bf16(ag, frag(rp[slot][x]), dvacc[x]);
-          dkacc[x] = mfma_bf16(aq, frag(rs[slot][x]), dkacc[x]);
+        for (int x = 0; x < CT; x++) {
+          dvacc[x] = mfma_bf16(frag(rg[slot][x]), pf[ks], dvacc[x]);
+          dkacc[x] = mfma_bf16(frag(rq[slot][x]), dsf[ks], dkacc[x]);
         }
       }
     }
-    if (more) wait_vmcnt<kDmaOps>();                 // step t + 1 has landed; t + 2 may still be in flight
-    else wait_vmcnt<0>();
-    cur = nxt;
-    settle(cur.L);
-    settle(cur.Ds);
+    wait_vmcnt<0>();                                 // the next step's rows have landed ...
     asm volatile("s_barrier" ::: "memory");          // ... for everyone; this step's tiles are free
-    const int b = b_cur;
-    b_cur = b_nxt;
-    b_nxt = b_far;
-    b_far = b;
-    i_nxt = i_far;
-    i_far = i_pf;
+    cur = nxt;
   }
   __syncthreads();
 
   // ================= linear branch =================
-  uint16_t* dht = reinterpret_cast<uint16_t*>(smem + SM::kStepOff);      // dH [c][e] as bf16, row stride LD
+  uint16_t* dht = reinterpret_cast<uint16_t*>(smem);                     // dH [c][e] as bf16, row stride LD
+  uint16_t* kpt = dht + D * LD;                                          // K^phi_j [key][c], row stride LD
   const bool all_selected = ksel >= Tn;
   {
     // dH = dH_total - sum over the query blocks that selected j of dH_i (Alg. 3's M_c[i, j] = 0 sum)
@@ -696,49 +668,48 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_mfma_kernel(
     }
     if (tid < D) dzs[tid] = dzj;
   }
-  // K_j -> K^phi_j = exp(K - colmean(K) - lnZ) in place (rows past the end: 0)
-  for (int idx = tid; idx < kTileTokens * (D / 8); idx += NT) {
-    const int t = idx / (D / 8), pc = idx % (D / 8);
-    const int c = 8 * (pc ^ SL::swz(t));             // the channels held by physical chunk pc of row t
-    const float lnz = k_stats[(size_t)bh * N + t0 + min(t, valid - 1)];
-    bf16x8 x = *reinterpret_cast<const bf16x8*>(ktile + t * D + 8 * pc);
+  // K_j -> K^phi_j = exp(K - colmean(K) - lnZ) in the fragment registers (keys past the end: 0); one
+  // wave of each key half also leaves it in LDS for the softmax-backward step
+  {
+    const float lnz2 = k_stats[(size_t)bh * N + t0 + min(mykey, valid - 1)] * kLog2e;
 #pragma unroll
-    for (int e = 0; e < 8; e++) {
-      const float kp = t < valid ? fast_exp2(((float)x[e] - mus[c + e] - lnz) * kLog2e) : 0.f;
-      x[e] = (__bf16)kp;
+    for (int ks = 0; ks < KS; ks++) {
+      const f32x4 m0 = *reinterpret_cast<const f32x4*>(mus + 16 * ks + 8 * g);
+      const f32x4 m1 = *reinterpret_cast<const f32x4*>(mus + 16 * ks + 8 * g + 4);
+#pragma unroll
+      for (int e = 0; e < 8; e++) {
+        const float kp = key_ok ? fast_exp2(((float)kfr[ks][e] - (e < 4 ? m0[e] : m1[e - 4])) * kLog2e - lnz2) : 0.f;
+        kfr[ks][e] = (__bf16)kp;
+      }
+      if (cgrp == 0) *reinterpret_cast<bf16x8*>(kpt + mykey * LD + 16 * ks + 8 * g) = kfr[ks];
     }
-    *reinterpret_cast<bf16x8*>(ktile + t * D + 8 * pc) = x;
   }
   __syncthreads();
-  // dK^phi^T = dH V^T (+ dZ 1^T below) and dV^T += dH^T K^phi^T, both channels x keys
-  f32x16 dkp[TPW];
+  // dK^phi^T = dH V^T (+ dZ 1^T below) and dV^T += dH^T K^phi^T, both channels x keys; V_j and K^phi_j
+  // are the B operands, from registers
+  f32x16 dkp[CT];
 #pragma unroll
-  for (int x = 0; x < TPW; x++)
+  for (int x = 0; x < CT; x++)
 #pragma unroll
     for (int e = 0; e < 16; e++) dkp[x][e] = 0.f;
 #pragma unroll
   for (int ks = 0; ks < KS; ks++) {
-    const bf16x8 ah = row_fragment<PL>(dht, 32 * ct + lane % 32, 16 * ks + 8 * g);   // dH[c][e..]: contraction over e
-    const bf16x8 aht = v_fragment<PL>(dht, ks, 32 * ct, lane);                       // dH^T[e][c..], c in token order
 #pragma unroll
-    for (int x = 0; x < TPW; x++) {
-      const int key = 32 * kh_of(x) + lane % 32;
-      dkp[x] = mfma_bf16(ah, row_fragment<SL>(vtile, key, 16 * ks + 8 * g), dkp[x]);
-      const bf16x4 lo = *reinterpret_cast<const bf16x4*>(ktile + SL::offset(key, 16 * ks + 4 * g));
-      const bf16x4 hi = *reinterpret_cast<const bf16x4*>(ktile + SL::offset(key, 16 * ks + 8 + 4 * g));
-      const bf16x8 bk = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-      dvacc[x] = mfma_bf16(aht, bk, dvacc[x]);
+    for (int x = 0; x < CT; x++) {
+      const int ct = CT * cgrp + x;
+      dkp[x] = mfma_bf16(row_fragment<PL>(dht, 32 * ct + lane % 32, 16 * ks + 8 * g), vfr[ks], dkp[x]);   // over e
+      dvacc[x] = mfma_bf16(nat_fragment<PL>(dht, ks, 32 * ct, lane), kfr[ks], dvacc[x]);                 // over c
     }
   }
   // back through phi: dK' += K^phi (.) (dK^phi - rowsum(dK^phi (.) K^phi)); the row sum spans all channels
-  float kp[TPW][16];
+  float kp[CT][16];
 #pragma unroll
-  for (int x = 0; x < TPW; x++) {
-    const int key = 32 * kh_of(x) + lane % 32;
+  for (int x = 0; x < CT; x++) {
+    const int ct = CT * cgrp + x;
     float part = 0.f;
 #pragma unroll
     for (int v4 = 0; v4 < 4; v4++) {
-      const bf16x4 kk = *reinterpret_cast<const bf16x4*>(ktile + SL::offset(key, 32 * ct + 8 * v4 + 4 * g));
+      const bf16x4 kk = *reinterpret_cast<const bf16x4*>(kpt + mykey * LD + 32 * ct + 8 * v4 + 4 * g);
       const f32x4 dz = *reinterpret_cast<const f32x4*>(dzs + 32 * ct + 8 * v4 + 4 * g);
 #pragma unroll
       for (int r = 0; r < 4; r++) {
@@ -748,27 +719,29 @@ __global__ __launch_bounds__(256, 1) void bwd_kv_mfma_kernel(
       }
     }
     part = half_sum(part);
-    if (g == 0) dred[ct * 64 + key] = part;
+    if (g == 0) dred[ct * 64 + mykey] = part;
   }
   __syncthreads();                                   // row sums complete; every wave is done with the dH and K^phi tiles
   uint16_t* okt = dht;                               // dK' [key][c], then dV [key][e] behind it
   uint16_t* ovt = dht + 64 * LD;
-#pragma unroll
-  for (int x = 0; x < TPW; x++) {
-    const int key = 32 * kh_of(x) + lane % 32;
+  {
     float dot = 0.f;
 #pragma unroll
-    for (int c2 = 0; c2 < ET; c2++) dot += dred[c2 * 64 + key];
+    for (int c2 = 0; c2 < ET; c2++) dot += dred[c2 * 64 + mykey];
 #pragma unroll
-    for (int v4 = 0; v4 < 4; v4++) {
-      bf16x4 pk, pv;
+    for (int x = 0; x < CT; x++) {
+      const int ct = CT * cgrp + x;
 #pragma unroll
-      for (int r = 0; r < 4; r++) {
-        pk[r] = (__bf16)(dkacc[x][4 * v4 + r] * rscale + kp[x][4 * v4 + r] * (dkp[x][4 * v4 + r] - dot));
-        pv[r] = (__bf16)dvacc[x][4 * v4 + r];
+      for (int v4 = 0; v4 < 4; v4++) {
+        bf16x4 pk, pv;
+#pragma unroll
+        for (int r = 0; r < 4; r++) {
+          pk[r] = (__bf16)(dkacc[x][4 * v4 + r] * rscale + kp[x][4 * v4 + r] * (dkp[x][4 * v4 + r] - dot));
+          pv[r] = (__bf16)dvacc[x][4 * v4 + r];
+        }
+        *reinterpret_cast<bf16x4*>(okt + mykey * LD + 32 * ct + 8 * v4 + 4 * g) = pk;
+        *reinterpret_cast<bf16x4*>(ovt + mykey * LD + 32 * ct + 8 * v4 + 4 * g) = pv;
       }
-      *reinterpret_cast<bf16x4*>(okt + key * LD + 32 * ct + 8 * v4 + 4 * g) = pk;
-      *reinterpret_cast<bf16x4*>(ovt + key * LD + 32 * ct + 8 * v4 + 4 * g) = pv;
     }
   }
   __syncthreads();
