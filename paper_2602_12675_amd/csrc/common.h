@@ -93,7 +93,7 @@ struct BwdArgs {
   // scratch.  dh: one d x d slot per query block as bf16 (bf16 tensors) or per 64 query rows as fp32
   float *ds, *lraw, *dz, *dh_total, *dz_total, *colsum, *dk_mean, *dalpha_part;
   void* dh;
-  int32_t *col_ptr, *col_idx;
+  int32_t *col_ptr, *col_idx, *col_cnt;
   uint32_t* mask_bits;                       // M_c as bits, [BH, T_m, ceil(T_n / 32)]
 };
 hipError_t launch_backward(const Shape& s, const BwdArgs& a, hipStream_t stream);

@@ -72,7 +72,7 @@ static int make_shape(const sla2_params* p, Shape* s) {
 
 // scratch of the backward pass, carved out of the `bwd` region of the workspace
 struct BwdLayout {
-  size_t ds, dh, dz, dh_total, dz_total, colsum, dk_mean, dalpha_part, col_ptr, col_idx, mask_bits, h_i, z_i, lraw, total;
+  size_t ds, dh, dz, dh_total, dz_total, colsum, dk_mean, dalpha_part, col_ptr, col_idx, col_cnt, mask_bits, h_i, z_i, lraw, total;
 };
 static BwdLayout make_bwd_layout(const Shape& s) {
   BwdLayout B;
@@ -90,6 +90,7 @@ static BwdLayout make_bwd_layout(const Shape& s) {
   B.dalpha_part = take(slots * sizeof(float));
   B.col_ptr = take(BH * (size_t)(s.Tn + 1) * sizeof(int32_t));
   B.col_idx = take(BH * s.Tm * (size_t)(s.k > 0 ? s.k : 1) * sizeof(int32_t));
+  B.col_cnt = take(BH * (size_t)s.Tn * sizeof(int32_t));
   B.mask_bits = take(BH * s.Tm * (size_t)((s.Tn + 31) / 32) * sizeof(uint32_t));
   // bf16 tensors: the forward kernel leaves H_i^T (bf16) and Z_i per query block here; L on the raw keys
   B.h_i = take(s.bf16 ? BH * s.Tm * d * d * 2 : 0);
@@ -369,7 +370,7 @@ int sla2_backward(const sla2_params* params, const void* q, const void* k, const
   a.colsum = (float*)(bw + B.colsum); a.dk_mean = (float*)(bw + B.dk_mean);
   a.dalpha_part = (float*)(bw + B.dalpha_part);
   a.col_ptr = (int32_t*)(bw + B.col_ptr); a.col_idx = (int32_t*)(bw + B.col_idx);
-  a.mask_bits = (uint32_t*)(bw + B.mask_bits);
+  a.mask_bits = (uint32_t*)(bw + B.mask_bits); a.col_cnt = (int32_t*)(bw + B.col_cnt);
   if (launch_backward(s, a, (hipStream_t)hip_stream) != hipSuccess) return SLA2_EHIP;
   return SLA2_OK;
 }

@@ -40,59 +40,80 @@ __global__ __launch_bounds__(64) void bwd_mask_bits_kernel(const int32_t* __rest
 }
 
 // For every key block j of head bh: the ascending list of query blocks i with M_c[i, j] = 1, as
-// offsets col_ptr[bh][0..T_n] into col_idx[bh][.].  One workgroup per head, one thread per column
-// (two passes over the bit rows, whose words are shared by 32 neighbouring threads).
-constexpr int kTransposeThreads = 1024;
-__global__ __launch_bounds__(kTransposeThreads) void bwd_transpose_kernel(const uint32_t* __restrict__ bits,
-                                                                          int32_t* __restrict__ col_ptr,
-                                                                          int32_t* __restrict__ col_idx, int Tm, int Tn,
-                                                                          int ksel) {
-  constexpr int CPT = kMaxKeyBlocks / kTransposeThreads;   // columns per thread
-  __shared__ int cnt[kMaxKeyBlocks + 1];
+// offsets col_ptr[bh][0..T_n] into col_idx[bh][.].  Three small kernels: column counts, their
+// exclusive scan, and the fill.  Counts and fill run one wave per (head, 32-column word): the wave
+// walks the bit rows 64 at a time, one ballot per column; the rank of a set bit inside the ballot
+// plus the running count of the column is its place in the (ascending) list.
+__global__ __launch_bounds__(64) void bwd_col_count_kernel(const uint32_t* __restrict__ bits, int32_t* __restrict__ counts,
+                                                           int Tm, int Tn) {
+  const int W = (Tn + 31) / 32, x = blockIdx.x, bh = blockIdx.y, lane = threadIdx.x;
+  const uint32_t* rows = bits + (size_t)bh * Tm * W + x;
+  int run[32];
+#pragma unroll
+  for (int b = 0; b < 32; b++) run[b] = 0;
+  for (int i0 = 0; i0 < Tm; i0 += 64) {
+    const int i = i0 + lane;
+    const uint32_t word = i < Tm ? rows[(size_t)i * W] : 0u;
+#pragma unroll
+    for (int b = 0; b < 32; b++) run[b] += __popcll(__ballot((word >> b) & 1u));
+  }
+  int mine = 0;
+#pragma unroll
+  for (int b = 0; b < 32; b++) mine = lane == b ? run[b] : mine;
+  const int j = 32 * x + lane;
+  if (lane < 32 && j < Tn) counts[(size_t)bh * Tn + j] = mine;
+}
+
+__global__ __launch_bounds__(256) void bwd_col_scan_kernel(const int32_t* __restrict__ counts, int32_t* __restrict__ col_ptr,
+                                                           int Tn) {
+  constexpr int PER = kMaxKeyBlocks / 256;
+  __shared__ int part[256];
   const int bh = blockIdx.x, tid = threadIdx.x;
-  const int W = (Tn + 31) / 32;
-  const uint32_t* rows = bits + (size_t)bh * Tm * W;
-  int c[CPT];
+  int v[PER], sum = 0;
 #pragma unroll
-  for (int x = 0; x < CPT; x++) c[x] = 0;
-#pragma unroll 8
-  for (int i = 0; i < Tm; i++) {
-#pragma unroll
-    for (int x = 0; x < CPT; x++) {
-      const int j = tid + kTransposeThreads * x;
-      if (j < Tn) c[x] += (rows[(size_t)i * W + (j >> 5)] >> (j & 31)) & 1u;
-    }
+  for (int y = 0; y < PER; y++) {
+    const int j = tid * PER + y;
+    v[y] = j < Tn ? counts[(size_t)bh * Tn + j] : 0;
+    sum += v[y];
   }
-#pragma unroll
-  for (int x = 0; x < CPT; x++) {
-    const int j = tid + kTransposeThreads * x;
-    if (j < Tn) cnt[j] = c[x];
-  }
+  part[tid] = sum;
   __syncthreads();
-  if (tid == 0) {                                     // exclusive scan, in place
+  if (tid == 0) {                                     // exclusive scan of the 256 partial sums, in place
     int run = 0;
-    for (int j = 0; j < Tn; j++) {
-      const int v = cnt[j];
-      cnt[j] = run;
-      run += v;
+    for (int t = 0; t < 256; t++) {
+      const int c = part[t];
+      part[t] = run;
+      run += c;
     }
-    cnt[Tn] = run;
   }
   __syncthreads();
-  for (int j = tid; j <= Tn; j += kTransposeThreads) col_ptr[(size_t)bh * (Tn + 1) + j] = cnt[j];
-  int pos[CPT];
+  int run = part[tid];
 #pragma unroll
-  for (int x = 0; x < CPT; x++) {
-    const int j = tid + kTransposeThreads * x;
-    pos[x] = j < Tn ? cnt[j] : 0;
+  for (int y = 0; y < PER; y++) {
+    const int j = tid * PER + y;
+    if (j < Tn) col_ptr[(size_t)bh * (Tn + 1) + j] = run;
+    run += v[y];
+    if (j == Tn - 1) col_ptr[(size_t)bh * (Tn + 1) + Tn] = run;
   }
+}
+
+__global__ __launch_bounds__(64) void bwd_col_fill_kernel(const uint32_t* __restrict__ bits, const int32_t* __restrict__ col_ptr,
+                                                          int32_t* __restrict__ col_idx, int Tm, int Tn, int ksel) {
+  const int W = (Tn + 31) / 32, x = blockIdx.x, bh = blockIdx.y, lane = threadIdx.x;
+  const uint32_t* rows = bits + (size_t)bh * Tm * W + x;
   int32_t* out = col_idx + (size_t)bh * Tm * ksel;
-#pragma unroll 8
-  for (int i = 0; i < Tm; i++) {
+  int run[32];
 #pragma unroll
-    for (int x = 0; x < CPT; x++) {
-      const int j = tid + kTransposeThreads * x;
-      if (j < Tn && ((rows[(size_t)i * W + (j >> 5)] >> (j & 31)) & 1u)) out[pos[x]++] = i;
+  for (int b = 0; b < 32; b++) run[b] = 32 * x + b < Tn ? col_ptr[(size_t)bh * (Tn + 1) + 32 * x + b] : 0;
+  const unsigned long long below = (1ull << lane) - 1ull;
+  for (int i0 = 0; i0 < Tm; i0 += 64) {
+    const int i = i0 + lane;
+    const uint32_t word = i < Tm ? rows[(size_t)i * W] : 0u;
+#pragma unroll
+    for (int b = 0; b < 32; b++) {
+      const unsigned long long m = __ballot((word >> b) & 1u);
+      if ((word >> b) & 1u) out[run[b] + __popcll(m & below)] = i;
+      run[b] += __popcll(m);
     }
   }
 }
@@ -715,24 +736,27 @@ __global__ __launch_bounds__(256) void bwd_unsmooth_kernel(T* __restrict__ dk, c
   }
 }
 
-// d alpha: per head [H] (sum over batch, query blocks and parts) or per query block [H, T_m] (batch and parts)
+// d alpha: per head [H] (sum over batch, query blocks and parts) or per query block [H, T_m] (batch and
+// parts).  One workgroup per output; thread t adds the parts t, t + 256, .. and thread 0 the 256 sums.
 __global__ __launch_bounds__(256) void bwd_dalpha_kernel(const float* __restrict__ part, float* __restrict__ dalpha, int B,
                                                          int H, int Tm, int parts, int alpha_per_block) {
-  const int n = alpha_per_block ? H * Tm : H;
-  const int x = blockIdx.x * 256 + threadIdx.x;
-  if (x >= n) return;
+  __shared__ float red[256];
+  const int x = blockIdx.x, tid = threadIdx.x;
   const int h = alpha_per_block ? x / Tm : x;
+  const int per_b = alpha_per_block ? parts : Tm * parts;          // consecutive parts of one batch entry
   float s = 0.f;
-  for (int b = 0; b < B; b++) {
-    const float* p = part + ((size_t)(b * H + h) * Tm) * parts;
-    if (alpha_per_block) {
-      const int i = x % Tm;
-      for (int y = 0; y < parts; y++) s += p[(size_t)i * parts + y];
-    } else {
-      for (int y = 0; y < Tm * parts; y++) s += p[y];
-    }
+  for (int y = tid; y < B * per_b; y += 256) {
+    const int b = y / per_b, z = y % per_b;
+    const size_t first = ((size_t)(b * H + h) * Tm + (alpha_per_block ? x % Tm : 0)) * parts;
+    s += part[first + z];
   }
-  dalpha[x] = s;
+  red[tid] = s;
+  __syncthreads();
+  if (tid == 0) {
+    float t = 0.f;
+    for (int y = 0; y < 256; y++) t += red[y];
+    dalpha[x] = t;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -752,7 +776,12 @@ static hipError_t launch_backward_t(const Shape& s, const BwdArgs& a, hipStream_
   }
   // k = 0: every list is empty and the kernel writes all-zero offsets
   bwd_mask_bits_kernel<<<dim3((unsigned)(s.BH * s.Tm)), 64, 0, stream>>>(a.block_idx, a.mask_bits, s.Tn, s.k);
-  bwd_transpose_kernel<<<dim3((unsigned)s.BH), kTransposeThreads, 0, stream>>>(a.mask_bits, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
+  {
+    const dim3 words((unsigned)((s.Tn + 31) / 32), (unsigned)s.BH);
+    bwd_col_count_kernel<<<words, 64, 0, stream>>>(a.mask_bits, a.col_cnt, s.Tm, s.Tn);
+    bwd_col_scan_kernel<<<dim3((unsigned)s.BH), 256, 0, stream>>>(a.col_cnt, a.col_ptr, s.Tn);
+    bwd_col_fill_kernel<<<words, 64, 0, stream>>>(a.mask_bits, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
+  }
   bwd_q_kernel<T, D><<<dim3((unsigned)((size_t)s.BH * s.Tm * parts)), 256, smem_q, stream>>>(
       (const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.dout, (const T*)a.o_s, (const T*)a.o_l, a.lse, a.k_mean,
       a.k_stats, a.h_total, a.z_total, a.block_idx, a.alpha, (T*)a.dq, a.ds, (float*)a.dh, a.dz, a.dalpha_part, s.sin,
@@ -771,7 +800,7 @@ static hipError_t launch_backward_t(const Shape& s, const BwdArgs& a, hipStream_
         (T*)a.dk, a.dk_mean, s.sin, s.H, s.N, D);
   }
   const int n_alpha = s.alpha_per_block ? s.H * s.Tm : s.H;
-  bwd_dalpha_kernel<<<dim3((unsigned)((n_alpha + 255) / 256)), 256, 0, stream>>>(a.dalpha_part, a.dalpha, s.B, s.H, s.Tm,
+  bwd_dalpha_kernel<<<dim3((unsigned)n_alpha), 256, 0, stream>>>(a.dalpha_part, a.dalpha, s.B, s.H, s.Tm,
                                                                                  parts, s.alpha_per_block ? 1 : 0);
   return hipGetLastError();
 }
@@ -781,7 +810,12 @@ static hipError_t launch_backward_t(const Shape& s, const BwdArgs& a, hipStream_
 static hipError_t launch_backward_bf16(const Shape& s, const BwdArgs& a, hipStream_t stream) {
   const int D = s.d;
   bwd_mask_bits_kernel<<<dim3((unsigned)(s.BH * s.Tm)), 64, 0, stream>>>(a.block_idx, a.mask_bits, s.Tn, s.k);
-  bwd_transpose_kernel<<<dim3((unsigned)s.BH), kTransposeThreads, 0, stream>>>(a.mask_bits, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
+  {
+    const dim3 words((unsigned)((s.Tn + 31) / 32), (unsigned)s.BH);
+    bwd_col_count_kernel<<<words, 64, 0, stream>>>(a.mask_bits, a.col_cnt, s.Tm, s.Tn);
+    bwd_col_scan_kernel<<<dim3((unsigned)s.BH), 256, 0, stream>>>(a.col_cnt, a.col_ptr, s.Tn);
+    bwd_col_fill_kernel<<<words, 64, 0, stream>>>(a.mask_bits, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
+  }
   hipError_t e = launch_bwd_q_bf16(s, a, stream);
   if (e != hipSuccess) return e;
   bwd_sum_kernel<uint16_t><<<dim3((unsigned)((D * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
@@ -795,7 +829,7 @@ static hipError_t launch_backward_bf16(const Shape& s, const BwdArgs& a, hipStre
         (uint16_t*)a.dk, a.dk_mean, s.sin, s.H, s.N, D);
   }
   const int n_alpha = s.alpha_per_block ? s.H * s.Tm : s.H;
-  bwd_dalpha_kernel<<<dim3((unsigned)((n_alpha + 255) / 256)), 256, 0, stream>>>(a.dalpha_part, a.dalpha, s.B, s.H, s.Tm, 1,
+  bwd_dalpha_kernel<<<dim3((unsigned)n_alpha), 256, 0, stream>>>(a.dalpha_part, a.dalpha, s.B, s.H, s.Tm, 1,
                                                                                  s.alpha_per_block ? 1 : 0);
   return hipGetLastError();
 }

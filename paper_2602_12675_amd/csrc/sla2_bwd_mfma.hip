@@ -18,6 +18,8 @@
 //                dH = dH_total - sum over those query blocks of dH_i (Alg. 3's M_c[i, j] = 0 sum, by
 //                complement), dK^phi^T = dH V^T + dZ 1^T, dV^T += dH^T K^phi^T,
 //                dK' += softmax-backward(dK^phi).
+#include <type_traits>
+
 #include "mfma_tiles.h"
 
 namespace sla2 {
@@ -27,8 +29,8 @@ template <int D, int BQ> struct BwdQSmem {
   static constexpr int kLd = D + 8;
   static constexpr int kTile = SwizzledLayout<D>::kTileBytes;                  // one 64 x D bf16 tile
   static constexpr int kLoopBytes = 4 * kTile;                                 // two buffers of (K, V)
-  static constexpr int kEpiA = (D > BQ ? D : BQ) * kLd * 2;                    // H_i^T [D][kLd], later w [BQ][kLd]
-  static constexpr int kEpiB = BQ * kLd * 2;                                   // dQ tile, later dO^l [BQ][kLd]
+  static constexpr int kEpiA = (D > BQ ? D : BQ) * kLd * 2;                    // H_i^T [D][kLd], the dQ tile, dO [BQ][kLd]
+  static constexpr int kEpiB = BQ * kLd * 2;                                   // w [BQ][kLd]
   static constexpr int kTiles = kLoopBytes > kEpiA + kEpiB ? kLoopBytes : kEpiA + kEpiB;
   static constexpr int kZsOff = kTiles;                                        // float [D]   Z_i
   static constexpr int kMuOff = kZsOff + D * 4;                                // float [D]   colmean(K)
@@ -77,7 +79,11 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
   const uint16_t* doh = dout + head_offset(sout, bh, H);
   const int tok_stride = sin.n;
   const int32_t* sel = block_idx + ((size_t)bh * Tm + i) * ksel;
+#ifdef SLA2_EXP_Q_NO_LOOP
+  const int ntiles = 0;
+#else
   const int ntiles = ksel;
+#endif
   const float al = alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
   const float rscale = rsqrtf((float)D);
   const size_t slot = (size_t)bh * Tm + i;
@@ -91,8 +97,8 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
   if (ntiles > 0) dma(j_cur, 0);
   if (tid < D) mus[tid] = (float)k_mean[(size_t)bh * D + tid];
 
-  // ---- prologue: Q and dO^s = alpha dO as B-operand fragments; D^s, D^l, the d alpha part ----
-  bf16x8 qf[KS], dof[KS];
+  // ---- prologue: Q and dO as B-operand fragments (alpha is applied to the products); D^s, D^l, the d alpha part ----
+  bf16x8 qf[KS], gof[KS];
   float Ds = 0.f, Dl = 0.f, mix = 0.f;
   {
     const uint16_t* qsrc = qh + (size_t)(row0 + r_ld) * tok_stride + 8 * g;
@@ -102,16 +108,15 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
       qf[ks] = *reinterpret_cast<const bf16x8*>(qsrc + 16 * ks);
-      const bf16x8 go = *reinterpret_cast<const bf16x8*>(gsrc + 16 * ks);
+      gof[ks] = *reinterpret_cast<const bf16x8*>(gsrc + 16 * ks);
       const bf16x8 os = *reinterpret_cast<const bf16x8*>(ossrc + 16 * ks);
       const bf16x8 ol = *reinterpret_cast<const bf16x8*>(olsrc + 16 * ks);
 #pragma unroll
       for (int e = 0; e < 8; e++) {
-        const float gv = (float)go[e], osv = (float)os[e], olv = (float)ol[e];
+        const float gv = (float)gof[ks][e], osv = (float)os[e], olv = (float)ol[e];
         Ds += al * gv * osv;
         Dl += (1.f - al) * gv * olv;
         mix += gv * (osv - olv);
-        dof[ks][e] = (__bf16)(al * gv);
       }
     }
   }
@@ -148,6 +153,13 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
     lraw_out[(size_t)bh * N + row0 + qrow] = L2;      // as the key-side kernel uses it: L on the raw keys, times log2(e)
   }
 
+  // LDS byte offsets of this lane's operand reads inside a K or V tile: row-wise reads (key row
+  // l % 32, channel step ks at (offset of step 0) ^ 32 ks) and transposing reads (cf. read_tr4)
+  const unsigned b_off = (unsigned)SL::offset(lane % 32, 8 * g) * 2;
+  unsigned a_off[ET];
+#pragma unroll
+  for (int et = 0; et < ET; et++)
+    a_off[et] = (unsigned)SL::offset(4 * g + (lane % 16) / 4, 32 * et + 16 * ((lane / 16) % 2) + 4 * (lane % 4)) * 2;
   f32x16 dqacc[ET];
 #pragma unroll
   for (int et = 0; et < ET; et++)
@@ -163,48 +175,82 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
     if (s + 1 < ntiles) dma(j_nxt, buf ^ 1);
     j_cur = j_nxt;
     j_nxt = j_nn;
-    const uint16_t* kt = kbuf(buf);
-    const uint16_t* vt = vbuf(buf);
+    const unsigned ka = lds_address(kbuf(buf)), va = lds_address(vbuf(buf));
     f32x16 sacc[2], dpacc[2];
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
 #pragma unroll
       for (int e = 0; e < 16; e++) { sacc[mt][e] = 0.f; dpacc[mt][e] = 0.f; }
-    // S^T = K Q^T and dP^T = V dO^s^T (keys x query rows), two 32-key halves
+    // S^T = K Q^T and dP^T = V dO^T (keys x query rows; alpha joins below), two 32-key halves each.  One operand read
+    // (16 bytes of key row 32 mt + l % 32) per product, issued untracked and kept kAhead deep in flight:
+    // a tracked read would be waited for right before its product, one LDS round trip per product.
+    {
+      constexpr int kItems = 4 * KS, kAhead = 6, kSlots = kAhead + 1;
+      u32x4 ring[kSlots];
+      auto issue = [&](int n) {                      // item n: (K | V, key half, channel step)
+        const int grp = n / KS, ks = n % KS;
+        const unsigned base = (grp < 2 ? ka : va) + b_off;
+        if (grp % 2 == 0) ring[n % kSlots] = lds_read16_untracked<0>(base ^ (32u * ks));
+        else ring[n % kSlots] = lds_read16_untracked<32 * D * 2>(base ^ (32u * ks));
+      };
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++)
+      for (int n = 0; n < kAhead; n++) issue(n);
 #pragma unroll
-      for (int mt = 0; mt < 2; mt++)
-        sacc[mt] = mfma_bf16(row_fragment<SL>(kt, 32 * mt + lane % 32, 16 * ks + 8 * g), qf[ks], sacc[mt]);
-#pragma unroll
-    for (int ks = 0; ks < KS; ks++)
-#pragma unroll
-      for (int mt = 0; mt < 2; mt++)
-        dpacc[mt] = mfma_bf16(row_fragment<SL>(vt, 32 * mt + lane % 32, 16 * ks + 8 * g), dof[ks], dpacc[mt]);
-    // dS^T = P^T (.) (dP^T - D^s), as B-operand fragments in token order
+      for (int n = 0; n < kItems; n++) {
+        if (n + kAhead < kItems) issue(n + kAhead);
+        wait_lgkmcnt(n + kAhead < kItems ? kAhead : kItems - 1 - n);
+        settle(ring[n % kSlots]);
+        const bf16x8 a = __builtin_bit_cast(bf16x8, ring[n % kSlots]);
+        const int grp = n / KS, ks = n % KS;
+        if (grp < 2) sacc[grp] = mfma_bf16(a, qf[ks], sacc[grp]);
+        else dpacc[grp - 2] = mfma_bf16(a, gof[ks], dpacc[grp - 2]);
+      }
+    }
+    // dS^T = P^T (.) (alpha dP^T - D^s), as B-operand fragments in token order
     bf16x8 dsf[4];
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
 #pragma unroll
       for (int e = 0; e < 16; e++) {
-        float p = fast_exp2(sacc[mt][e] * c0 - L2);
-        if (32 * mt + 8 * (e / 4) + 4 * g + e % 4 >= valid) p = 0.f;
-        const float dsv = p * (dpacc[mt][e] - Ds);
+        float arg = sacc[mt][e] * c0 - L2;
+        if (valid < kTileTokens) arg = 32 * mt + 8 * (e / 4) + 4 * g + e % 4 >= valid ? -INFINITY : arg;
+        const float dsv = fast_exp2(arg) * (al * dpacc[mt][e] - Ds);
         sumds += dsv;
         dsf[2 * mt + e / 8][e % 8] = (__bf16)dsv;
       }
-    // dQ^T += K^T dS^T
+    // dQ^T += K^T dS^T: transposing reads of the K tile, those of the next 16-token step in flight
+    // while the products of this one run
+    {
+      constexpr int kReads = 2 * ET;
+      u32x2 rk[2][ET][2];
+      auto issue = [&](int ks, int slot) {
 #pragma unroll
-    for (int ks = 0; ks < kTileTokens / 16; ks++)
+        for (int et = 0; et < ET; et++)
 #pragma unroll
-      for (int et = 0; et < ET; et++) dqacc[et] = mfma_bf16(v_fragment<SL>(kt, ks, 32 * et, lane), dsf[ks], dqacc[et]);
+          for (int hi = 0; hi < 2; hi++) rk[slot][et][hi] = lds_read_tr_untracked_at<16 * D>(ka + a_off[et], 2 * ks + hi);
+      };
+      issue(0, 0);
+#pragma unroll
+      for (int ks = 0; ks < kTileTokens / 16; ks++) {
+        const int slot = ks & 1;
+        if (ks + 1 < kTileTokens / 16) issue(ks + 1, slot ^ 1);
+        wait_lgkmcnt(ks + 1 < kTileTokens / 16 ? kReads : 0);
+#pragma unroll
+        for (int et = 0; et < ET; et++) {
+          settle(rk[slot][et][0]);
+          settle(rk[slot][et][1]);
+          const u32x4 v4 = {rk[slot][et][0][0], rk[slot][et][0][1], rk[slot][et][1][0], rk[slot][et][1][1]};
+          dqacc[et] = mfma_bf16(__builtin_bit_cast(bf16x8, v4), dsf[ks], dqacc[et]);
+        }
+      }
+    }
     __builtin_amdgcn_s_waitcnt(kVmcnt0);             // the next tile has landed in LDS ...
     __syncthreads();                                 // ... for everyone, and this tile's buffer is free
   }
 
   // ================= epilogue =================
-  uint16_t* ta = reinterpret_cast<uint16_t*>(smem);                 // H_i^T [e][c], later w [row][c]
-  uint16_t* tb = reinterpret_cast<uint16_t*>(smem + SM::kEpiA);     // dQ [row][c], later dO^l [row][e]
+  uint16_t* ta = reinterpret_cast<uint16_t*>(smem);                 // H_i^T [e][c]; then the dQ tile; then dO [row][e]
+  uint16_t* tb = reinterpret_cast<uint16_t*>(smem + SM::kEpiA);     // w = Q^phi / (Q^phi Z_i) as [row][c]
   // dS K' = dS K - rowsum(dS) colmean(K)^T
   sumds = half_sum(sumds);
 #pragma unroll
@@ -223,85 +269,76 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
     }
     if (tid < D) zs[tid] = z_i[slot * D + tid];
   }
-  // Q^phi = softmax_d(Q) of this lane's row in the layout of the accumulators: channel
-  // 32 et + 8 (v / 4) + 4 g + v % 4 at [et][v]
-  f32x16 qp[ET];
-  {
-    const uint16_t* qsrc = qh + (size_t)(row0 + r_ld) * tok_stride + 4 * g;
-    float qm = -INFINITY;
+  // Q^phi = softmax_d(Q) of this lane's row from the Q fragments (channels 16 ks + 8 g + 0..7); the
+  // fragments are overwritten with exp(q - max), the normalisation is applied where they are used
+  // (the fragments are made opaque first: the widened copies that the prologue made of them would
+  // otherwise be kept alive across the whole main loop for reuse here)
 #pragma unroll
-    for (int et = 0; et < ET; et++)
+  for (int ks = 0; ks < KS; ks++) settle(qf[ks]);
+  float qm = -INFINITY;
 #pragma unroll
-      for (int v4 = 0; v4 < 4; v4++) {
-        const bf16x4 x = *reinterpret_cast<const bf16x4*>(qsrc + 32 * et + 8 * v4);
+  for (int ks = 0; ks < KS; ks++)
 #pragma unroll
-        for (int r = 0; r < 4; r++) {
-          qp[et][4 * v4 + r] = (float)x[r];
-          qm = fmaxf(qm, qp[et][4 * v4 + r]);
-        }
-      }
-    qm = half_max(qm);
-    float qs = 0.f;
+    for (int e = 0; e < 8; e++) qm = fmaxf(qm, (float)qf[ks][e]);
+  qm = half_max(qm);
+  float qs = 0.f;
 #pragma unroll
-    for (int et = 0; et < ET; et++)
+  for (int ks = 0; ks < KS; ks++)
 #pragma unroll
-      for (int e = 0; e < 16; e++) {
-        qp[et][e] = fast_exp2((qp[et][e] - qm) * kLog2e);
-        qs += qp[et][e];
-      }
-    qs = half_sum(qs);
-    const float qinv = 1.f / qs;
-#pragma unroll
-    for (int et = 0; et < ET; et++)
-#pragma unroll
-      for (int e = 0; e < 16; e++) qp[et][e] *= qinv;
-  }
+    for (int e = 0; e < 8; e++) {
+      const float x = fast_exp2(((float)qf[ks][e] - qm) * kLog2e);
+      qs += x;
+      qf[ks][e] = (__bf16)x;
+    }
+  qs = half_sum(qs);
+  const float qinv = 1.f / qs;
   __syncthreads();                                   // H_i^T and Z_i visible
   float den = 0.f;
 #pragma unroll
-  for (int et = 0; et < ET; et++)
+  for (int ks = 0; ks < KS; ks++) {
+    const f32x4 z0 = *reinterpret_cast<const f32x4*>(zs + 16 * ks + 8 * g);
+    const f32x4 z1 = *reinterpret_cast<const f32x4*>(zs + 16 * ks + 8 * g + 4);
 #pragma unroll
-    for (int v4 = 0; v4 < 4; v4++) {
-      const f32x4 z = *reinterpret_cast<const f32x4*>(zs + 32 * et + 8 * v4 + 4 * g);
-#pragma unroll
-      for (int r = 0; r < 4; r++) den += qp[et][4 * v4 + r] * z[r];
-    }
-  den = half_sum(den);
+    for (int e = 0; e < 8; e++) den += (float)qf[ks][e] * (e < 4 ? z0[e] : z1[e - 4]);
+  }
+  den = half_sum(den) * qinv;
   // every block selected: the linear branch receives and passes no gradient
   const float inv_den = (ksel >= Tn || !row_ok) ? 0.f : 1.f / den;
-  // dQ^phi^T = H_i dO^l^T: A = H_i read transposed out of the H_i^T tile (contraction index e in token
-  // order), B = dO^l of this lane's row in that same order
+  // w as a [row][c] tile (zero rows past the end); the softmax-backward step reads Q^phi = w den back
+  // from it in the layout of the accumulators
+  {
+    const float wscale = qinv * inv_den;
+#pragma unroll
+    for (int ks = 0; ks < KS; ks++) {
+      bf16x8 wv;
+#pragma unroll
+      for (int e = 0; e < 8; e++) wv[e] = (__bf16)((float)qf[ks][e] * wscale);
+      *reinterpret_cast<bf16x8*>(tb + qrow * LD + 16 * ks + 8 * g) = wv;
+    }
+  }
+  if (g == 0) dls[qrow] = Dl;
+  // dQ^phi^T = (1 - alpha) H_i dO^T: A = H_i read transposed out of the H_i^T tile, B = the dO fragments
   f32x16 dqp[ET];
 #pragma unroll
   for (int ct = 0; ct < ET; ct++)
 #pragma unroll
     for (int e = 0; e < 16; e++) dqp[ct][e] = 0.f;
-  {
-    const uint16_t* gsrc = doh + (size_t)(row0 + r_ld) * sout.n + 4 * g;
 #pragma unroll
-    for (int ks = 0; ks < KS; ks++) {
-      const bf16x4 lo = *reinterpret_cast<const bf16x4*>(gsrc + 16 * ks);
-      const bf16x4 hi = *reinterpret_cast<const bf16x4*>(gsrc + 16 * ks + 8);
-      bf16x8 dol;
+  for (int ks = 0; ks < KS; ks++)
 #pragma unroll
-      for (int r = 0; r < 4; r++) {
-        dol[r] = (__bf16)((1.f - al) * (float)lo[r]);
-        dol[4 + r] = (__bf16)((1.f - al) * (float)hi[r]);
-      }
-#pragma unroll
-      for (int ct = 0; ct < ET; ct++) dqp[ct] = mfma_bf16(v_fragment<PL>(ta, ks, 32 * ct, lane), dol, dqp[ct]);
-    }
-  }
+    for (int ct = 0; ct < ET; ct++) dqp[ct] = mfma_bf16(nat_fragment<PL>(ta, ks, 32 * ct, lane), gof[ks], dqp[ct]);
+  __syncthreads();                                   // w complete; nobody reads H_i^T any more
   float dot = 0.f;
 #pragma unroll
   for (int ct = 0; ct < ET; ct++)
 #pragma unroll
     for (int v4 = 0; v4 < 4; v4++) {
       const f32x4 z = *reinterpret_cast<const f32x4*>(zs + 32 * ct + 8 * v4 + 4 * g);
+      const bf16x4 wq = *reinterpret_cast<const bf16x4*>(tb + qrow * LD + 32 * ct + 8 * v4 + 4 * g);
 #pragma unroll
       for (int r = 0; r < 4; r++) {
-        dqp[ct][4 * v4 + r] = (dqp[ct][4 * v4 + r] - Dl * z[r]) * inv_den;
-        dot += dqp[ct][4 * v4 + r] * qp[ct][4 * v4 + r];
+        dqp[ct][4 * v4 + r] = ((1.f - al) * dqp[ct][4 * v4 + r] - Dl * z[r]) * inv_den;
+        dot += dqp[ct][4 * v4 + r] * ((float)wq[r] * den);
       }
     }
   dot = half_sum(dot);
@@ -310,43 +347,27 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
   for (int et = 0; et < ET; et++)
 #pragma unroll
     for (int v4 = 0; v4 < 4; v4++) {
+      const bf16x4 wq = *reinterpret_cast<const bf16x4*>(tb + qrow * LD + 32 * et + 8 * v4 + 4 * g);
       bf16x4 pk;
 #pragma unroll
       for (int r = 0; r < 4; r++)
-        pk[r] = (__bf16)(dqacc[et][4 * v4 + r] + qp[et][4 * v4 + r] * (dqp[et][4 * v4 + r] - dot));
-      *reinterpret_cast<bf16x4*>(tb + qrow * LD + 32 * et + 8 * v4 + 4 * g) = pk;
+        pk[r] = (__bf16)(dqacc[et][4 * v4 + r] + (float)wq[r] * den * (dqp[et][4 * v4 + r] - dot));
+      *reinterpret_cast<bf16x4*>(ta + qrow * LD + 32 * et + 8 * v4 + 4 * g) = pk;
     }
-  __syncthreads();                                   // dQ tile complete; nobody reads H_i^T any more
+  __syncthreads();                                   // dQ tile complete
   {
     uint16_t* dst = dq + head_offset(sin, bh, H) + (size_t)row0 * tok_stride;
     for (int idx = tid; idx < BQ * (D / 8); idx += NT) {
       const int r = idx / (D / 8), ch = idx % (D / 8);
       if (r < rows_valid)
-        *reinterpret_cast<u32x4*>(dst + (size_t)r * tok_stride + 8 * ch) = *reinterpret_cast<const u32x4*>(tb + r * LD + 8 * ch);
+        *reinterpret_cast<u32x4*>(dst + (size_t)r * tok_stride + 8 * ch) = *reinterpret_cast<const u32x4*>(ta + r * LD + 8 * ch);
     }
   }
-  // w = Q^phi / (Q^phi Z_i) as a [row][c] tile (zero rows past the end)
-#pragma unroll
-  for (int et = 0; et < ET; et++)
-#pragma unroll
-    for (int v4 = 0; v4 < 4; v4++) {
-      bf16x4 pk;
-#pragma unroll
-      for (int r = 0; r < 4; r++) pk[r] = (__bf16)(qp[et][4 * v4 + r] * inv_den);
-      *reinterpret_cast<bf16x4*>(ta + qrow * LD + 32 * et + 8 * v4 + 4 * g) = pk;
-    }
-  if (g == 0) dls[qrow] = Dl;
   __syncthreads();                                   // the dQ tile has been read out
-  for (int idx = tid; idx < BQ * (D / 8); idx += NT) {   // dO^l = (1 - alpha) dO as a [row][e] tile
-    const int r = idx / (D / 8), ch = idx % (D / 8);
-    const bf16x8 x = *reinterpret_cast<const bf16x8*>(doh + (size_t)(row0 + min(r, rows_valid - 1)) * sout.n + 8 * ch);
-    bf16x8 y;
 #pragma unroll
-    for (int e = 0; e < 8; e++) y[e] = (__bf16)((1.f - al) * (float)x[e]);
-    *reinterpret_cast<bf16x8*>(tb + r * LD + 8 * ch) = y;
-  }
+  for (int ks = 0; ks < KS; ks++) *reinterpret_cast<bf16x8*>(ta + qrow * LD + 16 * ks + 8 * g) = gof[ks];   // dO as [row][e]
   __syncthreads();
-  // dH_i[c][e] = sum_r w[r][c] dO^l[r][e]: both operands read transposed, contraction over the rows
+  // dH_i[c][e] = (1 - alpha) sum_r w[r][c] dO[r][e]: both operands read transposed, contraction over the rows
   constexpr int kTilesPerWave = ET * ET / NW;
   static_assert(kTilesPerWave >= 1, "unsupported split");
   uint16_t* dh_slot = dh_out + slot * D * D;
@@ -358,14 +379,14 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
     for (int e = 0; e < 16; e++) acc[e] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < BQ / 16; ks++)
-      acc = mfma_bf16(v_fragment<PL>(ta, ks, 32 * ct, lane), v_fragment<PL>(tb, ks, 32 * et, lane), acc);
+      acc = mfma_bf16(v_fragment<PL>(tb, ks, 32 * ct, lane), v_fragment<PL>(ta, ks, 32 * et, lane), acc);
 #pragma unroll
     for (int e = 0; e < 16; e++)
-      dh_slot[(32 * ct + 8 * (e / 4) + 4 * g + e % 4) * D + 32 * et + lane % 32] = f32_to_bf16_bits(acc[e]);
+      dh_slot[(32 * ct + 8 * (e / 4) + 4 * g + e % 4) * D + 32 * et + lane % 32] = f32_to_bf16_bits((1.f - al) * acc[e]);
   }
   if (tid < D) {                                     // dZ_i[c] = -sum_r w[r][c] D^l_r
     float dz = 0.f;
-    for (int r = 0; r < BQ; r++) dz -= bf16_bits_to_f32(ta[r * LD + tid]) * dls[r];
+    for (int r = 0; r < BQ; r++) dz -= bf16_bits_to_f32(tb[r * LD + tid]) * dls[r];
     dz_out[slot * D + tid] = dz;
   }
 }
@@ -571,20 +592,26 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_mfma_kernel(
     // alpha P and dS = P (.) (alpha dP - D^s), as B-operand fragments over the 64 rows (token order);
     // masked entries get exp2(-inf) = 0
     bf16x8 pf[4], dsf[4];
+    auto probabilities = [&](auto masked) {          // masked: a short key block or a short last row block
 #pragma unroll
-    for (int rh = 0; rh < 2; rh++)
+      for (int rh = 0; rh < 2; rh++)
 #pragma unroll
-      for (int v4 = 0; v4 < 4; v4++) {
-        const f32x4 l4 = *reinterpret_cast<const f32x4*>(st_l + 32 * rh + 8 * v4 + 4 * g);
-        const f32x4 d4 = *reinterpret_cast<const f32x4*>(st_l + 64 + 32 * rh + 8 * v4 + 4 * g);
+        for (int v4 = 0; v4 < 4; v4++) {
+          const f32x4 l4 = *reinterpret_cast<const f32x4*>(st_l + 32 * rh + 8 * v4 + 4 * g);
+          const f32x4 d4 = *reinterpret_cast<const f32x4*>(st_l + 64 + 32 * rh + 8 * v4 + 4 * g);
 #pragma unroll
-        for (int r = 0; r < 4; r++) {
-          const bool off_end = !key_ok || 32 * rh + 8 * v4 + 4 * g + r >= cur.rows;
-          const float p = fast_exp2(off_end ? -INFINITY : sacc[rh][4 * v4 + r] * c0 - l4[r]);
-          pf[2 * rh + v4 / 2][4 * (v4 % 2) + r] = (__bf16)(cur.al * p);
-          dsf[2 * rh + v4 / 2][4 * (v4 % 2) + r] = (__bf16)(p * (cur.al * dpacc[rh][4 * v4 + r] - d4[r]));
+          for (int r = 0; r < 4; r++) {
+            float arg = sacc[rh][4 * v4 + r] * c0 - l4[r];
+            if constexpr (decltype(masked)::value)
+              arg = (!key_ok || 32 * rh + 8 * v4 + 4 * g + r >= cur.rows) ? -INFINITY : arg;
+            const float p = fast_exp2(arg);
+            pf[2 * rh + v4 / 2][4 * (v4 % 2) + r] = (__bf16)(cur.al * p);
+            dsf[2 * rh + v4 / 2][4 * (v4 % 2) + r] = (__bf16)(p * (cur.al * dpacc[rh][4 * v4 + r] - d4[r]));
+          }
         }
-      }
+    };
+    if (cur.rows < 64 || valid < kTileTokens) probabilities(std::true_type{});
+    else probabilities(std::false_type{});
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");   // nothing tracked is in flight when the counted reads below start
     // dV^T += dO^T (alpha P), dK'^T += Q^T dS: contraction over the 64 rows of the step; the operand
     // reads of the next 16-row step are in flight while the products of this one run
