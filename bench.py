@@ -41,6 +41,7 @@ def parse():
                     help="q, k, v as slices of one [B, N, 3, H, d] tensor and out as [B, N, H, d], passed by strides")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-backward", action="store_true", help="skip the forward-for-training + backward timing")
     ap.add_argument("--cpu-heads", type=int, default=6, help="heads of the workload the oracle is timed on")
     ap.add_argument("--event-stride", type=int, default=1,
                     help="bracket the dominant kernel with HIP events on every n-th timed step")
@@ -85,6 +86,47 @@ def cpu_baseline(inp, heads):
     return {"value": flops / dt / 1e12, "unit": "TFLOP/s (dense-equivalent)", "cores": int(cores), "kind": "oracle",
             "sample": "%d of %d heads of the same workload, all query blocks, %.1f s; ms per full call extrapolated: %.0f"
                       % (heads, w.B * w.H, dt, dt / heads * w.B * w.H * 1e3)}
+
+
+def backward_timing(api, W, torch, w, inp, dt, qm, tensors, rw, al, stream, ksel, reps=20):
+    """Times sla2_forward with SLA2_FLAG_SAVE_FOR_BACKWARD and sla2_backward on the bench workload (contiguous
+    layout).  Not part of `value`; a reported figure for the training path (Alg. 3)."""
+    import numpy as np
+    p = api.make_params(w.B, w.H, w.N, w.d, w.block_q, w.block_kv, w.topk_frac, dtype=dt, quant_mode=qm,
+                        flags=api.SLA2_FLAG_SAVE_FOR_BACKWARD)
+    q, k, v, _ = tensors
+    if not q.is_contiguous():
+        q, k, v = (api.to_device(a, dt) for a in (inp.q, inp.k, inp.v))
+    out = torch.empty_like(q)
+    g = np.random.default_rng(7).normal(size=inp.q.shape).astype(np.float32)
+    dout = api.to_device(W.f32_to_bf16_bits(g) if w.dtype == "bf16" else g, dt)
+    dq, dk, dv = (torch.empty_like(q) for _ in range(3))
+    dal = torch.empty_like(al)
+    ws = api.alloc_workspace(p)
+
+    def timed(f):
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            f()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps * 1e3
+
+    fwd_ms = timed(lambda: api.sla2_forward(p, q, k, v, rw, al, out, workspace=ws, stream=stream))
+    bwd_ms = timed(lambda: api.sla2_backward(p, q, k, v, al, dout, dq, dk, dv, dal, ws, stream=stream))
+    BH = w.B * w.H
+    pair = 2.0 * w.block_q * w.block_kv * w.d                   # one product over a (query block, key block) pair
+    # S, dP, dQ, dK, dV per selected pair; dQ^phi and dH_i per query block; dK^phi and the linear dV per key block
+    flops = BH * (w.T_m * ksel * 5.0 * pair + w.T_m * 2 * 2.0 * w.block_q * w.d * w.d + w.T_n * 2 * 2.0 * w.block_kv * w.d * w.d)
+    tf = flops / (bwd_ms * 1e-3) / 1e12
+    res = {"ms": round(bwd_ms, 4), "forward_saving_ms": round(fwd_ms, 4), "algorithmic_flops": flops,
+           "TFLOP/s": round(tf, 1), "dtype": "bf16 MFMA products, fp32 elsewhere" if w.dtype == "bf16" else "f32",
+           "workspace_bytes": int(ws.numel())}
+    if w.dtype == "bf16":
+        res["frac_of_bf16_mfma_peak"] = round(tf / MFMA_PEAK_TFLOPS["bf16"], 4)
+    return res
 
 
 def main():
@@ -227,6 +269,8 @@ def main():
         line["dense_bf16"] = {"ms": round(dense_ms, 3), "TFLOP/s": round(dense_flops / (dense_ms * 1e-3) / 1e12, 1),
                               "frac_of_mfma_peak": round(dense_flops / (dense_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4)}
         line["speedup_vs_dense_bf16"] = round(dense_ms / ms_per_step, 2)
+    if not args.no_backward:
+        line["backward"] = backward_timing(api, W, torch, w, inp, dt, qm, sets[0], rw, al, stream, ksel)
     line["paper_context"] = "paper: 97 % sparsity, 18.6x attention speed-up over FlashAttn2 on an RTX5090 (other hardware; not a target)"
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(inp, max(1, min(args.cpu_heads, w.H)))
