@@ -124,7 +124,8 @@ typedef struct sla2_ws_layout {
   size_t o_s;       /* dtype  [BH, N, d]     sparse-branch output O^s, before the mix of Eq. 13   (input of Alg. 3) */
   size_t o_l;       /* dtype  [BH, N, d]     linear-branch output O^l */
   size_t lse;       /* float  [BH, N]        L_i of Alg. 2 (log-sum-exp of the kept scores; -inf when k = 0) */
-  size_t bwd;       /* scratch of sla2_backward */
+  size_t bwd;       /* scratch of sla2_backward; for bf16 tensors sla2_forward also leaves the state of the
+                       linear branch of every query block here (H_i^T as bf16, Z_i) */
   size_t total;     /* = sla2_workspace_bytes() */
 } sla2_ws_layout;
 
@@ -176,8 +177,10 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
 
 /* Backward pass (Alg. 3 of the appendix, plus the steps it leaves to automatic differentiation: phi,
  * the smoothing of K, the mix of Eq. 13): gradients of q, k, v and alpha for the block mask of the
- * matching forward call (hard Top-k passes no gradient to the router, Sec. 6.1).  Taken in fp32
- * arithmetic from the original q, k, v whatever quant_mode the forward ran in (Sec. 5).
+ * matching forward call (hard Top-k passes no gradient to the router, Sec. 6.1).  Taken from the
+ * original q, k, v whatever quant_mode the forward ran in (Sec. 5): fp32 arithmetic for fp32 tensors;
+ * for bf16 tensors the products run on the matrix cores (bf16 operands, fp32 accumulation) and
+ * everything between them is fp32.
  *   params     the params of the forward call, SLA2_FLAG_SAVE_FOR_BACKWARD set
  *   workspace  the workspace of that forward call, untouched since: it holds the block lists, the
  *              per-token and per-head statistics of K, O^s, O^l and L
