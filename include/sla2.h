@@ -186,7 +186,8 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
  *              per-token and per-head statistics of K, O^s, O^l and L
  *   q, k, v, alpha   as in the forward call;  dout: gradient of out, layout of out (out_stride)
  *   dq, dk, dv       written; element type and layout of q, k, v (in_stride); must not overlap
- *                    each other or any input
+ *                    each other or any input (they may be the slices of one packed [B, N, x, H, d]
+ *                    buffer: interleaved, sharing no element)
  *   dalpha           DEVICE float [H] or [H, T_m] (alpha_per_block), written
  * Deterministic (no atomics).  Errors as sla2_forward; SLA2_EINVAL without the flag. */
 int sla2_backward(const sla2_params* params, const void* q, const void* k, const void* v, const float* alpha,

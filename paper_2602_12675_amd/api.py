@@ -170,8 +170,10 @@ def sla2_forward(params, q, k, v, router_w, alpha, out, block_idx=None, lse=None
     return rc
 
 
-def sla2_backward(params, q, k, v, alpha, dout, dq, dk, dv, dalpha, workspace, stream=None, check=True) -> int:
-    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+def sla2_backward(params, q, k, v, alpha, dout, dq, dk, dv, dalpha, workspace, stream=None, check=True,
+                  ws_bytes=None) -> int:
+    if ws_bytes is None:
+        ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     rc = _lib.sla2_backward(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(v), _ptr(alpha), _ptr(dout), _ptr(dq),
                             _ptr(dk), _ptr(dv), _ptr(dalpha), _ptr(workspace), ws_bytes, _stream(stream))
     if check and rc != SLA2_OK:

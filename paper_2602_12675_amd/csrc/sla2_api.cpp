@@ -140,6 +140,20 @@ static bool overlaps(const void* a, size_t na, const void* b, size_t nb) {
   return x < y + nb && y < x + na;
 }
 
+// Two tensors of the same strides whose address ranges interleave (slices of one packed projection,
+// [.., N, x, H, d]): they are disjoint when every token period holds each of them in its own stretch.
+// With the batch stride a multiple of the token stride, a tensor occupies the offsets
+// [r, r + (H - 1) head_stride + d) of every period; the two stretches must not meet (nor wrap).
+static bool interleaved_disjoint(const Shape& s, const Strides& st, const void* a, const void* b) {
+  const long long esz = s.bf16 ? 2 : 4, period = st.n;
+  if (st.h < s.d || (s.B > 1 && st.b % period != 0)) return false;
+  const long long extent = (long long)(s.H - 1) * st.h + s.d;
+  if (extent > period) return false;
+  const long long delta = ((long long)(intptr_t)b - (long long)(intptr_t)a) / esz;
+  const long long r = ((delta % period) + period) % period;
+  return r >= extent && r <= period - extent;
+}
+
 static int check_workspace(const sla2_ws_layout& L, const void* ws, size_t bytes) {
   if (!ws || ((uintptr_t)ws & 255) || bytes < L.total) return SLA2_EWORKSPACE;
   return SLA2_OK;
@@ -349,8 +363,9 @@ int sla2_backward(const sla2_params* params, const void* q, const void* k, const
   for (void* o : outs)
     for (int x = 0; x < 4; x++)
       if (overlaps(o, in_bytes, ins[x], x == 3 ? span_bytes(s, s.sout) : in_bytes)) return SLA2_EALIAS;
-  if (overlaps(dq, in_bytes, dk, in_bytes) || overlaps(dq, in_bytes, dv, in_bytes) || overlaps(dk, in_bytes, dv, in_bytes))
-    return SLA2_EALIAS;
+  void* pairs[3][2] = {{dq, dk}, {dq, dv}, {dk, dv}};
+  for (auto& pr : pairs)
+    if (overlaps(pr[0], in_bytes, pr[1], in_bytes) && !interleaved_disjoint(s, s.sin, pr[0], pr[1])) return SLA2_EALIAS;
   make_layout(s, &L);
   if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
   const BwdLayout B = make_bwd_layout(s);

@@ -133,3 +133,27 @@ def test_strided_alias_and_alignment_checks(api):
     assert api.sla2_forward(p, q, k, v, 256, 256, q + span - 16, workspace=ws, ws_bytes=need, check=False) == api.SLA2_EALIAS
     assert api.sla2_forward(p, q, k, v, 256, 256, q + 8, workspace=ws, ws_bytes=need, check=False) == api.SLA2_EINVAL
     assert api.sla2_forward(p, q + 2, k, v, 256, 256, 1 << 30, workspace=ws, ws_bytes=need, check=False) == api.SLA2_EINVAL
+
+
+def test_backward_gradient_slices_may_interleave_but_not_share_elements(api):
+    # dq, dk, dv as slices of one packed [B, N, 3, H, d] gradient buffer are fine as far as the host checks go
+    # (that call would go on to launch, so only the refusals are exercised here): shifted by half a row they
+    # share elements with their neighbour and must be refused, as must a gradient on top of an input
+    B, H, N, d = 1, 2, 1024, 64
+    st = (N * 3 * H * d, d, 3 * H * d)
+    p = api.make_params(B, H, N, d, 64, 64, 0.125, dtype=api.SLA2_BF16, in_stride=st, out_stride=(N * H * d, d, H * d),
+                        flags=api.SLA2_FLAG_SAVE_FOR_BACKWARD)
+    need = api.sla2_workspace_bytes(p)
+    assert need > 0
+    base, gbase, ws = 1 << 20, 1 << 26, 1 << 28
+    q, k, v = base, base + H * d * 2, base + 2 * H * d * 2
+    dq, dk, dv = gbase, gbase + H * d * 2, gbase + 2 * H * d * 2
+    go = 1 << 27
+
+    def call(dq_, dk_, dv_):
+        return api.sla2_backward(p, q, k, v, 256, go, dq_, dk_, dv_, 512, ws, ws_bytes=need, check=False)
+
+    assert call(dq, dq + 32, dv) == api.SLA2_EALIAS            # dk starts inside head 0's dq rows
+    assert call(dq, dk, dk + (H - 1) * d * 2) == api.SLA2_EALIAS
+    assert call(q, dk, dv) == api.SLA2_EALIAS                  # a gradient on top of an input
+    assert call(dq, dk, go) == api.SLA2_EALIAS

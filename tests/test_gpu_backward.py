@@ -20,6 +20,11 @@ CASES = [
     (BASE.replace(name="bwd-bf16-ragged-bq64", grid=(3, 11, 31), d=128, block_q=64, dtype="bf16", topk_frac=0.2), True, True),
     (BASE.replace(name="bwd-bf16-fp8-forward", grid=(3, 11, 31), d=128, block_q=128, dtype="bf16", quant="fp8", topk_frac=0.2), False, True),
     (BASE.replace(name="bwd-bf16-d64", grid=(3, 11, 31), d=64, block_q=128, dtype="bf16", topk_frac=0.125), False, True),
+    (BASE.replace(name="bwd-bf16-d64-bq64-b2", grid=(2, 13, 37), d=64, block_q=64, B=2, H=2, dtype="bf16", topk_frac=0.25), True, True),
+    (BASE.replace(name="bwd-bf16-per-block-alpha-no-smooth", grid=(3, 11, 31), d=128, block_q=128, H=3, dtype="bf16", topk_frac=0.15), True, False),
+    (BASE.replace(name="bwd-bf16-one-short-block", grid=(1, 5, 9), d=128, block_q=128, dtype="bf16", topk_frac=1.0), False, True),       # N = 45
+    (BASE.replace(name="bwd-bf16-int8-forward", grid=(3, 11, 31), d=128, block_q=64, dtype="bf16", quant="int8", topk_frac=0.2), False, True),
+    (BASE.replace(name="bwd-bf16-fp8v-forward", grid=(3, 11, 31), d=128, block_q=128, dtype="bf16", quant="fp8v", topk_frac=0.2), False, True),
 ]
 
 
@@ -111,3 +116,49 @@ def test_backward_needs_the_save_flag():
     ws = api.alloc_workspace(p)
     t = torch.zeros(64, device="cuda")
     assert api.sla2_backward(p, t, t, t, t, t, t, t, t, t, ws, check=False) == api.SLA2_EINVAL
+
+
+@pytest.mark.parametrize("w", [
+    BASE.replace(name="bwd-strided-f32", grid=(3, 11, 31), H=3),
+    BASE.replace(name="bwd-strided-bf16", grid=(3, 11, 31), d=128, block_q=128, B=2, H=2, dtype="bf16", topk_frac=0.2),
+], ids=lambda w: w.name)
+def test_backward_strided_equals_contiguous(w):
+    """q, k, v as slices of a packed [B, N, 3, H, d] projection, dout as [B, N, H, d], and the gradients
+    written into the slices of a packed [B, N, 3, H, d + pad] buffer: the same bits as the contiguous
+    call, and nothing written between the rows."""
+    import torch
+    from paper_2602_12675_amd import api
+    inp = W.generate(w)
+    rng = np.random.default_rng(9)
+    alpha = rng.uniform(0.1, 0.9, size=(w.H,)).astype(np.float32)
+    dout = rng.normal(size=(w.B, w.H, w.N, w.d)).astype(np.float32)
+    if w.dtype == "bf16":
+        dout = W.f32_to_bf16_bits(dout)
+    ref = run_fwd_bwd(api, torch, inp, alpha, False, True, dout)
+    dt = api.SLA2_BF16 if w.dtype == "bf16" else api.SLA2_F32
+    q, k, v = (api.to_device(a, dt) for a in (inp.q, inp.k, inp.v))
+    pad = 8
+    qkv = torch.empty((w.B, w.N, 3, w.H, w.d + pad), dtype=q.dtype, device="cuda")
+    grads = torch.full_like(qkv, 7.0)
+    for x, t in enumerate((q, k, v)):
+        qkv[:, :, x, :, :w.d] = t.permute(0, 2, 1, 3)
+    go = api.to_device(dout, dt).permute(0, 2, 1, 3).contiguous()                  # [B, N, H, d]
+    row = 3 * w.H * (w.d + pad)
+    in_stride = (w.N * row, w.d + pad, row)
+    out_stride = (w.N * w.H * w.d, w.d, w.H * w.d)
+    p = api.make_params(w.B, w.H, w.N, w.d, w.block_q, w.block_kv, w.topk_frac, dtype=dt,
+                        flags=api.SLA2_FLAG_SAVE_FOR_BACKWARD, in_stride=in_stride, out_stride=out_stride)
+    rw = torch.from_numpy(inp.router_w).cuda()
+    al = torch.from_numpy(alpha).cuda()
+    ws = api.alloc_workspace(p)
+    out = torch.empty((w.B, w.N, w.H, w.d), dtype=q.dtype, device="cuda")
+    api.sla2_forward(p, qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], rw, al, out, workspace=ws)
+    dal = torch.empty_like(al)
+    api.sla2_backward(p, qkv[:, :, 0], qkv[:, :, 1], qkv[:, :, 2], al, go, grads[:, :, 0], grads[:, :, 1], grads[:, :, 2],
+                      dal, ws)
+    torch.cuda.synchronize()
+    gr = grads.float().cpu().numpy()
+    assert np.all(gr[..., w.d:] == 7.0)
+    for x, name in enumerate(("dq", "dk", "dv")):
+        assert np.array_equal(gr[:, :, x, :, :w.d].transpose(0, 2, 1, 3), ref[name]), name
+    assert np.array_equal(dal.cpu().numpy(), ref["dalpha"])

@@ -88,3 +88,31 @@ def test_full_size_constant_values_and_dense_ratio():
     assert err <= 3e-2, err          # bf16 output (2^-8 relative) plus bf16 H_i, P rounding
     dense = run_dense(api, torch, inp)
     assert np.abs(dense - cv).max() <= 3e-2
+
+
+@pytest.mark.parametrize("quant", ["fp8", "none"])
+def test_wan_1p3b_backward_full_size(quant):
+    """The backward pass at the benchmark size (32,760 tokens, 12 heads, 97 % sparsity), after the forward
+    pass bench.py times: every gradient row of two heads against the oracle's backward of the same
+    forward (8 s of oracle per head), d alpha of those heads, and finiteness of the rest."""
+    import torch
+    import sla2_oracle as O
+    from paper_2602_12675_amd import api
+    from test_gpu_backward import rel, run_fwd_bwd
+    w = W.WAN_1P3B_97_FP8.replace(name="wan1.3b-97-bwd-" + quant, quant=quant)
+    inp = W.generate(w)
+    rng = np.random.default_rng(11)
+    dout = W.f32_to_bf16_bits(rng.normal(size=(w.B, w.H, w.N, w.d)).astype(np.float32))
+    alpha = inp.alpha.astype(np.float32)
+    r = run_fwd_bwd(api, torch, inp, alpha, False, True, dout)
+    assert all(np.isfinite(r[n]).all() for n in ("dq", "dk", "dv", "dalpha"))
+    oq = {"none": O.QUANT_NONE, "fp8": O.QUANT_FP8}[quant]
+    for h in (3, 11):
+        Q, K, V = (inp.values(n, 0, h) for n in ("q", "k", "v"))
+        g = O.backward_head(Q, K, V, r["idx"][0, h], float(alpha[h]), r["go"][0, h].astype(np.float64), w.block_q, w.block_kv,
+                            quant=oq)
+        for name in ("dq", "dk", "dv"):
+            e = rel(r[name][0, h], g["d" + name[1].upper()])
+            print("%s head %d %s rel-L2 %.4f" % (w.name, h, name, e))
+            assert e <= 2e-2, (name, h, e)
+        np.testing.assert_allclose(r["dalpha"][h], g["dalpha"].sum(), rtol=3e-2, atol=3e-2 * abs(g["dalpha"].sum()))
