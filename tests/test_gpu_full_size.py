@@ -116,3 +116,30 @@ def test_wan_1p3b_backward_full_size(quant):
             print("%s head %d %s rel-L2 %.4f" % (w.name, h, name, e))
             assert e <= 2e-2, (name, h, e)
         np.testing.assert_allclose(r["dalpha"][h], g["dalpha"].sum(), rtol=3e-2, atol=3e-2 * abs(g["dalpha"].sum()))
+
+
+def test_backward_ragged_75601():
+    """The backward pass on the 14B-shaped sequence with one extra token (1182 key blocks - not a multiple
+    of the 32-column words of the mask transpose -, a 17-token last key block, an 81-token last query
+    block), two heads; every gradient row of one head against the oracle."""
+    import torch
+    import sla2_oracle as O
+    from paper_2602_12675_amd import api
+    from test_gpu_backward import rel, run_fwd_bwd
+    w = W.SWEEP_BASE.replace(name="sweep-75601-bwd", B=1, H=2, extra_tokens=1, quant="none", topk_frac=0.03)
+    inp = W.generate(w)
+    rng = np.random.default_rng(12)
+    dout = W.f32_to_bf16_bits(rng.normal(size=(w.B, w.H, w.N, w.d)).astype(np.float32))
+    alpha = inp.alpha.astype(np.float32)
+    r = run_fwd_bwd(api, torch, inp, alpha, False, True, dout)
+    assert all(np.isfinite(r[n]).all() for n in ("dq", "dk", "dv", "dalpha"))
+    h = 1
+    Q, K, V = (inp.values(n, 0, h) for n in ("q", "k", "v"))
+    g = O.backward_head(Q, K, V, r["idx"][0, h], float(alpha[h]), r["go"][0, h].astype(np.float64), w.block_q, w.block_kv)
+    for name in ("dq", "dk", "dv"):
+        e = rel(r[name][0, h], g["d" + name[1].upper()])
+        print("%s head %d %s rel-L2 %.4f" % (w.name, h, name, e))
+        assert e <= 2e-2, (name, h, e)
+        tail = slice(w.N - 17, w.N)                        # the short last key block / the end of the last query block
+        assert rel(r[name][0, h][tail], g["d" + name[1].upper()][tail]) <= 3e-2
+    np.testing.assert_allclose(r["dalpha"][h], g["dalpha"].sum(), rtol=3e-2, atol=3e-2 * abs(g["dalpha"].sum()))
