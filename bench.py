@@ -233,6 +233,17 @@ def main():
                 "traffic": measured_traffic(w.name, w.quant), "ms": round(attn_ms, 4),
                 "launches_timed": prof["attn"][1],
                 "algorithmic_flops": attn_flops, "note": note}
+    # the same kernel against the other roof it can hit: bytes it has to gather per (query block, key block)
+    # pair - the K tile (codes in the low-bit modes) and the V tile - plus Q read and out written once.
+    # (The K^phi fragments it also loads, 16 KB per pair, are this design's choice and not counted.)
+    k_tile = w.block_kv * w.d * (1 if w.quant != "none" else esz)
+    v_tile = w.block_kv * w.d * esz + (w.block_kv * w.d if w.quant == "fp8v" else 0)
+    gather_bytes = tile_iters * float(k_tile + v_tile) + 2.0 * BH * w.N * w.d * esz
+    gather_gbs = gather_bytes / (attn_ms * 1e-3) / 1e9
+    roofline["gathered_tiles"] = {"bound": "hbm", "achieved": round(gather_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                  "frac": round(gather_gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": gather_bytes,
+                                  "note": "K and V tiles of every selected pair + Q + out over the same kernel time; "
+                                          "most tiles are served by L2 / Infinity Cache (see traffic)"}
     qk_bytes = 2.0 * BH * w.N * w.d * esz
     hbm = {}
     if "block_sums" in stages:

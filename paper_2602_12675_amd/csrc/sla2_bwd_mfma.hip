@@ -47,7 +47,7 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
     const float* __restrict__ z_i, const int32_t* __restrict__ block_idx, const float* __restrict__ alpha,
     uint16_t* __restrict__ dq, float* __restrict__ ds_out, float* __restrict__ lraw_out, uint16_t* __restrict__ dh_out,
     float* __restrict__ dz_out, float* __restrict__ dalpha_part, Strides sin, Strides sout, int H, int N, int Tm, int Tn,
-    int ksel, int alpha_per_block, int total_blocks) {
+    int ksel, int alpha_per_block) {
   constexpr int NW = BQ / 32, NT = NW * kWave;
   constexpr int LD = D + 8, KS = D / 16, ET = D / 32;
   typedef SwizzledLayout<D> SL;
@@ -61,11 +61,12 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
   auto kbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + buf * 2 * SM::kTile); };
   auto vbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + buf * 2 * SM::kTile + SM::kTile); };
 
-  // consecutive query blocks of a head share key/value tiles: keep them on one XCD
-  const int per_xcd = (total_blocks + kXcds - 1) / kXcds;
-  const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-  if (logical >= total_blocks) return;
-  const int bh = logical / Tm, i = logical % Tm, h = bh % H;
+  // consecutive query blocks of a head share key/value tiles: every head is cut into 8 runs of
+  // consecutive blocks, one per XCD (own L2), and all XCDs work through the heads in the same order
+  const int per_head = (Tm + kXcds - 1) / kXcds;
+  const int bh = (blockIdx.x / kXcds) / per_head, i = (blockIdx.x % kXcds) * per_head + (blockIdx.x / kXcds) % per_head;
+  if (i >= Tm) return;
+  const int h = bh % H;
   const int tid = threadIdx.x, lane = tid % kWave, g = lane / 32;
   const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int row0 = i * BQ;
@@ -400,12 +401,11 @@ static hipError_t launch_bwd_q_mfma(const Shape& s, const BwdArgs& a, hipStream_
     if (e != hipSuccess) return e;
     configured = true;
   }
-  const int total = s.BH * s.Tm;
-  const int grid = ((total + kXcds - 1) / kXcds) * kXcds;
+  const int grid = ((s.Tm + kXcds - 1) / kXcds) * kXcds * s.BH;
   bwd_q_mfma_kernel<D, BQ><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(
       (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.dout, (const uint16_t*)a.o_s,
       (const uint16_t*)a.o_l, a.lse, a.k_mean, a.h_i, a.z_i, a.block_idx, a.alpha, (uint16_t*)a.dq, a.ds, a.lraw,
-      (uint16_t*)a.dh, a.dz, a.dalpha_part, s.sin, s.sout, s.H, s.N, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0, total);
+      (uint16_t*)a.dh, a.dz, a.dalpha_part, s.sin, s.sout, s.H, s.N, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
   return hipGetLastError();
 }
 
@@ -437,7 +437,7 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_mfma_kernel(
     const int32_t* __restrict__ col_idx, const uint16_t* __restrict__ dh_in, const float* __restrict__ dz_in,
     const float* __restrict__ dh_total, const float* __restrict__ dz_total, const float* __restrict__ alpha,
     uint16_t* __restrict__ dk, uint16_t* __restrict__ dv, float* __restrict__ colsum, Strides sin, Strides sout, int H,
-    int N, int Tm, int Tn, int ksel, int alpha_per_block, int total_blocks) {
+    int N, int Tm, int Tn, int ksel, int alpha_per_block) {
   constexpr int NW = 4, NT = 256;
   constexpr int LD = D + 8, KS = D / 16, ET = D / 32;
   constexpr int HP = BQ / 64;                        // 64-row steps per query block
@@ -453,11 +453,11 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_mfma_kernel(
   float* dzs = reinterpret_cast<float*>(smem + SM::kDzOff);
   float* dred = reinterpret_cast<float*>(smem + SM::kDotOff);
 
-  // consecutive key blocks of a head were selected by overlapping sets of query blocks: one XCD
-  const int per_xcd = (total_blocks + kXcds - 1) / kXcds;
-  const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-  if (logical >= total_blocks) return;
-  const int bh = logical / Tn, j = logical % Tn, h = bh % H;
+  // the same dealing for key blocks: 8 runs of consecutive key blocks per head, one per XCD
+  const int per_head = (Tn + kXcds - 1) / kXcds;
+  const int bh = (blockIdx.x / kXcds) / per_head, j = (blockIdx.x % kXcds) * per_head + (blockIdx.x / kXcds) % per_head;
+  if (j >= Tn) return;
+  const int h = bh % H;
   const int tid = threadIdx.x, lane = tid % kWave, g = lane / 32;
   const int w = __builtin_amdgcn_readfirstlane(tid / kWave);
   const int kh = w & 1, cgrp = w >> 1;
@@ -799,12 +799,11 @@ static hipError_t launch_bwd_kv_mfma(const Shape& s, const BwdArgs& a, hipStream
     if (e != hipSuccess) return e;
     configured = true;
   }
-  const int total = s.BH * s.Tn;
-  const int grid = ((total + kXcds - 1) / kXcds) * kXcds;
+  const int grid = ((s.Tn + kXcds - 1) / kXcds) * kXcds * s.BH;
   bwd_kv_mfma_kernel<D, BQ><<<dim3((unsigned)grid), 256, smem, stream>>>(
       (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.dout, a.lraw, a.ds, a.k_mean,
       a.k_stats, a.col_ptr, a.col_idx, (const uint16_t*)a.dh, a.dz, a.dh_total, a.dz_total, a.alpha, (uint16_t*)a.dk,
-      (uint16_t*)a.dv, a.colsum, s.sin, s.sout, s.H, s.N, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0, total);
+      (uint16_t*)a.dv, a.colsum, s.sin, s.sout, s.H, s.N, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
   return hipGetLastError();
 }
 

@@ -328,7 +328,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     uint16_t* __restrict__ out, float* __restrict__ lse, uint16_t* __restrict__ o_s_save,
     uint16_t* __restrict__ o_l_save, float* __restrict__ lse_save, uint16_t* __restrict__ h_save,
     float* __restrict__ z_save, Strides sin, Strides sout, int H, int N, int Tm,
-    int Tn, int ksel, int alpha_per_block, int total_blocks) {
+    int Tn, int ksel, int alpha_per_block) {
   // FP8 below means "8-bit codes of Q and K": everything the two low-bit modes share.  INT8 marks the
   // places where the integer mode differs (the quantiser of Q and the Q K^T product).
   // FP8V: V is quantised too and P V runs as an FP8 product (the linear branch still reads the bf16 V).
@@ -357,12 +357,14 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   auto vbuf = [&](int buf) { return reinterpret_cast<uint16_t*>(smem + buf * SM::kBufBytes + SM::kKBytes); };
   auto vqbuf = [&](int buf) { return smem + buf * SM::kBufBytes + SM::kKBytes + SM::kVBytes; };
 
-  // consecutive query blocks of a head share key/value tiles: keep them on one XCD (workgroups are
-  // dealt round-robin to the 8 XCDs, each with its own L2)
-  const int per_xcd = (total_blocks + kXcds - 1) / kXcds;
-  const int logical = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
-  if (logical >= total_blocks) return;
-  const int bh = logical / Tm, i = logical % Tm, h = bh % H;
+  // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2.  Consecutive query blocks of
+  // a head share key/value tiles: every head is cut into 8 runs of consecutive blocks, one per XCD, and
+  // all XCDs work through the heads in the same order - the tiles in flight then belong to one or two
+  // heads, which the memory-side cache holds whole.
+  const int per_head = (Tm + kXcds - 1) / kXcds;
+  const int bh = (blockIdx.x / kXcds) / per_head, i = (blockIdx.x % kXcds) * per_head + (blockIdx.x / kXcds) % per_head;
+  if (i >= Tm) return;
+  const int h = bh % H;
   const int tid = threadIdx.x, lane = tid % kWave, g = lane / 32;
   const int w = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave index, known to be uniform
   const int row0 = i * BQ;
@@ -957,13 +959,12 @@ static hipError_t launch_attn_t(const Shape& s, const AttnArgs& a, hipStream_t s
     configured = true;
   }
   const int Tm = (s.N + BQ - 1) / BQ;
-  const int total = s.BH * Tm;
-  const int grid = ((total + kXcds - 1) / kXcds) * kXcds;
+  const int grid = ((Tm + kXcds - 1) / kXcds) * kXcds * s.BH;   // some workgroups of the last run of a head may have no block
   attn_mfma_kernel<D, BQ, MODE><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(
       a.q, a.k, a.v, a.k_mean, a.k_phi, a.z_blocks, a.k_fp8, a.k_scale, a.v_codes, a.v_scale, a.h_total, a.z_total,
       a.block_idx, a.alpha,
       a.out, a.lse, (uint16_t*)a.sv.o_s, (uint16_t*)a.sv.o_l, a.sv.lse, a.sv.h_i, a.sv.z_i, s.sin, s.sout, s.H, s.N, Tm, s.Tn, s.k,
-      s.alpha_per_block ? 1 : 0, total);
+      s.alpha_per_block ? 1 : 0);
   return hipGetLastError();
 }
 
