@@ -42,7 +42,7 @@ def parse():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-backward", action="store_true", help="skip the forward-for-training + backward timing")
-    ap.add_argument("--cpu-heads", type=int, default=6, help="heads of the workload the oracle is timed on")
+    ap.add_argument("--cpu-heads", type=int, default=12, help="heads of the workload the oracle is timed on")
     ap.add_argument("--event-stride", type=int, default=1,
                     help="bracket the dominant kernel with HIP events on every n-th timed step")
     ap.add_argument("--copy-calibration", action="store_true",
