@@ -1,10 +1,15 @@
 // Backward pass of SLA2 (Alg. 3 of the paper's appendix, with the steps it leaves to automatic
 // differentiation written out: phi = softmax over d, the smoothing of K, the mix of Eq. 13).
-// High precision throughout, from the original Q, K, V (Sec. 5: the backward pass is never quantised):
-// fp32 arithmetic on fp32 or bf16 tensors.  These are plain LDS-tiled FMA kernels - the readable,
-// deterministic statement of the data flow (no atomics, fixed summation orders); they are not tuned.
+// High precision throughout, from the original Q, K, V (Sec. 5: the backward pass is never quantised).
 //
-//   bwd_transpose  for every key block j, the ascending list of query blocks i with M_c[i, j] = 1
+// This file holds the launch sequence, the small kernels every tensor type shares, and the two heavy
+// kernels for fp32 tensors: plain LDS-tiled FMA kernels in fp32 - the readable, deterministic
+// statement of the data flow (no atomics, fixed summation orders); they are not tuned.  bf16 tensors
+// run the two heavy steps on the matrix cores instead (sla2_bwd_mfma.hip).
+//
+//   bwd_mask_bits, bwd_col_count / _scan / _fill
+//                  M_c as bits, then for every key block j the ascending list of query blocks i with
+//                  M_c[i, j] = 1
 //   bwd_q          per 64 query rows of block i:  D^s, D^l, d alpha;  over the selected blocks:
 //                  P = exp(S - L), dP = dO^s V^T, dS = P (.) (dP - D^s), dQ += dS K' / sqrt d, and the
 //                  state of the selected blocks (as in the forward pass) -> H_i, Z_i;  then
@@ -14,7 +19,8 @@
 //                  dK' += dS^T Q / sqrt d;  dH = dH_total - sum over those same query blocks of dH_i
 //                  (the M_c[i, j] = 0 sum of Alg. 3, by complement), dZ likewise;
 //                  dK^phi = V dH^T + 1 dZ^T, dV += K^phi dH, dK' += softmax-backward(dK^phi)
-//   bwd_finish     dK = dK' - colmean(dK') (gradient of the smoothing), d alpha summed over its parts
+//   bwd_colmean, bwd_unsmooth, bwd_dalpha
+//                  dK = dK' - colmean(dK') (gradient of the smoothing), d alpha summed over its parts
 #include "common.h"
 
 namespace sla2 {

@@ -3,15 +3,15 @@
 // quantised).  Products run as v_mfma_f32_32x32x16_bf16 with fp32 accumulation; everything between
 // them (exp, the D^s / D^l terms, both softmax-backward steps) is fp32.
 //
-// Both kernels keep the scores transposed, S^T = K Q^T (keys x query rows), as the forward kernel does:
-// one lane owns one query row, so L and D^s of the row are per-lane scalars and dS^T can go straight
-// back into the next product as its B operand.
+// In each kernel the scores are laid out so that the probabilities feed the next product from registers:
 //
-//   bwd_q_mfma   one workgroup per query block i (b_q rows, one wave per 32 rows).  Over the selected
-//                key blocks: P^T = exp(S^T - L), dP^T = V dO^s^T, dS^T = P^T (.) (dP^T - D^s),
-//                dQ^T += K^T dS^T.  Then the linear branch from the H_i^T, Z_i the forward pass kept:
-//                dQ^phi^T = H_i dO^l^T - Z_i D^l^T (over Q^phi Z_i), dQ += softmax-backward(dQ^phi),
-//                dH_i = (Q^phi / (Q^phi Z_i))^T dO^l, dZ_i.
+//   bwd_q_mfma   one workgroup per query block i (b_q rows, one wave per 32 rows), scores transposed as
+//                in the forward kernel, S^T = K Q^T (keys x query rows): one lane owns one query row, so
+//                L and D^s are per-lane scalars and dS^T is the B operand of the product that contracts
+//                over keys.  Over the selected key blocks: P^T = exp(S^T - L), dP^T = V dO^T,
+//                dS^T = P^T (.) (alpha dP^T - D^s), dQ^T += K^T dS^T.  Then the linear branch from the
+//                H_i^T, Z_i the forward pass kept: dQ^phi^T = (1 - alpha) H_i dO^T - Z_i D^l^T (over
+//                Q^phi Z_i), dQ += softmax-backward(dQ^phi), dH_i = (Q^phi / (Q^phi Z_i))^T dO^l, dZ_i.
 //   bwd_kv_mfma  one workgroup per key block j, over the query blocks that selected it, 64 rows a
 //                step: here S = Q K^T (rows x keys), so that P and dS are already laid out as the
 //                B operands of dV^T += dO^T (alpha P), dK'^T += Q^T dS.  Then the linear branch:
