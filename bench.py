@@ -116,12 +116,17 @@ def backward_timing(api, W, torch, w, inp, dt, qm, tensors, rw, al, stream, ksel
 
     fwd_ms = timed(lambda: api.sla2_forward(p, q, k, v, rw, al, out, workspace=ws, stream=stream))
     bwd_ms = timed(lambda: api.sla2_backward(p, q, k, v, al, dout, dq, dk, dv, dal, ws, stream=stream))
+    api.sla2_profile_begin(["bwd_lists", "bwd_q", "bwd_kv", "bwd_rest"], reps)
+    for _ in range(reps):
+        api.sla2_backward(p, q, k, v, al, dout, dq, dk, dv, dal, ws, stream=stream)
+    torch.cuda.synchronize()
+    stage_ms = {name: round(ms / reps, 4) for name, (ms, n) in api.sla2_profile_end().items()}
     BH = w.B * w.H
     pair = 2.0 * w.block_q * w.block_kv * w.d                   # one product over a (query block, key block) pair
     # S, dP, dQ, dK, dV per selected pair; dQ^phi and dH_i per query block; dK^phi and the linear dV per key block
     flops = BH * (w.T_m * ksel * 5.0 * pair + w.T_m * 2 * 2.0 * w.block_q * w.d * w.d + w.T_n * 2 * 2.0 * w.block_kv * w.d * w.d)
     tf = flops / (bwd_ms * 1e-3) / 1e12
-    res = {"ms": round(bwd_ms, 4), "forward_saving_ms": round(fwd_ms, 4), "algorithmic_flops": flops,
+    res = {"ms": round(bwd_ms, 4), "forward_saving_ms": round(fwd_ms, 4), "stage_ms": stage_ms, "algorithmic_flops": flops,
            "TFLOP/s": round(tf, 1), "dtype": "bf16 MFMA products, fp32 elsewhere" if w.dtype == "bf16" else "f32",
            "workspace_bytes": int(ws.numel())}
     if w.dtype == "bf16":

@@ -204,7 +204,7 @@ int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, 
  * The forward pass is a fixed sequence of kernels ("stages").  Between sla2_profile_begin and
  * sla2_profile_end every launch of a stage whose bit is set in stage_mask is bracketed by two
  * hipEventRecord calls on the caller's stream, for at most max_calls calls of sla2_forward /
- * sla2_router / sla2_dense_forward; the events are created in sla2_profile_begin, so the
+ * sla2_router / sla2_dense_forward / sla2_backward; the events are created in sla2_profile_begin, so the
  * calls in between still allocate nothing.  sla2_profile_end synchronises on the recorded
  * events, adds up the elapsed milliseconds and the number of launches per stage into the two
  * HOST arrays (each SLA2_STAGE_COUNT long) and destroys the events.
@@ -216,7 +216,11 @@ typedef enum {
   SLA2_STAGE_KV_TOTAL = 3,    /* per-head totals of h and z */
   SLA2_STAGE_ATTN = 4,        /* sparse + linear branch + mix              (Alg. 2 block loop, Eq. 13) */
   SLA2_STAGE_DENSE = 5,       /* dense attention comparator */
-  SLA2_STAGE_COUNT = 6
+  SLA2_STAGE_BWD_LISTS = 6,   /* sla2_backward: the block mask as bits, per key block the list of its query blocks */
+  SLA2_STAGE_BWD_Q = 7,       /* query-side kernel: D^s, D^l, dQ, dH_i, dZ_i, d alpha parts          (Alg. 3) */
+  SLA2_STAGE_BWD_KV = 8,      /* key-side kernel: dK', dV                                             (Alg. 3) */
+  SLA2_STAGE_BWD_REST = 9,    /* totals of dH_i, dZ_i; dK = dK' - colmean(dK'); d alpha               */
+  SLA2_STAGE_COUNT = 10
 } sla2_stage;
 int sla2_profile_begin(unsigned stage_mask, int max_calls);
 /* The same, bracketing only calls 1, 1 + every, 1 + 2 every, ... (at most max_calls of them), for

@@ -28,7 +28,8 @@ EXPORTS = ("sla2_workspace_bytes", "sla2_workspace_layout", "sla2_num_selected",
            "sla2_profile_end",
            "sla2_strerror", "sla2_version")
 
-STAGES = ("block_sums", "topk", "kv_state", "kv_total", "attn", "dense")   # sla2_stage
+STAGES = ("block_sums", "topk", "kv_state", "kv_total", "attn", "dense",
+          "bwd_lists", "bwd_q", "bwd_kv", "bwd_rest")   # sla2_stage
 
 
 class Params(ctypes.Structure):

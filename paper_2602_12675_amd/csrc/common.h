@@ -96,7 +96,12 @@ struct BwdArgs {
   int32_t *col_ptr, *col_idx, *col_cnt;
   uint32_t* mask_bits;                       // M_c as bits, [BH, T_m, ceil(T_n / 32)]
 };
-hipError_t launch_backward(const Shape& s, const BwdArgs& a, hipStream_t stream);
+// the backward pass in the order it runs: lists, query side, totals, key side, finish
+hipError_t launch_bwd_lists(const Shape& s, const BwdArgs& a, hipStream_t stream);
+hipError_t launch_bwd_q(const Shape& s, const BwdArgs& a, hipStream_t stream);
+hipError_t launch_bwd_totals(const Shape& s, const BwdArgs& a, hipStream_t stream);
+hipError_t launch_bwd_kv(const Shape& s, const BwdArgs& a, hipStream_t stream);
+hipError_t launch_bwd_finish(const Shape& s, const BwdArgs& a, hipStream_t stream);
 hipError_t launch_bwd_q_bf16(const Shape& s, const BwdArgs& a, hipStream_t stream);   // matrix-core kernels, bf16 tensors
 hipError_t launch_bwd_kv_bf16(const Shape& s, const BwdArgs& a, hipStream_t stream);
 

@@ -386,7 +386,13 @@ int sla2_backward(const sla2_params* params, const void* q, const void* k, const
   a.dalpha_part = (float*)(bw + B.dalpha_part);
   a.col_ptr = (int32_t*)(bw + B.col_ptr); a.col_idx = (int32_t*)(bw + B.col_idx);
   a.mask_bits = (uint32_t*)(bw + B.mask_bits); a.col_cnt = (int32_t*)(bw + B.col_cnt);
-  if (launch_backward(s, a, (hipStream_t)hip_stream) != hipSuccess) return SLA2_EHIP;
+  hipStream_t st = (hipStream_t)hip_stream;
+  g_prof.calls++;
+  if (SLA2_STAGE(SLA2_STAGE_BWD_LISTS, launch_bwd_lists(s, a, st)) != hipSuccess) return SLA2_EHIP;
+  if (SLA2_STAGE(SLA2_STAGE_BWD_Q, launch_bwd_q(s, a, st)) != hipSuccess) return SLA2_EHIP;
+  if (SLA2_STAGE(SLA2_STAGE_BWD_REST, launch_bwd_totals(s, a, st)) != hipSuccess) return SLA2_EHIP;
+  if (SLA2_STAGE(SLA2_STAGE_BWD_KV, launch_bwd_kv(s, a, st)) != hipSuccess) return SLA2_EHIP;
+  if (SLA2_STAGE(SLA2_STAGE_BWD_REST, launch_bwd_finish(s, a, st)) != hipSuccess) return SLA2_EHIP;
   return SLA2_OK;
 }
 
@@ -417,6 +423,7 @@ int sla2_profile_begin_sampled(unsigned stage_mask, int max_calls, int every) {
   if (p.active || max_calls < 1 || max_calls > 100000 || every < 1 || (stage_mask >> SLA2_STAGE_COUNT)) return SLA2_EINVAL;
   int per_call = __builtin_popcount(stage_mask);
   if (per_call == 0) return SLA2_EINVAL;
+  if (stage_mask >> SLA2_STAGE_BWD_REST & 1u) per_call++;   // that stage is bracketed twice per call (totals, finish)
   size_t n = (size_t)2 * per_call * max_calls;
   p.pool.assign(n, nullptr);
   for (size_t i = 0; i < n; i++)

@@ -766,83 +766,86 @@ __global__ __launch_bounds__(256) void bwd_dalpha_kernel(const float* __restrict
 }
 
 // ---------------------------------------------------------------------------------------------
-template <typename T, int D>
-static hipError_t launch_backward_t(const Shape& s, const BwdArgs& a, hipStream_t stream) {
-  const int parts = s.bq / kBwdRows;
-  const size_t smem_q = ((size_t)4 * 64 * (D + 1) + 64 * 65 + D + 64 + 64 + 256) * sizeof(float);
-  const size_t smem_kv = ((size_t)4 * 64 * (D + 1) + 64 * 65 + 64 + 64 + D + 16 * D) * sizeof(float);
+constexpr size_t bwd_smem_q(int D) { return ((size_t)4 * 64 * (D + 1) + 64 * 65 + D + 64 + 64 + 256) * sizeof(float); }
+constexpr size_t bwd_smem_kv(int D) { return ((size_t)4 * 64 * (D + 1) + 64 * 65 + 64 + 64 + D + 16 * D) * sizeof(float); }
+
+// dH_i, dZ_i and d alpha parts: one slot per query block (bf16 tensors) or per 64 query rows (fp32 tensors)
+static int bwd_slots_per_block(const Shape& s) { return s.bf16 ? 1 : s.bq / kBwdRows; }
+
+hipError_t launch_bwd_lists(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  // k = 0: every list is empty (the bit rows are all zero)
+  bwd_mask_bits_kernel<<<dim3((unsigned)(s.BH * s.Tm)), 64, 0, stream>>>(a.block_idx, a.mask_bits, s.Tn, s.k);
+  const dim3 words((unsigned)((s.Tn + 31) / 32), (unsigned)s.BH);
+  bwd_col_count_kernel<<<words, 64, 0, stream>>>(a.mask_bits, a.col_cnt, s.Tm, s.Tn);
+  bwd_col_scan_kernel<<<dim3((unsigned)s.BH), 256, 0, stream>>>(a.col_cnt, a.col_ptr, s.Tn);
+  bwd_col_fill_kernel<<<words, 64, 0, stream>>>(a.mask_bits, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_bwd_q_f32(const Shape& s, const BwdArgs& a, hipStream_t stream) {
   static bool configured = false;
   if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)bwd_q_kernel<T, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)smem_q);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)bwd_kv_kernel<T, D>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_kv);
+    hipError_t e = hipFuncSetAttribute((const void*)bwd_q_kernel<float, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)bwd_smem_q(D));
     if (e != hipSuccess) return e;
     configured = true;
   }
-  // k = 0: every list is empty and the kernel writes all-zero offsets
-  bwd_mask_bits_kernel<<<dim3((unsigned)(s.BH * s.Tm)), 64, 0, stream>>>(a.block_idx, a.mask_bits, s.Tn, s.k);
-  {
-    const dim3 words((unsigned)((s.Tn + 31) / 32), (unsigned)s.BH);
-    bwd_col_count_kernel<<<words, 64, 0, stream>>>(a.mask_bits, a.col_cnt, s.Tm, s.Tn);
-    bwd_col_scan_kernel<<<dim3((unsigned)s.BH), 256, 0, stream>>>(a.col_cnt, a.col_ptr, s.Tn);
-    bwd_col_fill_kernel<<<words, 64, 0, stream>>>(a.mask_bits, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
+  const int parts = s.bq / kBwdRows;
+  bwd_q_kernel<float, D><<<dim3((unsigned)((size_t)s.BH * s.Tm * parts)), 256, bwd_smem_q(D), stream>>>(
+      (const float*)a.q, (const float*)a.k, (const float*)a.v, (const float*)a.dout, (const float*)a.o_s,
+      (const float*)a.o_l, a.lse, a.k_mean, a.k_stats, a.h_total, a.z_total, a.block_idx, a.alpha, (float*)a.dq, a.ds,
+      (float*)a.dh, a.dz, a.dalpha_part, s.sin, s.sout, s.H, s.N, s.bq, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_q(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  if (s.bf16) return launch_bwd_q_bf16(s, a, stream);
+  return s.d == 128 ? launch_bwd_q_f32<128>(s, a, stream) : launch_bwd_q_f32<64>(s, a, stream);
+}
+
+hipError_t launch_bwd_totals(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  const int D = s.d, count = s.Tm * bwd_slots_per_block(s);
+  const dim3 grid_h((unsigned)((D * D + 255) / 256), (unsigned)s.BH), grid_z((unsigned)((D + 255) / 256), (unsigned)s.BH);
+  if (s.bf16) bwd_sum_kernel<uint16_t><<<grid_h, 256, 0, stream>>>((const uint16_t*)a.dh, a.dh_total, count, D * D);
+  else bwd_sum_kernel<float><<<grid_h, 256, 0, stream>>>((const float*)a.dh, a.dh_total, count, D * D);
+  bwd_sum_kernel<float><<<grid_z, 256, 0, stream>>>(a.dz, a.dz_total, count, D);
+  return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_bwd_kv_f32(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  static bool configured = false;
+  if (!configured) {
+    hipError_t e = hipFuncSetAttribute((const void*)bwd_kv_kernel<float, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       (int)bwd_smem_kv(D));
+    if (e != hipSuccess) return e;
+    configured = true;
   }
-  bwd_q_kernel<T, D><<<dim3((unsigned)((size_t)s.BH * s.Tm * parts)), 256, smem_q, stream>>>(
-      (const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.dout, (const T*)a.o_s, (const T*)a.o_l, a.lse, a.k_mean,
-      a.k_stats, a.h_total, a.z_total, a.block_idx, a.alpha, (T*)a.dq, a.ds, (float*)a.dh, a.dz, a.dalpha_part, s.sin,
-      s.sout, s.H, s.N, s.bq, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
-  bwd_sum_kernel<float><<<dim3((unsigned)((D * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
-      (const float*)a.dh, a.dh_total, s.Tm * parts, D * D);
-  bwd_sum_kernel<float><<<dim3((unsigned)((D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(a.dz, a.dz_total,
-                                                                                             s.Tm * parts, D);
-  bwd_kv_kernel<T, D><<<dim3((unsigned)((size_t)s.BH * s.Tn)), 256, smem_kv, stream>>>(
-      (const T*)a.q, (const T*)a.k, (const T*)a.v, (const T*)a.dout, a.lse, a.ds, a.k_mean, a.k_stats, a.col_ptr,
-      a.col_idx, (const float*)a.dh, a.dz, a.dh_total, a.dz_total, a.alpha, (T*)a.dk, (T*)a.dv, a.colsum, s.sin, s.sout,
-      s.H, s.N, s.bq, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
+  bwd_kv_kernel<float, D><<<dim3((unsigned)((size_t)s.BH * s.Tn)), 256, bwd_smem_kv(D), stream>>>(
+      (const float*)a.q, (const float*)a.k, (const float*)a.v, (const float*)a.dout, a.lse, a.ds, a.k_mean, a.k_stats,
+      a.col_ptr, a.col_idx, (const float*)a.dh, a.dz, a.dh_total, a.dz_total, a.alpha, (float*)a.dk, (float*)a.dv,
+      a.colsum, s.sin, s.sout, s.H, s.N, s.bq, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
+  return hipGetLastError();
+}
+
+hipError_t launch_bwd_kv(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  if (s.bf16) return launch_bwd_kv_bf16(s, a, stream);
+  return s.d == 128 ? launch_bwd_kv_f32<128>(s, a, stream) : launch_bwd_kv_f32<64>(s, a, stream);
+}
+
+hipError_t launch_bwd_finish(const Shape& s, const BwdArgs& a, hipStream_t stream) {
+  const int D = s.d;
   if (s.smooth) {
     bwd_colmean_kernel<<<dim3((unsigned)s.BH), 1024, 0, stream>>>(a.colsum, a.dk_mean, s.Tn, s.N, D);
-    bwd_unsmooth_kernel<T><<<dim3((unsigned)(((size_t)s.N * D / 8 + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
-        (T*)a.dk, a.dk_mean, s.sin, s.H, s.N, D);
+    const dim3 grid((unsigned)(((size_t)s.N * D / 8 + 255) / 256), (unsigned)s.BH);
+    if (s.bf16) bwd_unsmooth_kernel<uint16_t><<<grid, 256, 0, stream>>>((uint16_t*)a.dk, a.dk_mean, s.sin, s.H, s.N, D);
+    else bwd_unsmooth_kernel<float><<<grid, 256, 0, stream>>>((float*)a.dk, a.dk_mean, s.sin, s.H, s.N, D);
   }
   const int n_alpha = s.alpha_per_block ? s.H * s.Tm : s.H;
   bwd_dalpha_kernel<<<dim3((unsigned)n_alpha), 256, 0, stream>>>(a.dalpha_part, a.dalpha, s.B, s.H, s.Tm,
-                                                                                 parts, s.alpha_per_block ? 1 : 0);
+                                                                 bwd_slots_per_block(s), s.alpha_per_block ? 1 : 0);
   return hipGetLastError();
-}
-
-// bf16 tensors: the two heavy kernels run on the matrix cores (one dH_i slot per query block, kept as
-// bf16); the small ones above are shared.
-static hipError_t launch_backward_bf16(const Shape& s, const BwdArgs& a, hipStream_t stream) {
-  const int D = s.d;
-  bwd_mask_bits_kernel<<<dim3((unsigned)(s.BH * s.Tm)), 64, 0, stream>>>(a.block_idx, a.mask_bits, s.Tn, s.k);
-  {
-    const dim3 words((unsigned)((s.Tn + 31) / 32), (unsigned)s.BH);
-    bwd_col_count_kernel<<<words, 64, 0, stream>>>(a.mask_bits, a.col_cnt, s.Tm, s.Tn);
-    bwd_col_scan_kernel<<<dim3((unsigned)s.BH), 256, 0, stream>>>(a.col_cnt, a.col_ptr, s.Tn);
-    bwd_col_fill_kernel<<<words, 64, 0, stream>>>(a.mask_bits, a.col_ptr, a.col_idx, s.Tm, s.Tn, s.k);
-  }
-  hipError_t e = launch_bwd_q_bf16(s, a, stream);
-  if (e != hipSuccess) return e;
-  bwd_sum_kernel<uint16_t><<<dim3((unsigned)((D * D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
-      (const uint16_t*)a.dh, a.dh_total, s.Tm, D * D);
-  bwd_sum_kernel<float><<<dim3((unsigned)((D + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(a.dz, a.dz_total, s.Tm, D);
-  e = launch_bwd_kv_bf16(s, a, stream);
-  if (e != hipSuccess) return e;
-  if (s.smooth) {
-    bwd_colmean_kernel<<<dim3((unsigned)s.BH), 1024, 0, stream>>>(a.colsum, a.dk_mean, s.Tn, s.N, D);
-    bwd_unsmooth_kernel<uint16_t><<<dim3((unsigned)(((size_t)s.N * D / 8 + 255) / 256), (unsigned)s.BH), 256, 0, stream>>>(
-        (uint16_t*)a.dk, a.dk_mean, s.sin, s.H, s.N, D);
-  }
-  const int n_alpha = s.alpha_per_block ? s.H * s.Tm : s.H;
-  bwd_dalpha_kernel<<<dim3((unsigned)n_alpha), 256, 0, stream>>>(a.dalpha_part, a.dalpha, s.B, s.H, s.Tm, 1,
-                                                                                 s.alpha_per_block ? 1 : 0);
-  return hipGetLastError();
-}
-
-hipError_t launch_backward(const Shape& s, const BwdArgs& a, hipStream_t stream) {
-  if (s.bf16) return launch_backward_bf16(s, a, stream);
-  return s.d == 128 ? launch_backward_t<float, 128>(s, a, stream) : launch_backward_t<float, 64>(s, a, stream);
 }
 
 }  // namespace sla2

@@ -57,3 +57,22 @@ def test_bad_arguments(tiny):
     with pytest.raises(api.Sla2Error):      # begin without end
         api.sla2_profile_begin(["attn"], 1)
     api.sla2_profile_end()
+
+
+def test_backward_stages_are_bracketed():
+    import torch
+    from paper_2602_12675_amd import api, workloads as W
+    from test_gpu_backward import run_fwd_bwd
+    w = W.TINY.replace(name="prof-bwd", per_head_freq=True)
+    inp = W.generate(w)
+    alpha = np.full((w.H,), 0.5, dtype=np.float32)
+    dout = np.ones((w.B, w.H, w.N, w.d), dtype=np.float32)
+    api.sla2_profile_begin(["attn", "bwd_lists", "bwd_q", "bwd_kv", "bwd_rest"], 2)
+    for _ in range(3):                      # a forward and a backward call each; the third pair is past max_calls
+        run_fwd_bwd(api, torch, inp, alpha, False, True, dout)
+    got = api.sla2_profile_end()
+    # max_calls counts entry-point calls: the first forward and the first backward call are bracketed
+    assert got["attn"][1] + got["bwd_q"][1] == 2, got
+    assert got["bwd_q"][1] == got["bwd_kv"][1] == got["bwd_lists"][1]
+    assert got["bwd_rest"][1] == 2 * got["bwd_q"][1]          # totals and finish
+    assert all(ms > 0.0 for ms, n in got.values())
