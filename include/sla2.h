@@ -70,8 +70,8 @@ typedef enum { SLA2_F32 = 0, SLA2_BF16 = 1 } sla2_dtype;   /* element type of q,
 typedef enum { SLA2_QUANT_NONE = 0, SLA2_QUANT_FP8 = 1, SLA2_QUANT_INT8 = 2, SLA2_QUANT_FP8_V = 3 } sla2_quant;
 
 #define SLA2_FLAG_NO_SMOOTH_K 1u   /* skip K <- K - colmean(K) (first step of Alg. 2) */
-#define SLA2_FLAG_SAVE_FOR_BACKWARD 2u   /* sla2_forward also keeps O^s, O^l and L in the workspace, and the
-                                            workspace is sized for sla2_backward */
+#define SLA2_FLAG_SAVE_FOR_BACKWARD 2u   /* sla2_forward also keeps what sla2_backward needs (O^s, L, ...) in the
+                                            workspace, and the workspace is sized for sla2_backward */
 
 typedef struct sla2_params {
   int B, H, N, d;          /* batch, heads, tokens, head dim.  d in {64, 128}; N >= 1;
@@ -122,7 +122,8 @@ typedef struct sla2_ws_layout {
   size_t partial;   /* scratch for per-chunk partial sums of h and z */
   /* with SLA2_FLAG_SAVE_FOR_BACKWARD only (0 bytes otherwise): */
   size_t o_s;       /* dtype  [BH, N, d]     sparse-branch output O^s, before the mix of Eq. 13   (input of Alg. 3) */
-  size_t o_l;       /* dtype  [BH, N, d]     linear-branch output O^l */
+  size_t o_l;       /* dtype  [BH, N, d]     linear-branch output O^l (fp32 tensors only; 0 bytes for bf16 tensors, whose
+                       backward pass rebuilds what it needs of O^l from the state kept in `bwd`) */
   size_t lse;       /* float  [BH, N]        L_i of Alg. 2 (log-sum-exp of the kept scores; -inf when k = 0) */
   size_t bwd;       /* scratch of sla2_backward; for bf16 tensors sla2_forward also leaves the state of the
                        linear branch of every query block here (H_i^T as bf16, Z_i) */

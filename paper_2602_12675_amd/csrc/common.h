@@ -66,8 +66,8 @@ __device__ __forceinline__ float load_elem(const uint16_t* p, size_t i) { return
 __device__ __forceinline__ void store_elem(float* p, size_t i, float v) { p[i] = v; }
 __device__ __forceinline__ void store_elem(uint16_t* p, size_t i, float v) { p[i] = f32_to_bf16_bits(v); }
 
-// Where sla2_forward keeps O^s, O^l ([BH, N, d], element type of out) and L ([BH, N]) for the backward
-// pass; all null when nothing is to be kept.  The bf16 kernels also keep the state of the linear branch
+// Where sla2_forward keeps O^s, O^l ([BH, N, d], element type of out; o_l may be null on its own) and
+// L ([BH, N]) for the backward pass; all null when nothing is to be kept.  The bf16 kernels also keep the state of the linear branch
 // per query block: H_i^T as bf16 [BH, T_m, d(e), d(c)] and Z_i [BH, T_m, d] (null for fp32 tensors, whose
 // backward pass rebuilds them).
 struct SavedForBackward {

@@ -121,7 +121,7 @@ static void make_layout(const Shape& s, sla2_ws_layout* L) {
   L->partial = take(BH * (size_t)s.chunks * (d * d + d) * sizeof(float));
   const size_t esz = s.bf16 ? 2 : 4;
   L->o_s = take(s.save ? BH * (size_t)s.N * d * esz : 0);
-  L->o_l = take(s.save ? BH * (size_t)s.N * d * esz : 0);
+  L->o_l = take(s.save && !s.bf16 ? BH * (size_t)s.N * d * esz : 0);   // bf16 tensors: rebuilt from H_i in the backward pass
   L->lse = take(s.save ? BH * (size_t)s.N * sizeof(float) : 0);
   L->bwd = take(s.save ? bwd_scratch_bytes(s) : 0);
   L->total = off;
@@ -305,6 +305,7 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
   if (s.save) {
     sv = SavedForBackward{at<void>(workspace, L.o_s), at<void>(workspace, L.o_l), at<float>(workspace, L.lse), nullptr, nullptr};
     if (s.bf16) {
+      sv.o_l = nullptr;
       const BwdLayout B = make_bwd_layout(s);
       sv.h_i = (uint16_t*)(at<char>(workspace, L.bwd) + B.h_i);
       sv.z_i = (float*)(at<char>(workspace, L.bwd) + B.z_i);

@@ -42,8 +42,8 @@ template <int D, int BQ> struct BwdQSmem {
 template <int D, int BQ>
 __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
-    const uint16_t* __restrict__ dout, const uint16_t* __restrict__ o_s, const uint16_t* __restrict__ o_l,
-    const float* __restrict__ lse, const double* __restrict__ k_mean, const uint16_t* __restrict__ h_i,
+    const uint16_t* __restrict__ dout, const uint16_t* __restrict__ o_s, const float* __restrict__ lse,
+    const double* __restrict__ k_mean, const uint16_t* __restrict__ h_i,
     const float* __restrict__ z_i, const int32_t* __restrict__ block_idx, const float* __restrict__ alpha,
     uint16_t* __restrict__ dq, float* __restrict__ ds_out, float* __restrict__ lraw_out, uint16_t* __restrict__ dh_out,
     float* __restrict__ dz_out, float* __restrict__ dalpha_part, Strides sin, Strides sout, int H, int N, int Tm, int Tn,
@@ -98,44 +98,27 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
   if (ntiles > 0) dma(j_cur, 0);
   if (tid < D) mus[tid] = (float)k_mean[(size_t)bh * D + tid];
 
-  // ---- prologue: Q and dO as B-operand fragments (alpha is applied to the products); D^s, D^l, the d alpha part ----
+  // ---- prologue: Q and dO as B-operand fragments (alpha is applied to the products); dO . O^s per row ----
   bf16x8 qf[KS], gof[KS];
-  float Ds = 0.f, Dl = 0.f, mix = 0.f;
+  float dot_s = 0.f;                                 // dO . O^s of this lane's row;  D^s = alpha dot_s
   {
     const uint16_t* qsrc = qh + (size_t)(row0 + r_ld) * tok_stride + 8 * g;
     const uint16_t* gsrc = doh + (size_t)(row0 + r_ld) * sout.n + 8 * g;
     const uint16_t* ossrc = o_s + ((size_t)bh * N + row0 + r_ld) * D + 8 * g;
-    const uint16_t* olsrc = o_l + ((size_t)bh * N + row0 + r_ld) * D + 8 * g;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
       qf[ks] = *reinterpret_cast<const bf16x8*>(qsrc + 16 * ks);
       gof[ks] = *reinterpret_cast<const bf16x8*>(gsrc + 16 * ks);
       const bf16x8 os = *reinterpret_cast<const bf16x8*>(ossrc + 16 * ks);
-      const bf16x8 ol = *reinterpret_cast<const bf16x8*>(olsrc + 16 * ks);
 #pragma unroll
-      for (int e = 0; e < 8; e++) {
-        const float gv = (float)gof[ks][e], osv = (float)os[e], olv = (float)ol[e];
-        Ds += al * gv * osv;
-        Dl += (1.f - al) * gv * olv;
-        mix += gv * (osv - olv);
-      }
+      for (int e = 0; e < 8; e++) dot_s += (float)gof[ks][e] * (float)os[e];
     }
   }
-  Ds = half_sum(Ds);
-  Dl = half_sum(Dl);
-  if (!row_ok) mix = 0.f;
-#pragma unroll
-  for (int o = 1; o < kWave; o <<= 1) mix += __shfl_xor(mix, o);
-  if (lane == 0) red[w] = mix;
+  dot_s = half_sum(dot_s);
+  const float Ds = al * dot_s;
   const float L = lse[(size_t)bh * N + row0 + r_ld];
   __builtin_amdgcn_s_waitcnt(kVmcnt0);               // tile 0 and everything above have landed
-  __syncthreads();                                   // ... for everyone; mus and red are visible
-  if (tid == 0) {
-    float t = 0.f;
-#pragma unroll
-    for (int x = 0; x < NW; x++) t += red[x];
-    dalpha_part[slot] = t;
-  }
+  __syncthreads();                                   // ... for everyone; mus is visible
   // The forward pass defines L on the smoothed keys; the products below use the raw K, whose scores are
   // larger by q . colmean(K) / sqrt(d) in every column of a row.
   float qmu = 0.f;
@@ -317,7 +300,6 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
       *reinterpret_cast<bf16x8*>(tb + qrow * LD + 16 * ks + 8 * g) = wv;
     }
   }
-  if (g == 0) dls[qrow] = Dl;
   // dQ^phi^T = (1 - alpha) H_i dO^T: A = H_i read transposed out of the H_i^T tile, B = the dO fragments
   f32x16 dqp[ET];
 #pragma unroll
@@ -329,6 +311,26 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
 #pragma unroll
     for (int ct = 0; ct < ET; ct++) dqp[ct] = mfma_bf16(nat_fragment<PL>(ta, ks, 32 * ct, lane), gof[ks], dqp[ct]);
   __syncthreads();                                   // w complete; nobody reads H_i^T any more
+  // O^l is not kept by the forward pass: dO . O^l of a row equals sum_c w[r][c] (H_i dO^T)[c][r], both at
+  // hand.  D^l = (1 - alpha) dO . O^l; the row's part of d alpha is dO . (O^s - O^l).
+  float dot_l = 0.f;
+#pragma unroll
+  for (int ct = 0; ct < ET; ct++)
+#pragma unroll
+    for (int v4 = 0; v4 < 4; v4++) {
+      const bf16x4 wq = *reinterpret_cast<const bf16x4*>(tb + qrow * LD + 32 * ct + 8 * v4 + 4 * g);
+#pragma unroll
+      for (int r = 0; r < 4; r++) dot_l += (float)wq[r] * dqp[ct][4 * v4 + r];
+    }
+  dot_l = half_sum(dot_l);
+  const float Dl = (1.f - al) * dot_l;
+  if (g == 0) dls[qrow] = Dl;
+  {
+    float mix = (row_ok && g == 0) ? dot_s - dot_l : 0.f;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) mix += __shfl_xor(mix, o);
+    if (lane == 0) red[w] = mix;
+  }
   float dot = 0.f;
 #pragma unroll
   for (int ct = 0; ct < ET; ct++)
@@ -355,7 +357,13 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
         pk[r] = (__bf16)(dqacc[et][4 * v4 + r] + (float)wq[r] * den * (dqp[et][4 * v4 + r] - dot));
       *reinterpret_cast<bf16x4*>(ta + qrow * LD + 32 * et + 8 * v4 + 4 * g) = pk;
     }
-  __syncthreads();                                   // dQ tile complete
+  __syncthreads();                                   // dQ tile complete; the waves' d alpha parts are visible
+  if (tid == 0) {
+    float t = 0.f;
+#pragma unroll
+    for (int x = 0; x < NW; x++) t += red[x];
+    dalpha_part[slot] = t;
+  }
   {
     uint16_t* dst = dq + head_offset(sin, bh, H) + (size_t)row0 * tok_stride;
     for (int idx = tid; idx < BQ * (D / 8); idx += NT) {
@@ -404,7 +412,7 @@ static hipError_t launch_bwd_q_mfma(const Shape& s, const BwdArgs& a, hipStream_
   const int grid = ((s.Tm + kXcds - 1) / kXcds) * kXcds * s.BH;
   bwd_q_mfma_kernel<D, BQ><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(
       (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.dout, (const uint16_t*)a.o_s,
-      (const uint16_t*)a.o_l, a.lse, a.k_mean, a.h_i, a.z_i, a.block_idx, a.alpha, (uint16_t*)a.dq, a.ds, a.lraw,
+      a.lse, a.k_mean, a.h_i, a.z_i, a.block_idx, a.alpha, (uint16_t*)a.dq, a.ds, a.lraw,
       (uint16_t*)a.dh, a.dz, a.dalpha_part, s.sin, s.sout, s.H, s.N, s.Tm, s.Tn, s.k, s.alpha_per_block ? 1 : 0);
   return hipGetLastError();
 }

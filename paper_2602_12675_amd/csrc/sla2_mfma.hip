@@ -902,9 +902,9 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     }
   }
   if (o_s_save != nullptr) {
-    // the two branches on their own ([BH, N, d] contiguous), kept for the backward pass: same route
-    // through the transposing tile as the mixed output
-    for (int which = 0; which < 2; which++) {
+    // O^s (and O^l, if asked for) on its own ([BH, N, d] contiguous), kept for the backward pass: same
+    // route through the transposing tile as the mixed output
+    for (int which = 0; which < (o_l_save != nullptr ? 2 : 1); which++) {
       __syncthreads();                                 // the tile has been read out
 #pragma unroll
       for (int et = 0; et < ET; et++)
