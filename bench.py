@@ -8,8 +8,10 @@ mix) on a synthetic Wan2.1-1.3B-shaped input set (B=1, H=12, N=32760, d=128,
 b_q=128, b_kv=64, 3 % of the key blocks kept = 97 % sparsity) that is already
 resident in HBM.  Prints ONE JSON line: dense-equivalent TFLOP/s (4 N^2 d H B / t,
 the paper's C/t), ms per call, the roofline entry of the dominant kernel measured
-live with HIP events, the per-kernel breakdown, the in-build dense bf16 attention
-on the same inputs, and the CPU oracle timed on a bounded sample.
+live with HIP events (against the matrix-core peak, and against the bytes it has to
+gather), the per-kernel breakdown, the in-build dense bf16 attention on the same
+inputs, the training path (forward keeping its intermediates + sla2_backward; not
+part of `value`), and the CPU oracle timed on the same workload.
 """
 from __future__ import annotations
 
