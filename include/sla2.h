@@ -1,5 +1,5 @@
 /*
- * libsla2 - SLA2 attention forward pass on MI355X (gfx950), C ABI.
+ * libsla2 - SLA2 attention (forward pass, and its backward pass) on MI355X (gfx950), C ABI.
  *
  * The operator is  O = SLA2(Q, K, V, k%, R, alpha)  of the paper
  * "SLA2: Sparse-Linear Attention with Learnable Routing and QAT":
@@ -10,11 +10,12 @@
  *   M   = expansion of M_c = Top-k(k%, proj_q(pool Q) proj_k(pool K)^T)   (Eq. 15-16)
  *
  * computed block-wise as in the paper's forward algorithm (Alg. 2), with K
- * first replaced by K - colmean(K).
+ * first replaced by K - colmean(K).  sla2_backward returns the gradients of
+ * Q, K, V and alpha (Alg. 3).
  *
  * Conventions for every entry point
- *   - q, k, v, out are DEVICE pointers to contiguous [B, H, N, d] tensors of
- *     params->dtype; router_w, alpha, block_idx, lse, workspace are DEVICE
+ *   - q, k, v, out are DEVICE pointers to [B, H, N, d] tensors of params->dtype,
+ *     contiguous unless params->in_stride / out_stride say otherwise; router_w, alpha, block_idx, lse, workspace are DEVICE
  *     pointers; params is a HOST pointer.  All memory is owned by the caller;
  *     the library allocates nothing, frees nothing and never synchronises.
  *   - All work is enqueued on `hip_stream` (a hipStream_t passed as void*;
@@ -43,7 +44,7 @@ typedef enum {
   SLA2_EINVAL = -1,       /* null pointer, non-positive size, topk_frac outside [0,1], bad enum */
   SLA2_EUNSUPPORTED = -2, /* a shape / mode combination the kernels do not cover (see sla2_params) */
   SLA2_EWORKSPACE = -3,   /* workspace null, misaligned or smaller than sla2_workspace_bytes() */
-  SLA2_EALIAS = -4,       /* out overlaps q, k or v */
+  SLA2_EALIAS = -4,       /* an output overlaps an input (or another output) */
   SLA2_EHIP = -5          /* a kernel launch failed */
 } sla2_status;
 
