@@ -492,6 +492,51 @@ def test_backward_central_differences():
         assert abs(fd - g[name][idx]) < 1e-7 * max(1.0, abs(fd)), (name, idx, fd, g[name][idx])
 
 
+@pytest.mark.parametrize("quant", [O.QUANT_FP8, O.QUANT_INT8, O.QUANT_FP8_V])
+def test_backward_after_a_low_bit_forward(quant):
+    """Sec. 5: the backward pass runs in high precision on the original Q, K, V and takes from a low-bit
+    forward only that forward's outputs.  Against the backward of the exact forward: nothing of the
+    linear branch moves; the sparse branch moves exactly as the N x N expanded form says when its L and
+    O^s are replaced by the low-bit forward's (P = exp(S - L), D^s = rowsum(dO^s (.) O^s))."""
+    N, d, bq, bk = 96, 16, 32, 16
+    Q, K, V, Wq, Wk = rand_head(50, N, d)
+    rng = np.random.default_rng(51)
+    alpha = 0.4
+    T_n = O.num_blocks(N, bk)
+    Ks = O.smooth_k(K)
+    sel = O.topk_rows(O.router_scores(Q, Ks, Wq, Wk, bq, bk), O.num_selected(0.34, T_n))
+    dO = rng.normal(size=(N, d))
+    g0 = O.backward_head(Q, K, V, sel, alpha, dO, bq, bk)
+    g8 = O.backward_head(Q, K, V, sel, alpha, dO, bq, bk, quant=quant)
+    assert np.array_equal(g0["Dl"], g8["Dl"]) and np.array_equal(g0["dQphi"], g8["dQphi"])
+    assert np.array_equal(g0["dKphi"], g8["dKphi"])
+    ex = O.forward_head(Q, K, V, Wq, Wk, alpha, 0.34, bq, bk, sel=sel)
+    lo = O.forward_head(Q, K, V, Wq, Wk, alpha, 0.34, bq, bk, sel=sel, quant=quant)
+    assert not np.array_equal(ex["O_s"], lo["O_s"])
+    M = np.kron(O.mask_from_sel(sel, T_n), np.ones((bq, bk), dtype=bool))[:N, :N]
+    S = Q @ Ks.T / math.sqrt(d)
+    dOs = alpha * dO
+    dP = dOs @ V.T
+
+    def sparse_terms(L, Os):
+        P = np.where(M, np.exp(S - L[:, None]), 0.0)
+        dS = P * (dP - (dOs * Os).sum(axis=1)[:, None])
+        return P.T @ dOs, dS @ Ks / math.sqrt(d), dS.T @ Q / math.sqrt(d)
+
+    dv0, dq0, dk0 = sparse_terms(ex["L"], ex["O_s"])
+    dv8, dq8, dk8 = sparse_terms(lo["L"], lo["O_s"])
+    np.testing.assert_allclose(g8["dV"] - g0["dV"], dv8 - dv0, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(g8["dQ"] - g0["dQ"], dq8 - dq0, rtol=0, atol=1e-12)
+    dk_shift = dk8 - dk0
+    np.testing.assert_allclose(g8["dK"] - g0["dK"], dk_shift - dk_shift.mean(axis=0, keepdims=True), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(g8["dalpha"].sum() - g0["dalpha"].sum(), (dO * (lo["O_s"] - ex["O_s"])).sum(), rtol=0, atol=1e-12)
+    # and the move is of the size of the forward's own quantisation error, not more
+    fwd_err = np.linalg.norm(lo["O_s"] - ex["O_s"]) / np.linalg.norm(ex["O_s"])
+    for name in ("dQ", "dK", "dV"):
+        move = np.linalg.norm(g8[name] - g0[name]) / np.linalg.norm(g0[name])
+        assert 0.0 < move <= 20.0 * fwd_err, (name, move, fwd_err)
+
+
 # ---- SoftTop-k (Sec. 6.1) ---------------------------------------------------- #
 def test_soft_topk_row_sums_range_and_order():
     rng = np.random.default_rng(30)
