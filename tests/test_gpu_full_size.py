@@ -143,3 +143,32 @@ def test_backward_ragged_75601():
         tail = slice(w.N - 17, w.N)                        # the short last key block / the end of the last query block
         assert rel(r[name][0, h][tail], g["d" + name[1].upper()][tail]) <= 3e-2
     np.testing.assert_allclose(r["dalpha"][h], g["dalpha"].sum(), rtol=3e-2, atol=3e-2 * abs(g["dalpha"].sum()))
+
+
+def test_maximum_number_of_key_blocks_forward_and_backward():
+    """T_n = 2048 key blocks, the limit of the interface (131,072 tokens, 1024 query blocks, 64 mask words per
+    row): mask, output and L of the whole head, then every gradient row, against the oracle (about half a
+    minute of oracle)."""
+    import torch
+    import sla2_oracle as O
+    from paper_2602_12675_amd import api
+    from test_gpu_backward import rel, run_fwd_bwd
+    w = W.TINY.replace(name="max-blocks", grid=(32, 64, 64), d=64, dtype="bf16", H=1, topk_frac=0.005, block_q=128,
+                       per_head_freq=True)
+    assert w.T_n == 2048 and w.k == 10
+    inp = W.generate(w)
+    r = run_forward(api, torch, inp)
+    o = oracle_heads(inp, heads=[(0, 0)])[(0, 0)]
+    assert check_mask(r["idx"][0, 0], o["R"], o["sel"]) == 0
+    assert rel_l2(r["out"][0, 0], o["O"]) <= 2e-2
+    np.testing.assert_allclose(r["lse"][0, 0], o["L"], rtol=0, atol=3e-2)
+    dout = W.f32_to_bf16_bits(np.random.default_rng(13).normal(size=(w.B, w.H, w.N, w.d)).astype(np.float32))
+    alpha = inp.alpha.astype(np.float32)
+    g_gpu = run_fwd_bwd(api, torch, inp, alpha, False, True, dout)
+    Q, K, V = (inp.values(n, 0, 0) for n in ("q", "k", "v"))
+    g = O.backward_head(Q, K, V, g_gpu["idx"][0, 0], float(alpha[0]), g_gpu["go"][0, 0].astype(np.float64), w.block_q, w.block_kv)
+    for name in ("dq", "dk", "dv"):
+        e = rel(g_gpu[name][0, 0], g["d" + name[1].upper()])
+        print("%s %s rel-L2 %.4f" % (w.name, name, e))
+        assert e <= 2e-2, (name, e)
+    np.testing.assert_allclose(g_gpu["dalpha"][0], g["dalpha"].sum(), rtol=3e-2, atol=3e-2 * abs(g["dalpha"].sum()))
