@@ -90,7 +90,7 @@ def cpu_baseline(inp, heads):
                       % (heads, w.B * w.H, dt, dt / heads * w.B * w.H * 1e3)}
 
 
-def backward_timing(api, W, torch, w, inp, dt, qm, tensors, rw, al, stream, ksel, reps=20):
+def backward_timing(api, W, torch, w, inp, dt, qm, tensors, rw, al, stream, ksel, reps=40):
     """Times sla2_forward with SLA2_FLAG_SAVE_FOR_BACKWARD and sla2_backward on the bench workload (contiguous
     layout).  Not part of `value`; a reported figure for the training path (Alg. 3)."""
     import numpy as np
@@ -107,7 +107,7 @@ def backward_timing(api, W, torch, w, inp, dt, qm, tensors, rw, al, stream, ksel
     ws = api.alloc_workspace(p)
 
     def timed(f):
-        for _ in range(3):
+        for _ in range(15):                            # the clocks settle over a few dozen calls
             f()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
