@@ -617,6 +617,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     float rs = 0.f;
     bf16x8 pf[FP8V ? 1 : 4];                         // P^T fragments, token order
     i32x8 pb;                                        // FP8V: the e4m3 codes of P^T, byte 16 mt + e of the lane's half
+    int codes = 0;
 #pragma unroll
     for (int mt = 0; mt < 2; mt++)
 #pragma unroll
@@ -629,7 +630,9 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
           if (e % 4 == 0) pb[q] = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, 0, false);
           else pb[q] = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, pb[q], true);
         } else if constexpr (FP8) {
-          const int codes = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, 0, false);       // quant(P): e4m3 grid
+          // quant(P): e4m3 grid.  The instruction keeps the other half of its destination; feeding it the
+          // previous pair's register (dead by now) instead of a zero saves a register move per pair
+          codes = __builtin_amdgcn_cvt_pk_fp8_f32(p0, p1, codes, false);
           typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
           const bf16x2 pq = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(codes, 1.0f, false);
           pf[2 * mt + e / 8][e % 8] = pq[0];
