@@ -9,6 +9,10 @@
 // Phase markers for timing experiments; compiled out unless a harness defines them.
 #ifndef SLA2_PHASE_MARK
 #define SLA2_PHASE_MARK(i)
+#define SLA2_PHASE_DECL
+#endif
+#ifndef SLA2_PHASE_MARK_KV
+#define SLA2_PHASE_MARK_KV(i)
 #endif
 
 namespace sla2 {

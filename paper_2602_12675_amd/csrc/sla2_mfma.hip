@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
   }
   for (int j = j0; j < j1; j++) {
     const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
-    SLA2_PHASE_MARK(0)
+    SLA2_PHASE_MARK_KV(0)
     __syncthreads();                                   // previous tile fully consumed
     TC::store(kr, ktile, tid);
     TC::store(vr, vtile, tid);
@@ -115,7 +115,7 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
       TC::load(vr, vh + (size_t)(j + 1) * kTileTokens * sin.n, sin.n, nvalid, tid);
     }
     __syncthreads();
-    SLA2_PHASE_MARK(1)
+    SLA2_PHASE_MARK_KV(1)
     {  // per-token log-partition of softmax_d(k'), 4 threads per token
       const int t = tid / 4, sub = tid % 4;
       float x[D / 4];
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
       }
     }
     __syncthreads();
-    SLA2_PHASE_MARK(2)
+    SLA2_PHASE_MARK_KV(2)
     // K^phi fragments (kept for the attention kernel), h += K^phi^T V on the matrix cores, z_j
     float zsum[HS::kMtw];
 #pragma unroll
@@ -257,7 +257,7 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
       zacc[a] += z;
       if (g == 0 && nt0 == 0) z_blocks[((size_t)bh * Tn + j) * D + 32 * (mt0 + a) + lane] = z;
     }
-    SLA2_PHASE_MARK(3)
+    SLA2_PHASE_MARK_KV(3)
   }
   float* ph = partial + (size_t)blockIdx.x * (D * D + D);
 #pragma unroll
@@ -414,6 +414,31 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       qf[ks] = *reinterpret_cast<const bf16x8*>(
           src + (INT8 ? 32 * (ks / 2) + 16 * g + 8 * (ks % 2) : FP8 ? 64 * (ks / 4) + 32 * g + 8 * (ks % 4) : 16 * ks + 8 * g));
   }
+  // The state accumulators start at -H_total (and -Z_total): the loop adds the h_j and z_j of the selected
+  // blocks, which leaves -(H_total - sum) = -H_i.  The d x d total is read here, behind the first tile's
+  // transfer, instead of in the epilogue, where a wave would wait for it with nothing else to do.
+  f32x16 hacc[HS::kMtw][HS::kNtw];
+  float zsel[HS::kMtw];
+#pragma unroll
+  for (int a = 0; a < HS::kMtw; a++) {
+    zsel[a] = 0.f;
+#pragma unroll
+    for (int b = 0; b < HS::kNtw; b++)
+#pragma unroll
+      for (int e = 0; e < 16; e++) hacc[a][b][e] = 0.f;
+  }
+  if constexpr (!DENSE) {
+    const float* htot = h_total + (size_t)bh * D * D;
+#pragma unroll
+    for (int a = 0; a < HS::kMtw; a++) {
+#pragma unroll
+      for (int b = 0; b < HS::kNtw; b++)
+#pragma unroll
+        for (int e = 0; e < 16; e++)
+          hacc[a][b][e] = -htot[(32 * (mt0 + a) + 8 * (e / 4) + 4 * g + e % 4) * D + 32 * (nt0 + b) + lane % 32];
+      zsel[a] = -z_total[(size_t)bh * D + 32 * (mt0 + a) + lane % 32];
+    }
+  }
   // Everything issued so far is settled here, on every path into the main loop; a pending load
   // left over from the prologue would otherwise put a vmcnt wait in front of every use of a Q
   // fragment inside the loop and drain the tile prefetch with it.
@@ -462,22 +487,13 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   for (int et = 0; et < ET; et++)
 #pragma unroll
     for (int e = 0; e < 16; e++) oacc[et][e] = 0.f;
-  f32x16 hacc[HS::kMtw][HS::kNtw];
-  float zsel[HS::kMtw];
-#pragma unroll
-  for (int a = 0; a < HS::kMtw; a++) {
-    zsel[a] = 0.f;
-#pragma unroll
-    for (int b = 0; b < HS::kNtw; b++)
-#pragma unroll
-      for (int e = 0; e < 16; e++) hacc[a][b][e] = 0.f;
-  }
   // running max and sum of this lane's query row, in the log2 domain.  In FP8 mode P is carried
   // scaled by 2^8 (the rounding grid of P, see sla2.h): the factor cancels in O / l.
   float m_run = -INFINITY, l_run = 0.f;
   constexpr float kPShift = FP8 ? 8.f : 0.f;
   const float c0 = kLog2e * rsqrtf((float)D);        // scores are used as S * log2(e) / sqrt(d)
 
+  SLA2_PHASE_DECL
   for (int s = 0; s < ntiles; s++) {
     SLA2_PHASE_MARK(0)
     const int buf = s & 1;
@@ -496,20 +512,30 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     // use, which stalls every iteration on the tile that was just requested.
     bf16x8 kphi[DENSE ? 1 : HS::kMtw][kTileTokens / 16];
     float zj[DENSE ? 1 : HS::kMtw];
-    if constexpr (!DENSE) {
+    auto state_loads = [&]() {
+      if constexpr (!DENSE) {
 #pragma unroll
-      for (int a = 0; a < HS::kMtw; a++) {
+        for (int a = 0; a < HS::kMtw; a++) {
 #pragma unroll
-        for (int ks = 0; ks < kTileTokens / 16; ks++)
-          kphi[a][ks] = load_maybe_tracked<bf16x8, kManual>(k_phi + kphi_offset<D>(blk0 + j, mt0 + a, ks, lane));
-        zj[a] = load_maybe_tracked<float, kManual>(z_blocks + (blk0 + j) * D + 32 * (mt0 + a) + lane % 32);
-        if constexpr (!kManual) zsel[a] += zj[a];
+          for (int ks = 0; ks < kTileTokens / 16; ks++)
+            kphi[a][ks] = load_maybe_tracked<bf16x8, kManual>(k_phi + kphi_offset<D>(blk0 + j, mt0 + a, ks, lane));
+          zj[a] = load_maybe_tracked<float, kManual>(z_blocks + (blk0 + j) * D + 32 * (mt0 + a) + lane % 32);
+          if constexpr (!kManual) zsel[a] += zj[a];
+        }
       }
+    };
+    auto next_tile = [&]() {
+      if (s + 1 < ntiles) dma(j_nxt, buf ^ 1);       // next tile -> other buffer
+    };
+    // With the reads under this kernel's own control (low-bit modes) the requests for the rest of the
+    // tile's data are placed inside the score product: the fragment loads behind its operand reads, the
+    // next tile's transfer behind its matrix instructions - some hundred instructions that otherwise
+    // stand in front of it, on a wave whose progress is bound by its own chain of dependent steps.
+    constexpr bool kRequestsInsideScores = kManual;
+    if constexpr (!kRequestsInsideScores) {
+      state_loads();
+      next_tile();
     }
-
-    if (s + 1 < ntiles) dma(j_nxt, buf ^ 1);         // next tile -> other buffer
-    j_cur = j_nxt;
-    j_nxt = j_nn;
     const uint16_t* vt = vbuf(buf);
     // Two waves share a SIMD.  The one that is issuing matrix products is given the higher issue priority, so
     // that the matrix pipe is fed while the other wave's softmax fills the gaps (measured: 2 % on the
@@ -534,6 +560,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         kq[ks4][0] = lds_read16_untracked<0>(ka ^ (32u * ks4));
         kq[ks4][1] = lds_read16_untracked<32 * D>(ka ^ (32u * ks4));
       }
+      if constexpr (kRequestsInsideScores) state_loads();
       i32x16 iacc[2];
 #pragma unroll
       for (int mt = 0; mt < 2; mt++)
@@ -551,6 +578,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
                            (int)(unsigned)((unsigned long)qf8[2 * ks4 + 1]), (int)(unsigned)((unsigned long)qf8[2 * ks4 + 1] >> 32)};
           iacc[mt] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, iacc[mt], 0, 0, 0);
         }
+      if constexpr (kRequestsInsideScores) next_tile();
 #pragma unroll
       for (int mt = 0; mt < 2; mt++)
 #pragma unroll
@@ -570,6 +598,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         klo[ks2][1] = lds_read16_untracked<32 * D>(ka ^ (64u * ks2));
         khi[ks2][1] = lds_read16_untracked<32 * D + 16>(ka ^ (64u * ks2));
       }
+      if constexpr (kRequestsInsideScores) state_loads();
 #pragma unroll
       for (int ks2 = 0; ks2 < KS2; ks2++)
 #pragma unroll
@@ -587,6 +616,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
           }
           sacc[mt] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, sacc[mt], 0, 0, 0, 0, 0, 0);   // e4m3 x e4m3, no scales
         }
+      if constexpr (kRequestsInsideScores) next_tile();
     } else {
       const uint16_t* kt = reinterpret_cast<const uint16_t*>(kbuf(buf));
 #pragma unroll
@@ -595,6 +625,8 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         for (int mt = 0; mt < 2; mt++)
           sacc[mt] = mfma_bf16(row_fragment<SL>(kt, 32 * mt + lane % 32, 16 * ks + 8 * g), qf[ks], sacc[mt]);
     }
+    j_cur = j_nxt;
+    j_nxt = j_nn;
     if constexpr (!DENSE) __builtin_amdgcn_s_setprio(0);   // softmax: the other wave's matrix products go first
     SLA2_PHASE_MARK(1)
     // ---- online softmax of this lane's query row over the 64 keys ----
@@ -797,12 +829,13 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
   }
+  SLA2_PHASE_MARK(6)
   uint16_t* ht = reinterpret_cast<uint16_t*>(smem);  // H_i^T as bf16 [e][c], row stride LD
   uint16_t* os = ht + D * LD;                        // output tile [BQ][LD]
   f32x16 lacc[ET];
   float inv_den = 0.f;
   if constexpr (!DENSE) {
-    const float* htot = h_total + (size_t)bh * D * D;
+    // H_i^T = -(accumulated)^T as bf16, Z_i likewise
 #pragma unroll
     for (int a = 0; a < HS::kMtw; a++) {
 #pragma unroll
@@ -813,16 +846,14 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
           const int cc = 32 * (mt0 + a) + 8 * v4 + 4 * g;
           bf16x4 pk;
 #pragma unroll
-          for (int r = 0; r < 4; r++) pk[r] = (__bf16)(htot[(cc + r) * D + e_col] - hacc[a][b][4 * v4 + r]);
+          for (int r = 0; r < 4; r++) pk[r] = (__bf16)(-hacc[a][b][4 * v4 + r]);
           *reinterpret_cast<bf16x4*>(ht + e_col * LD + cc) = pk;
         }
       }
       // zsel holds the same sum on both lane halves (each half added z_j of channel l % 32)
-      if (g == 0 && nt0 == 0) {
-        const int c = 32 * (mt0 + a) + lane;
-        zs[c] = z_total[(size_t)bh * D + c] - zsel[a];
-      }
+      if (g == 0 && nt0 == 0) zs[32 * (mt0 + a) + lane] = -zsel[a];
     }
+    SLA2_PHASE_MARK(7)
     // Q^phi = softmax_d(Q) of this lane's row, kept as fragments
     float qx[KS][8];
     float qm = -INFINITY;
@@ -844,7 +875,9 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       }
     qs = half_sum(qs);
     const float qinv = 1.f / qs;
+    SLA2_PHASE_MARK(8)
     __syncthreads();                                 // H_i^T and Z_i visible
+    SLA2_PHASE_MARK(9)
     float den = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
@@ -871,6 +904,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       }
     }
   }
+  SLA2_PHASE_MARK(10)
   // ---- mix (Eq. 13), transpose through LDS, coalesced store ----
   const float al = DENSE ? 1.f : alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
   const float ws = al * inv_l * (FP8V ? sv_prev : 1.f), wl = (1.f - al) * inv_den;   // FP8V: back from the last tile's V scale
@@ -888,6 +922,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       *reinterpret_cast<bf16x4*>(os + qrow * LD + 32 * et + 8 * v4 + 4 * g) = pk;
     }
   __syncthreads();
+  SLA2_PHASE_MARK(11)
   uint16_t* oh = out + head_offset(sout, bh, H) + (size_t)row0 * sout.n;
   for (int idx = tid; idx < BQ * (D / 8); idx += NT) {
     const int r = idx / (D / 8), ch = idx % (D / 8);
@@ -932,7 +967,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       }
     }
   }
-  SLA2_PHASE_MARK(6)
+  SLA2_PHASE_MARK(12)
 }
 
 struct AttnArgs {
