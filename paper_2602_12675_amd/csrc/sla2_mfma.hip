@@ -892,17 +892,18 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     }
     den = half_sum(den);
     inv_den = ksel >= Tn ? 0.f : 1.f / den;          // every block selected: nothing left for the linear branch
-    // O_l^T = H_i^T Q^phi^T
+    // O_l^T = H_i^T Q^phi^T (the four accumulators take turns, so that no product waits for the one before it)
 #pragma unroll
-    for (int et = 0; et < ET; et++) {
+    for (int et = 0; et < ET; et++)
 #pragma unroll
       for (int e = 0; e < 16; e++) lacc[et][e] = 0.f;
 #pragma unroll
-      for (int ks = 0; ks < KS; ks++) {
+    for (int ks = 0; ks < KS; ks++)
+#pragma unroll
+      for (int et = 0; et < ET; et++) {
         bf16x8 a = *reinterpret_cast<const bf16x8*>(ht + (32 * et + lane % 32) * LD + 16 * ks + 8 * g);
         lacc[et] = mfma_bf16(a, qf[ks], lacc[et]);
       }
-    }
   }
   SLA2_PHASE_MARK(10)
   // ---- mix (Eq. 13), transpose through LDS, coalesced store ----
