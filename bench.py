@@ -267,6 +267,10 @@ def main():
                                   "frac": round(gather_gbs / HBM_PEAK_GBS, 4), "algorithmic_bytes": gather_bytes,
                                   "note": "K and V tiles of every selected pair + Q + out over the same kernel time; "
                                           "most tiles are served by L2 / Infinity Cache (see traffic)"}
+    if roofline["traffic"]:
+        # what the counters saw leave L2 for the fabric (profiles/), over the kernel time measured here
+        t_gbs = roofline["traffic"] / (attn_ms * 1e-3) / 1e9
+        roofline["traffic_rate"] = {"GB/s": round(t_gbs, 1), "frac_of_hbm_peak": round(t_gbs / HBM_PEAK_GBS, 4)}
     qk_bytes = 2.0 * BH * w.N * w.d * esz
     hbm = {}
     if "block_sums" in stages:
