@@ -80,11 +80,7 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
   const uint16_t* doh = dout + head_offset(sout, bh, H);
   const int tok_stride = sin.n;
   const int32_t* sel = block_idx + ((size_t)bh * Tm + i) * ksel;
-#ifdef SLA2_EXP_Q_NO_LOOP
-  const int ntiles = 0;
-#else
   const int ntiles = ksel;
-#endif
   const float al = alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
   const float rscale = rsqrtf((float)D);
   const size_t slot = (size_t)bh * Tm + i;
@@ -495,11 +491,7 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_mfma_kernel(
   const int32_t* cp = col_ptr + (size_t)bh * (Tn + 1);
   const int32_t* ci = col_idx + (size_t)bh * Tm * ksel;
   const int l0 = __builtin_amdgcn_readfirstlane(cp[j]), l1 = __builtin_amdgcn_readfirstlane(cp[j + 1]);
-#ifdef SLA2_EXP_NO_LOOP
-  const int nsteps = 0;
-#else
   const int nsteps = (l1 - l0) * HP;
-#endif
 
   // Step t covers rows [64 (t % HP), +64) of query block ci[l0 + t / HP].  A half block with no rows
   // (short last query block) still runs, on the block's first rows with every probability masked.
@@ -561,9 +553,7 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_mfma_kernel(
     Step nxt = cur;
     if (t + 1 < nsteps) {
       nxt = place(t + 1, i_nxt);
-#ifndef SLA2_EXP_NO_DMA
       request(nxt, buf ^ 1);
-#endif
     }
     i_nxt = block_of(t + 2);
     const unsigned qa = lds_address(qbuf(buf)), ga = lds_address(gbuf(buf));
@@ -677,11 +667,7 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_mfma_kernel(
       for (int e = 0; e < 4; e++) { acc[n][e] = all_selected ? 0.f : a[e]; acc[n][4 + e] = all_selected ? 0.f : b[e]; }
     }
     float dzj = (tid < D && !all_selected) ? dz_total[(size_t)bh * D + tid] : 0.f;
-#ifndef SLA2_EXP_NO_GATHER
     if (!all_selected)
-#else
-    if (false)
-#endif
       for (int l = l0; l < l1; l++) {
         const size_t slot = (size_t)bh * Tm + ci[l];
         const uint16_t* src = dh_in + slot * D * D;
