@@ -854,7 +854,8 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       if (g == 0 && nt0 == 0) zs[32 * (mt0 + a) + lane] = -zsel[a];
     }
     SLA2_PHASE_MARK(7)
-    // Q^phi = softmax_d(Q) of this lane's row, kept as fragments
+    // Q^phi = softmax_d(Q) of this lane's row, kept as fragments - without its normaliser, which cancels
+    // between Q^phi H_i and Q^phi Z_i
     float qx[KS][8];
     float qm = -INFINITY;
 #pragma unroll
@@ -865,16 +866,10 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         qm = fmaxf(qm, qx[ks][e]);
       }
     qm = half_max(qm);
-    float qs = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++)
 #pragma unroll
-      for (int e = 0; e < 8; e++) {
-        qx[ks][e] = fast_exp2((qx[ks][e] - qm) * kLog2e);
-        qs += qx[ks][e];
-      }
-    qs = half_sum(qs);
-    const float qinv = 1.f / qs;
+      for (int e = 0; e < 8; e++) qx[ks][e] = fast_exp2((qx[ks][e] - qm) * kLog2e);
     SLA2_PHASE_MARK(8)
     __syncthreads();                                 // H_i^T and Z_i visible
     SLA2_PHASE_MARK(9)
@@ -885,7 +880,6 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       const f32x4 z1 = *reinterpret_cast<const f32x4*>(zs + 16 * ks + 8 * g + 4);
 #pragma unroll
       for (int e = 0; e < 8; e++) {
-        qx[ks][e] *= qinv;
         den += qx[ks][e] * (e < 4 ? z0[e] : z1[e - 4]);
         qf[ks][e] = (__bf16)qx[ks][e];
       }
