@@ -24,3 +24,32 @@ def test_workloads_offered_are_the_benchmark_configurations():
     assert (w.B, w.H, w.N, w.d) == (1, 40, 75600, 128)
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--help"], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0 and "--workload" in r.stdout and "--steps" in r.stdout and "--warmup" in r.stdout
+
+
+import json
+
+import pytest
+
+
+@pytest.mark.gpu
+def test_result_line_carries_the_required_objects():
+    """One short run on the benchmark workload: a single JSON line with the metric, the roofline of the
+    attention kernel and the oracle's time on the host cores."""
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--steps", "4", "--warmup", "2", "--cpu-heads", "1",
+                        "--no-backward"], capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [l for l in r.stdout.splitlines() if l.startswith("{")]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 4 and d["warmup"] == 2 and d["vs_baseline"] is None
+    assert d["config"]["workload"] == "wan1.3b-97-fp8" and d["data"] == "synthetic" and d["dtype"] == "fp8"
+    assert abs(d["value"] - 4.0 * 32760 ** 2 * 128 * 12 / (d["ms_per_step"] * 1e-3) / 1e12) / d["value"] < 1e-3
+    roof = d["roofline"]
+    assert roof["bound"] in ("hbm", "mfma") and roof["unit"] in ("GB/s", "TFLOP/s")
+    assert abs(roof["frac"] - roof["achieved"] / roof["peak"]) < 1e-3 and 0 < roof["frac"] < 1
+    assert roof["traffic"] is None or roof["traffic"] > 0
+    cpu = d["cpu_baseline"]
+    assert cpu["kind"] == "oracle" and cpu["cores"] >= 1 and cpu["value"] > 0 and cpu["sample"]
