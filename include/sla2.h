@@ -151,7 +151,7 @@ int sla2_num_selected(const sla2_params* params);
 int sla2_router(const sla2_params* params, const void* q, const void* k, const float* router_w,
                 int32_t* block_idx, void* workspace, size_t workspace_bytes, void* hip_stream);
 
-/* SoftTop-k form of the router (Sec. 6.1: the differentiable operator that replaces Top-k in the
+/* SoftTop-k form of the router (Sec. 6: the differentiable operator that replaces Top-k in the
  * first training stage):  mask[b,h,i,j] = sigmoid(P_c[i,j] / tau + lambda_i), P_c the row softmax
  * of the router scores of Eq. 16 (with the 1/sqrt(d) of Alg. 2), lambda_i found by bisection so that
  * row i sums to k = sla2_num_selected(params); k = 0 gives zeros, k = T_n ones.  fp64 inside.
@@ -179,7 +179,7 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
 
 /* Backward pass (Alg. 3 of the appendix, plus the steps it leaves to automatic differentiation: phi,
  * the smoothing of K, the mix of Eq. 13): gradients of q, k, v and alpha for the block mask of the
- * matching forward call (hard Top-k passes no gradient to the router, Sec. 6.1).  Taken from the
+ * matching forward call (hard Top-k passes no gradient to the router, Sec. 6).  Taken from the
  * original q, k, v whatever quant_mode the forward ran in (Sec. 5): fp32 arithmetic for fp32 tensors;
  * for bf16 tensors the products run on the matrix cores (bf16 operands, fp32 accumulation) and
  * everything between them is fp32.
@@ -191,18 +191,20 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
  *                    each other or any input (they may be the slices of one packed [B, N, x, H, d]
  *                    buffer: interleaved, sharing no element)
  *   dalpha           DEVICE float [H] or [H, T_m] (alpha_per_block), written
- * Deterministic (no atomics).  Errors as sla2_forward; SLA2_EINVAL without the flag. */
+ * Deterministic: fixed summation orders; the only atomic is an order-independent OR on LDS words.  Errors as sla2_forward; SLA2_EINVAL without the flag. */
 int sla2_backward(const sla2_params* params, const void* q, const void* k, const void* v, const float* alpha,
                   const void* dout, void* dq, void* dk, void* dv, float* dalpha,
                   void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Dense attention softmax(Q K^T / sqrt(d)) V with the same tile machinery: the
- * comparator the paper measures speed-ups against (Sec. 8.1: "C = 4 N^2 d").
+ * comparator the paper measures speed-ups against (Sec. 9.1: C = 4 N^2 d).
  * Uses B, H, N, d, dtype of params (dtype must be SLA2_BF16); needs no workspace. */
 int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, const void* v,
                        void* out, void* hip_stream);
 
-/* Per-kernel timing for benchmarks (not part of the operator; host-side state, not thread-safe).
+/* Per-kernel timing for benchmarks (not part of the operator).  While no profile is open the other entry
+ * points share no mutable host state and may be called from several threads; between sla2_profile_begin
+ * and sla2_profile_end all calls must come from one thread.
  * The forward pass is a fixed sequence of kernels ("stages").  Between sla2_profile_begin and
  * sla2_profile_end every launch of a stage whose bit is set in stage_mask is bracketed by two
  * hipEventRecord calls on the caller's stream, for at most max_calls calls of sla2_forward /

@@ -138,7 +138,7 @@ def _sigmoid(x: np.ndarray) -> np.ndarray:
 
 
 def soft_topk_rows(R: np.ndarray, k: int, tau: float = 0.1) -> np.ndarray:
-    """SoftTop-k(k%, P_c) of Sec. 6.1 (the differentiable stand-in for Top-k used in the
+    """SoftTop-k(k%, P_c) of Sec. 6 (the differentiable stand-in for Top-k used in the
     first training stage), row-wise:
 
         P_c    = softmax over the row of R             (the router step of Alg. 2)
@@ -457,7 +457,7 @@ def forward_head(Q, K, V, Wq, Wk, alpha, topk_frac: float, b_q: int, b_k: int,
 def backward_head(Q, K, V, sel, alpha, dO, b_q: int, b_k: int, smooth: bool = True, quant: int = QUANT_NONE):
     """Gradients of one head of the un-quantised operator with respect to Q, K,
     V and alpha, for a fixed block mask `sel` (hard Top-k passes no gradient to
-    the router; Sec. 6.1).  dO: [N, d], the gradient of the output of Eq. 13.
+    the router; Sec. 6).  dO: [N, d], the gradient of the output of Eq. 13.
     Sec. 5: the backward pass is always taken in high precision from the
     original Q, K, V, whatever precision the forward ran in; what it takes
     from a low-bit forward (`quant`) is that forward's O^s and L, as inputs.

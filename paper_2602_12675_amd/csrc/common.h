@@ -4,16 +4,9 @@
 #include <stddef.h>
 #include <stdint.h>
 
-#include "../../include/sla2.h"
+#include <atomic>
 
-// Phase markers for timing experiments; compiled out unless a harness defines them.
-#ifndef SLA2_PHASE_MARK
-#define SLA2_PHASE_MARK(i)
-#define SLA2_PHASE_DECL
-#endif
-#ifndef SLA2_PHASE_MARK_KV
-#define SLA2_PHASE_MARK_KV(i)
-#endif
+#include "../../include/sla2.h"
 
 namespace sla2 {
 
@@ -42,6 +35,20 @@ struct Strides {
 };
 __host__ __device__ __forceinline__ size_t head_offset(const Strides& st, int bh, int H) {
   return (size_t)(bh / H) * (size_t)st.b + (size_t)(bh % H) * (size_t)st.h;
+}
+
+// hipFuncSetAttribute(MaxDynamicSharedMemorySize) once per kernel and device.  Safe to call from several
+// threads: the flag is atomic and setting the attribute twice is harmless.
+struct OncePerDevice { std::atomic<unsigned long long> done{0}; };
+inline hipError_t allow_dynamic_lds(OncePerDevice& once, const void* kernel, int bytes) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const unsigned long long bit = 1ull << (dev & 63);
+  if (once.done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) once.done.fetch_or(bit, std::memory_order_release);
+  return e;
 }
 
 // Host-side description of one call, derived from sla2_params.

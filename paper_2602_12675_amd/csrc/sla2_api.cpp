@@ -4,6 +4,7 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <atomic>
 #include <vector>
 
 #include "common.h"
@@ -163,8 +164,10 @@ template <class T>
 static T* at(void* ws, size_t off) { return (T*)((char*)ws + off); }
 
 // ---- optional per-stage event timing (see sla2_profile_begin in sla2.h) ----
+// Calls made while no profile is open only read `active` (atomic): they share no mutable state, so
+// the entry points may be used from several threads.  An open profile is single-threaded by contract.
 struct Profiler {
-  bool active = false;
+  std::atomic<bool> active{false};
   unsigned mask = 0;
   int max_calls = 0, calls = 0, every = 1;          // every-th call is bracketed; max_calls of them
   std::vector<hipEvent_t> pool;                   // created in begin(); two per (call, stage)
@@ -191,6 +194,7 @@ struct StageTimer {
   }
 };
 #define SLA2_STAGE(stage, call) ([&]() { StageTimer t_(stage, st); return (call); }())
+static void count_call() { if (g_prof.active.load(std::memory_order_acquire)) g_prof.calls++; }
 
 // pool -> colmean -> project -> scores + top-k.  Leaves the index lists in the workspace.
 static int run_router(const Shape& s, const sla2_ws_layout& L, const void* q, const void* k, const float* router_w,
@@ -246,7 +250,7 @@ int sla2_router(const sla2_params* params, const void* q, const void* k, const f
   make_layout(s, &L);
   if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  g_prof.calls++;
+  count_call();
   if ((rc = run_router(s, L, q, k, router_w, workspace, st)) != SLA2_OK) return rc;
   if (s.k > 0) {
     size_t bytes = (size_t)s.BH * s.Tm * s.k * sizeof(int32_t);
@@ -266,7 +270,7 @@ int sla2_router_soft(const sla2_params* params, const void* q, const void* k, co
   make_layout(s, &L);
   if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  g_prof.calls++;
+  count_call();
   if (SLA2_STAGE(SLA2_STAGE_BLOCK_SUMS, launch_block_sums(s, q, k, router_w, at<double>(workspace, L.q_sum),
                                                           at<double>(workspace, L.k_sum),
                                                           at<double>(workspace, L.router_m), st)) != hipSuccess)
@@ -293,7 +297,7 @@ int sla2_forward(const sla2_params* params, const void* q, const void* k, const 
   make_layout(s, &L);
   if ((rc = check_workspace(L, workspace, workspace_bytes)) != SLA2_OK) return rc;
   hipStream_t st = (hipStream_t)hip_stream;
-  g_prof.calls++;
+  count_call();
   if ((rc = run_router(s, L, q, k, router_w, workspace, st)) != SLA2_OK) return rc;
   int32_t* idx = at<int32_t>(workspace, L.block_idx);
   if (block_idx_or_null && s.k > 0) {
@@ -388,7 +392,7 @@ int sla2_backward(const sla2_params* params, const void* q, const void* k, const
   a.col_ptr = (int32_t*)(bw + B.col_ptr); a.col_idx = (int32_t*)(bw + B.col_idx);
   a.mask_bits = (uint32_t*)(bw + B.mask_bits); a.col_cnt = (int32_t*)(bw + B.col_cnt);
   hipStream_t st = (hipStream_t)hip_stream;
-  g_prof.calls++;
+  count_call();
   if (SLA2_STAGE(SLA2_STAGE_BWD_LISTS, launch_bwd_lists(s, a, st)) != hipSuccess) return SLA2_EHIP;
   if (SLA2_STAGE(SLA2_STAGE_BWD_Q, launch_bwd_q(s, a, st)) != hipSuccess) return SLA2_EHIP;
   if (SLA2_STAGE(SLA2_STAGE_BWD_REST, launch_bwd_totals(s, a, st)) != hipSuccess) return SLA2_EHIP;
@@ -410,7 +414,7 @@ int sla2_dense_forward(const sla2_params* params, const void* q, const void* k, 
       overlaps(out, out_bytes, v, in_bytes))
     return SLA2_EALIAS;
   hipStream_t st = (hipStream_t)hip_stream;
-  g_prof.calls++;
+  count_call();
   if (SLA2_STAGE(SLA2_STAGE_DENSE, launch_dense_bf16(s, (const uint16_t*)q, (const uint16_t*)k, (const uint16_t*)v,
                                                      (uint16_t*)out, st)) != hipSuccess)
     return SLA2_EHIP;

@@ -784,13 +784,8 @@ hipError_t launch_bwd_lists(const Shape& s, const BwdArgs& a, hipStream_t stream
 
 template <int D>
 static hipError_t launch_bwd_q_f32(const Shape& s, const BwdArgs& a, hipStream_t stream) {
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)bwd_q_kernel<float, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)bwd_smem_q(D));
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static OncePerDevice once;
+  if (hipError_t e = allow_dynamic_lds(once, (const void*)bwd_q_kernel<float, D>, (int)bwd_smem_q(D)); e != hipSuccess) return e;
   const int parts = s.bq / kBwdRows;
   bwd_q_kernel<float, D><<<dim3((unsigned)((size_t)s.BH * s.Tm * parts)), 256, bwd_smem_q(D), stream>>>(
       (const float*)a.q, (const float*)a.k, (const float*)a.v, (const float*)a.dout, (const float*)a.o_s,
@@ -815,13 +810,8 @@ hipError_t launch_bwd_totals(const Shape& s, const BwdArgs& a, hipStream_t strea
 
 template <int D>
 static hipError_t launch_bwd_kv_f32(const Shape& s, const BwdArgs& a, hipStream_t stream) {
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)bwd_kv_kernel<float, D>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)bwd_smem_kv(D));
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static OncePerDevice once;
+  if (hipError_t e = allow_dynamic_lds(once, (const void*)bwd_kv_kernel<float, D>, (int)bwd_smem_kv(D)); e != hipSuccess) return e;
   bwd_kv_kernel<float, D><<<dim3((unsigned)((size_t)s.BH * s.Tn)), 256, bwd_smem_kv(D), stream>>>(
       (const float*)a.q, (const float*)a.k, (const float*)a.v, (const float*)a.dout, a.lse, a.ds, a.k_mean, a.k_stats,
       a.col_ptr, a.col_idx, (const float*)a.dh, a.dz, a.dh_total, a.dz_total, a.alpha, (float*)a.dk, (float*)a.dv,

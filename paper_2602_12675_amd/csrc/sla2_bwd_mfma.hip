@@ -399,12 +399,8 @@ __global__ __launch_bounds__(BQ * 2, 2) void bwd_q_mfma_kernel(
 template <int D, int BQ>
 static hipError_t launch_bwd_q_mfma(const Shape& s, const BwdArgs& a, hipStream_t stream) {
   constexpr int smem = BwdQSmem<D, BQ>::kBytes;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)bwd_q_mfma_kernel<D, BQ>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static OncePerDevice once;
+  if (hipError_t e = allow_dynamic_lds(once, (const void*)bwd_q_mfma_kernel<D, BQ>, smem); e != hipSuccess) return e;
   const int grid = ((s.Tm + kXcds - 1) / kXcds) * kXcds * s.BH;
   bwd_q_mfma_kernel<D, BQ><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(
       (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.dout, (const uint16_t*)a.o_s,
@@ -787,12 +783,8 @@ __global__ __launch_bounds__(256, 2) void bwd_kv_mfma_kernel(
 template <int D, int BQ>
 static hipError_t launch_bwd_kv_mfma(const Shape& s, const BwdArgs& a, hipStream_t stream) {
   constexpr int smem = BwdKvSmem<D>::kBytes;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)bwd_kv_mfma_kernel<D, BQ>, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static OncePerDevice once;
+  if (hipError_t e = allow_dynamic_lds(once, (const void*)bwd_kv_mfma_kernel<D, BQ>, smem); e != hipSuccess) return e;
   const int grid = ((s.Tn + kXcds - 1) / kXcds) * kXcds * s.BH;
   bwd_kv_mfma_kernel<D, BQ><<<dim3((unsigned)grid), 256, smem, stream>>>(
       (const uint16_t*)a.q, (const uint16_t*)a.k, (const uint16_t*)a.v, (const uint16_t*)a.dout, a.lraw, a.ds, a.k_mean,

@@ -131,13 +131,8 @@ hipError_t launch_kv_state_f32(const Shape& s, const float* k, const float* v, c
                                float* partial, hipStream_t stream) {
   dim3 grid((unsigned)(s.BH * s.chunks));
   const size_t smem = (size_t)2 * kBK * (s.d + 1) * sizeof(float);
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e0 = hipFuncSetAttribute((const void*)kv_state_f32_kernel<128>,
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, 2 * kBK * 129 * (int)sizeof(float));
-    if (e0 != hipSuccess) return e0;
-    configured = true;
-  }
+  static OncePerDevice once;
+  if (hipError_t e0 = allow_dynamic_lds(once, (const void*)kv_state_f32_kernel<128>, 2 * kBK * 129 * (int)sizeof(float)); e0 != hipSuccess) return e0;
   if (s.d == 128)
     kv_state_f32_kernel<128><<<grid, 256, smem, stream>>>(k, v, k_mean, k_stats, partial, s.sin, s.H, s.N, s.Tn, s.chunks,
                                                           s.blocks_per_chunk);
@@ -387,13 +382,8 @@ static hipError_t launch_attn_f32_t(const Shape& s, const float* q, const float*
                                     const float* z_total, const int32_t* block_idx, const float* alpha, float* out,
                                     float* lse, const SavedForBackward& sv, hipStream_t stream) {
   size_t smem = ((size_t)3 * 64 * (D + 1) + 64 * 65 + D) * sizeof(float);
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_f32_kernel<D>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       (int)smem);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static OncePerDevice once;
+  if (hipError_t e = allow_dynamic_lds(once, (const void*)attn_f32_kernel<D>, (int)smem); e != hipSuccess) return e;
   dim3 grid((unsigned)((size_t)s.BH * s.Tm * (s.bq / kRowsF32)));
   attn_f32_kernel<D><<<grid, 256, smem, stream>>>(q, k, v, k_mean, k_stats, h_total, z_total, block_idx, alpha, out,
                                                   lse, (float*)sv.o_s, (float*)sv.o_l, sv.lse, s.sin, s.sout, s.H, s.N,

@@ -105,7 +105,6 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
   }
   for (int j = j0; j < j1; j++) {
     const int t0 = j * kTileTokens, valid = min(kTileTokens, N - t0);
-    SLA2_PHASE_MARK_KV(0)
     __syncthreads();                                   // previous tile fully consumed
     TC::store(kr, ktile, tid);
     TC::store(vr, vtile, tid);
@@ -115,7 +114,6 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
       TC::load(vr, vh + (size_t)(j + 1) * kTileTokens * sin.n, sin.n, nvalid, tid);
     }
     __syncthreads();
-    SLA2_PHASE_MARK_KV(1)
     {  // per-token log-partition of softmax_d(k'), 4 threads per token
       const int t = tid / 4, sub = tid % 4;
       float x[D / 4];
@@ -230,7 +228,6 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
       }
     }
     __syncthreads();
-    SLA2_PHASE_MARK_KV(2)
     // K^phi fragments (kept for the attention kernel), h += K^phi^T V on the matrix cores, z_j
     float zsum[HS::kMtw];
 #pragma unroll
@@ -257,7 +254,6 @@ __global__ __launch_bounds__(256) void kv_state_bf16_kernel(const uint16_t* __re
       zacc[a] += z;
       if (g == 0 && nt0 == 0) z_blocks[((size_t)bh * Tn + j) * D + 32 * (mt0 + a) + lane] = z;
     }
-    SLA2_PHASE_MARK_KV(3)
   }
   float* ph = partial + (size_t)blockIdx.x * (D * D + D);
 #pragma unroll
@@ -493,9 +489,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
   constexpr float kPShift = FP8 ? 8.f : 0.f;
   const float c0 = kLog2e * rsqrtf((float)D);        // scores are used as S * log2(e) / sqrt(d)
 
-  SLA2_PHASE_DECL
   for (int s = 0; s < ntiles; s++) {
-    SLA2_PHASE_MARK(0)
     const int buf = s & 1;
     const int j = j_cur;
     const int valid = min(kTileTokens, N - j * kTileTokens);
@@ -628,7 +622,6 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     j_cur = j_nxt;
     j_nxt = j_nn;
     if constexpr (!DENSE) __builtin_amdgcn_s_setprio(0);   // softmax: the other wave's matrix products go first
-    SLA2_PHASE_MARK(1)
     // ---- online softmax of this lane's query row over the 64 keys ----
     const float c1 = FP8 ? c0 * s_q * sk : c0;       // dequantisation folded into the score scale
     if (valid < kTileTokens) {
@@ -685,7 +678,6 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
 #pragma unroll
       for (int e = 0; e < 16; e++) oacc[et][e] *= corr_o;
 
-    SLA2_PHASE_MARK(2)
     if constexpr (!DENSE) __builtin_amdgcn_s_setprio(2);   // matrix products again
     if constexpr (!DENSE) {
       if constexpr (kManual) {
@@ -790,12 +782,9 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         }
       }
     }
-    SLA2_PHASE_MARK(3)
     __builtin_amdgcn_s_waitcnt(kVmcnt0);             // the next tile has landed in LDS ...
     __syncthreads();                                 // ... for everyone, and this tile's buffer is free
-    SLA2_PHASE_MARK(4)
   }
-  SLA2_PHASE_MARK(5)
 
   if constexpr (!DENSE) __builtin_amdgcn_s_setprio(0);
   // ================= epilogue =================
@@ -829,7 +818,6 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) qf[ks] = *reinterpret_cast<const bf16x8*>(src + 16 * ks);
   }
-  SLA2_PHASE_MARK(6)
   uint16_t* ht = reinterpret_cast<uint16_t*>(smem);  // H_i^T as bf16 [e][c], row stride LD
   uint16_t* os = ht + D * LD;                        // output tile [BQ][LD]
   f32x16 lacc[ET];
@@ -853,7 +841,6 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       // zsel holds the same sum on both lane halves (each half added z_j of channel l % 32)
       if (g == 0 && nt0 == 0) zs[32 * (mt0 + a) + lane] = -zsel[a];
     }
-    SLA2_PHASE_MARK(7)
     // Q^phi = softmax_d(Q) of this lane's row, kept as fragments - without its normaliser, which cancels
     // between Q^phi H_i and Q^phi Z_i
     float qx[KS][8];
@@ -870,9 +857,7 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
     for (int ks = 0; ks < KS; ks++)
 #pragma unroll
       for (int e = 0; e < 8; e++) qx[ks][e] = fast_exp2((qx[ks][e] - qm) * kLog2e);
-    SLA2_PHASE_MARK(8)
     __syncthreads();                                 // H_i^T and Z_i visible
-    SLA2_PHASE_MARK(9)
     float den = 0.f;
 #pragma unroll
     for (int ks = 0; ks < KS; ks++) {
@@ -899,7 +884,6 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         lacc[et] = mfma_bf16(a, qf[ks], lacc[et]);
       }
   }
-  SLA2_PHASE_MARK(10)
   // ---- mix (Eq. 13), transpose through LDS, coalesced store ----
   const float al = DENSE ? 1.f : alpha[alpha_per_block ? (size_t)h * Tm + i : (size_t)h];
   const float ws = al * inv_l * (FP8V ? sv_prev : 1.f), wl = (1.f - al) * inv_den;   // FP8V: back from the last tile's V scale
@@ -917,7 +901,6 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       *reinterpret_cast<bf16x4*>(os + qrow * LD + 32 * et + 8 * v4 + 4 * g) = pk;
     }
   __syncthreads();
-  SLA2_PHASE_MARK(11)
   uint16_t* oh = out + head_offset(sout, bh, H) + (size_t)row0 * sout.n;
   for (int idx = tid; idx < BQ * (D / 8); idx += NT) {
     const int r = idx / (D / 8), ch = idx % (D / 8);
@@ -962,7 +945,6 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
       }
     }
   }
-  SLA2_PHASE_MARK(12)
 }
 
 struct AttnArgs {
@@ -984,13 +966,8 @@ struct AttnArgs {
 template <int D, int BQ, int MODE>
 static hipError_t launch_attn_t(const Shape& s, const AttnArgs& a, hipStream_t stream) {
   constexpr int smem = AttnSmem<D, BQ, MODE == kSparseFp8 || MODE == kSparseInt8 || MODE == kSparseFp8V, MODE == kSparseFp8V>::kBytes;
-  static bool configured = false;
-  if (!configured) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_mfma_kernel<D, BQ, MODE>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem);
-    if (e != hipSuccess) return e;
-    configured = true;
-  }
+  static OncePerDevice once;
+  if (hipError_t e = allow_dynamic_lds(once, (const void*)attn_mfma_kernel<D, BQ, MODE>, smem); e != hipSuccess) return e;
   const int Tm = (s.N + BQ - 1) / BQ;
   const int grid = ((Tm + kXcds - 1) / kXcds) * kXcds * s.BH;   // some workgroups of the last run of a head may have no block
   attn_mfma_kernel<D, BQ, MODE><<<dim3((unsigned)grid), BQ * 2, smem, stream>>>(

@@ -112,7 +112,6 @@ __global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restr
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const double* M = router_m + (w_per_head ? (size_t)(bh % H) * D * D : 0);
 
-  SLA2_PHASE_MARK(0)
   double mb[ProjGeom<D>::kSteps];
   project16_fetch<D>(mb, M, wave, lane);               // operands of the projection, in flight during the Qbar load
   for (int e = threadIdx.x; e < kRouterRows * D; e += 1024) {
@@ -122,7 +121,6 @@ __global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restr
     xa[r][c] = q_sum[((size_t)bh * Tm + row) * D + c] / (double)rows;     // mean pooling (Eq. 15)
   }
   __syncthreads();
-  SLA2_PHASE_MARK(1)
   project16<D>(xa, xb, mb, wave, lane);                                   // Qbar (Wq Wk^T / sqrt(d)), in shares
   __syncthreads();
   for (int e = threadIdx.x; e < kRouterRows * D; e += 1024) {
@@ -134,7 +132,6 @@ __global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restr
   }
   __syncthreads();
 
-  SLA2_PHASE_MARK(2)
   uint64_t key[SLOTS];
 #pragma unroll
   for (int s = 0; s < SLOTS; s++) key[s] = 0;
@@ -191,7 +188,6 @@ __global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restr
     }
   }
 
-  SLA2_PHASE_MARK(3)
   const int row = row0 + wave;
   if (row >= Tm || k <= 0) return;
   const int slots = rounds * 4;
@@ -248,7 +244,6 @@ __global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restr
     for (int s = 0; s < SLOTS; s++) gt += wave_count(key[s] > thr);
     need_eq = k - gt;
   }
-  SLA2_PHASE_MARK(4)
   const uint64_t lane_lt = (1ull << lane) - 1ull;
   int written = 0;
 #pragma unroll
@@ -270,7 +265,6 @@ __global__ __launch_bounds__(1024) void router_topk_kernel(const double* __restr
       written += __builtin_popcountll(m);
     }
   }
-  SLA2_PHASE_MARK(5)
 }
 
 hipError_t launch_router_topk(const Shape& s, const double* q_sum, const double* k_sum, const double* router_m,
@@ -281,13 +275,10 @@ hipError_t launch_router_topk(const Shape& s, const double* q_sum, const double*
   const int rounds = (s.Tn + kColsPerRound - 1) / kColsPerRound;     // <= 8 (kMaxKeyBlocks)
 #define SLA2_TOPK(DD, SS)                                                                                        \
   {                                                                                                              \
-    static bool configured = false;                                                                              \
-    if (!configured) {                                                                                           \
-      hipError_t e = hipFuncSetAttribute((const void*)router_topk_kernel<DD, SS>,                                \
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)router_lds_bytes<DD>()); \
-      if (e != hipSuccess) return e;                                                                             \
-      configured = true;                                                                                         \
-    }                                                                                                            \
+    static OncePerDevice once;                                                                                   \
+    if (hipError_t e = allow_dynamic_lds(once, (const void*)router_topk_kernel<DD, SS>, (int)router_lds_bytes<DD>()); \
+        e != hipSuccess)                                                                                         \
+      return e;                                                                                                  \
     router_topk_kernel<DD, SS><<<grid, 1024, router_lds_bytes<DD>(), stream>>>(                                  \
         q_sum, k_sum, router_m, block_idx, k_mean, s.H, s.N, s.bq, s.bk, s.Tm, s.Tn, s.k, s.w_per_head ? 1 : 0,   \
         topk_blocks, s.smooth ? 1 : 0);                                                                          \

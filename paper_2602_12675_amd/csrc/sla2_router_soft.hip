@@ -1,4 +1,4 @@
-// SoftTop-k router (Sec. 6.1 of the paper): the differentiable stand-in for the hard block selection that
+// SoftTop-k router (Sec. 6 of the paper): the differentiable stand-in for the hard block selection that
 // the first training stage uses,
 //      M[i][j] = sigmoid(P_c[i][j] / tau + lambda_i),   P_c = row softmax of the router scores,
 // with lambda_i found by bisection so that row i sums to k.  One workgroup per query block i; fp64

@@ -6,7 +6,7 @@ the benchmark and the CPU oracle's tests.  numpy only - it imports neither the
 HIP binding nor the oracle.
 
 The paper's own tensors are Q, K, V captured from Wan2.1 attention layers
-(Sec. 8.1 of the paper, "Setup"), which are not available.  The stand-ins keep
+(Sec. 9.1 of the paper, "Setup"), which are not available.  The stand-ins keep
 what the method relies on: the shapes of the two models (N = 32,760 tokens on a
 21 x 30 x 52 latent grid with 12 heads, N = 75,600 on 21 x 45 x 80 with 40
 heads, d = 128) and the similarity of neighbouring tokens that makes pooled

@@ -157,3 +157,89 @@ def test_backward_gradient_slices_may_interleave_but_not_share_elements(api):
     assert call(dq, dk, dk + (H - 1) * d * 2) == api.SLA2_EALIAS
     assert call(q, dk, dv) == api.SLA2_EALIAS                  # a gradient on top of an input
     assert call(dq, dk, go) == api.SLA2_EALIAS
+
+
+# ---- the header, compiled as plain C, against the ctypes mirror -------------------------------- #
+_C_PROBE = r"""
+#include <stdio.h>
+#include <stddef.h>
+#include "sla2.h"
+#define FIELD(S, f) printf("field " #S " " #f " %zu %zu\n", offsetof(S, f), sizeof(((S*)0)->f))
+#define ENUM(e) printf("enum " #e " %d\n", (int)(e))
+int main(void) {
+  printf("sizeof sla2_params %zu\n", sizeof(sla2_params));
+  printf("sizeof sla2_ws_layout %zu\n", sizeof(sla2_ws_layout));
+@BODY@
+  return 0;
+}
+"""
+
+
+def _header_struct_fields(name):
+    src = open(os.path.join(ROOT, "include", "sla2.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    body = re.search(r"typedef struct %s \{(.*?)\} %s;" % (name, name), src, flags=re.S).group(1)
+    fields = []
+    for decl in body.split(";"):
+        decl = decl.strip()
+        if not decl:
+            continue
+        names = re.sub(r"^(unsigned|long long|size_t|int|float)\s+", "", decl)
+        fields += [re.sub(r"\[.*\]", "", n).strip() for n in names.split(",")]
+    return fields
+
+
+def _header_enumerators():
+    src = open(os.path.join(ROOT, "include", "sla2.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    names = []
+    for body in re.findall(r"typedef enum \{(.*?)\}", src, flags=re.S):
+        names += re.findall(r"\b(SLA2_[A-Z0-9_]+)\b", body)
+    names += re.findall(r"#define (SLA2_FLAG_[A-Z0-9_]+)", src)
+    return names
+
+
+def test_header_compiles_as_c_and_matches_the_binding(api, tmp_path):
+    """include/sla2.h must be a plain C header (no HIP, no C++), and every field offset, field size,
+    struct size and enumerator value the C compiler sees must be what the ctypes binding assumes."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no C compiler")
+    pf, wf, en = _header_struct_fields("sla2_params"), _header_struct_fields("sla2_ws_layout"), _header_enumerators()
+    lines = ["  FIELD(sla2_params, %s);" % f for f in pf] + ["  FIELD(sla2_ws_layout, %s);" % f for f in wf] + \
+            ["  ENUM(%s);" % e for e in en]
+    src = tmp_path / "probe.c"
+    src.write_text(_C_PROBE.replace("@BODY@", "\n".join(lines)))
+    exe = tmp_path / "probe"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(ROOT, "include"),
+                    str(src), "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    seen_fields, seen_enums, sizes = {}, {}, {}
+    for ln in out:
+        t = ln.split()
+        if not t:
+            continue
+        if t[0] == "field":
+            seen_fields[(t[1], t[2])] = (int(t[3]), int(t[4]))
+        elif t[0] == "enum":
+            seen_enums[t[1]] = int(t[2])
+        else:
+            sizes[t[1]] = int(t[2])
+    # structs: same field names in the same order, same offsets and sizes
+    for cname, cls, names in (("sla2_params", api.Params, pf), ("sla2_ws_layout", api.WsLayout, wf)):
+        assert [n for n, _ in cls._fields_] == names
+        assert ctypes.sizeof(cls) == sizes[cname]
+        for n in names:
+            fld = getattr(cls, n)
+            assert (fld.offset, fld.size) == seen_fields[(cname, n)], (cname, n)
+    # enumerators and flags: the binding's constants of the same name, and the stage order
+    for name, val in seen_enums.items():
+        if name.startswith("SLA2_STAGE_"):
+            continue
+        assert getattr(api, name) == val, name
+    stages = {n[len("SLA2_STAGE_"):].lower(): v for n, v in seen_enums.items() if n.startswith("SLA2_STAGE_")}
+    assert stages.pop("count") == len(api.STAGES)
+    assert {n: i for i, n in enumerate(api.STAGES)} == stages
+    assert api.QUANT_MODES == {"none": seen_enums["SLA2_QUANT_NONE"], "fp8": seen_enums["SLA2_QUANT_FP8"],
+                               "int8": seen_enums["SLA2_QUANT_INT8"], "fp8v": seen_enums["SLA2_QUANT_FP8_V"]}

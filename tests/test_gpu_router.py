@@ -110,7 +110,7 @@ def test_router_degenerate_k(frac):
 
 def test_router_identity_weights_is_topk_of_pooled_scores():
     """router_w = (I, I): the learnable router reduces to Top-k of pool(Q) pool(K)^T, the fixed
-    router the paper ablates against (Sec. 8.3, "Topk-router")."""
+    router the paper ablates against (Sec. 9.4, "Topk-router")."""
     import torch
     from paper_2602_12675_amd import api
     w = W.TINY.replace(name="identity-router", grid=(5, 16, 33), d=128, block_q=128, dtype="bf16", H=2,

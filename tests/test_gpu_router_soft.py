@@ -1,4 +1,4 @@
-"""GPU parity of the SoftTop-k router (Sec. 6.1) against the oracle's bisection, through the C ABI.
+"""GPU parity of the SoftTop-k router (Sec. 6) against the oracle's bisection, through the C ABI.
 Both sides solve the same monotone equation in fp64 until the bracket stops shrinking; the masks
 are float32 on the GPU side, so agreement is required to 1e-6 absolute and the row sums to k
 within the float32 rounding of T_n entries."""

@@ -252,7 +252,7 @@ def test_mask_invariances():
     k = base["sel"].shape[1]
     assert np.array_equal(O.topk_rows(Pc, k), base["sel"])
     assert np.array_equal(O.topk_rows(R * math.sqrt(d), k), base["sel"])
-    # proj = I recovers the pooled-QK router of SLA (Sec. 7, insight 1.c)
+    # proj = I recovers the pooled-QK router of SLA (Sec. 8, insight 1.c)
     eye = O.forward_head(Q, K, V, np.eye(d), np.eye(d), 0.5, 0.25, bq, bk, smooth=False)
     Qbar = Q.reshape(-1, bq, d).mean(axis=1)
     Kbar = K.reshape(-1, bk, d).mean(axis=1)
@@ -537,7 +537,7 @@ def test_backward_after_a_low_bit_forward(quant):
         assert 0.0 < move <= 20.0 * fwd_err, (name, move, fwd_err)
 
 
-# ---- SoftTop-k (Sec. 6.1) ---------------------------------------------------- #
+# ---- SoftTop-k (Sec. 6) ---------------------------------------------------- #
 def test_soft_topk_row_sums_range_and_order():
     rng = np.random.default_rng(30)
     R = rng.normal(size=(7, 40)) * 3.0
@@ -698,9 +698,9 @@ def test_table1_flops_confirm_workload_shapes():
             if line.strip() and not line.startswith("#"):
                 m, s, v = line.split()
                 rows[(m, int(s))] = float(v)
-    # C = 4 N^2 d per head (Sec. 8.1, "Metrics"); the table's full-attention rows
+    # C = 4 N^2 d per head (Sec. 9.1, "Metrics"); the table's full-attention rows
     # equal C*H times a constant (8 and 2.5: not explained in the paper)
     assert round(4 * 32760 ** 2 * 128 * 12 * 8 / 1e12, 2) == rows[("wan1.3b", 0)]
     assert round(4 * 75600 ** 2 * 128 * 40 * 2.5 / 1e12, 1) == rows[("wan14b", 0)]
-    # "29x" of Sec. 8.2 is the ratio of the table's FLOPs at 97 %
+    # "29x" of Sec. 9.2 is the ratio of the table's FLOPs at 97 %
     assert round(rows[("wan1.3b", 0)] / rows[("wan1.3b", 97)]) == 29
