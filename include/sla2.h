@@ -151,6 +151,21 @@ int sla2_num_selected(const sla2_params* params);
 int sla2_router(const sla2_params* params, const void* q, const void* k, const float* router_w,
                 int32_t* block_idx, void* workspace, size_t workspace_bytes, void* hip_stream);
 
+/* sla2_router for callers that cannot allocate device memory and hold no workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same result as sla2_router;
+ * the intermediate arrays (fp64 block sums of Q and K, colmean(K), the folded router matrix - the part of
+ * the workspace that precedes sla2_ws_layout.block_idx) live in an array of SLA2_STATIC_SCRATCH_BYTES that
+ * is part of the library's device image: every GPU the library runs on holds it until the process ends.
+ * The call allocates and frees nothing and never synchronises.  Parameters whose router arrays need more
+ * than SLA2_STATIC_SCRATCH_BYTES (sla2_workspace_layout(params).block_idx bytes; 9.5 MB for B = 1, H = 12,
+ * N = 32760, d = 128) are refused with SLA2_EWORKSPACE before anything is launched.  All calls on one GPU
+ * share that GPU's array, which keeps the last call's contents (nothing in it has to start at zero):
+ * calls that overlap in time on one GPU race - keep them on one stream or order them with events.
+ * q, k, router_w, block_idx, hip_stream and the other errors as for sla2_router. */
+#define SLA2_STATIC_SCRATCH_BYTES (32u << 20)
+int sla2_router_static(const sla2_params* params, const void* q, const void* k, const float* router_w,
+                       int32_t* block_idx, void* hip_stream);
+
 /* SoftTop-k form of the router (Sec. 6: the differentiable operator that replaces Top-k in the
  * first training stage):  mask[b,h,i,j] = sigmoid(P_c[i,j] / tau + lambda_i), P_c the row softmax
  * of the router scores of Eq. 16 (with the 1/sqrt(d) of Alg. 2), lambda_i found by bisection so that

@@ -23,7 +23,8 @@ SLA2_FLAG_NO_SMOOTH_K = 1
 SLA2_FLAG_SAVE_FOR_BACKWARD = 2
 SLA2_OK, SLA2_EINVAL, SLA2_EUNSUPPORTED, SLA2_EWORKSPACE, SLA2_EALIAS, SLA2_EHIP = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ("sla2_workspace_bytes", "sla2_workspace_layout", "sla2_num_selected", "sla2_router",
+SLA2_STATIC_SCRATCH_BYTES = 32 << 20
+EXPORTS = ("sla2_workspace_bytes", "sla2_workspace_layout", "sla2_num_selected", "sla2_router", "sla2_router_static",
            "sla2_router_soft", "sla2_forward", "sla2_backward", "sla2_dense_forward", "sla2_profile_begin", "sla2_profile_begin_sampled",
            "sla2_profile_end",
            "sla2_strerror", "sla2_version")
@@ -62,6 +63,8 @@ _lib.sla2_num_selected.restype = ctypes.c_int
 _lib.sla2_num_selected.argtypes = [_pp]
 _lib.sla2_router.restype = ctypes.c_int
 _lib.sla2_router.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp, ctypes.c_size_t, _vp]
+_lib.sla2_router_static.restype = ctypes.c_int
+_lib.sla2_router_static.argtypes = [_pp, _vp, _vp, _vp, _vp, _vp]
 _lib.sla2_router_soft.restype = ctypes.c_int
 _lib.sla2_router_soft.argtypes = [_pp, _vp, _vp, _vp, ctypes.c_float, _vp, _vp, ctypes.c_size_t, _vp]
 _lib.sla2_forward.restype = ctypes.c_int
@@ -146,6 +149,14 @@ def sla2_router(params, q, k, router_w, block_idx, workspace, stream=None, check
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     rc = _lib.sla2_router(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(router_w), _ptr(block_idx),
                           _ptr(workspace), ws_bytes, _stream(stream))
+    if check and rc != SLA2_OK:
+        raise Sla2Error(rc)
+    return rc
+
+
+def sla2_router_static(params, q, k, router_w, block_idx, stream=None, check=True) -> int:
+    rc = _lib.sla2_router_static(ctypes.byref(params), _ptr(q), _ptr(k), _ptr(router_w), _ptr(block_idx),
+                                 _stream(stream))
     if check and rc != SLA2_OK:
         raise Sla2Error(rc)
     return rc

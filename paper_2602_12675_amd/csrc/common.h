@@ -63,6 +63,10 @@ struct Shape {
   int blocks_per_chunk, chunks;
 };
 
+// sla2_api.cpp: parameter validation (SLA2_OK or a negative sla2_status) and the workspace carve-up
+int make_shape(const sla2_params* p, Shape* s);
+void make_layout(const Shape& s, sla2_ws_layout* L);
+
 __device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) {
   return __builtin_bit_cast(float, (uint32_t)b << 16);
 }

@@ -14,7 +14,7 @@ namespace sla2 {
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // Validate everything that does not need pointers and derive the block counts.
-static int make_shape(const sla2_params* p, Shape* s) {
+int make_shape(const sla2_params* p, Shape* s) {
   if (!p) return SLA2_EINVAL;
   if (p->B < 1 || p->H < 1 || p->N < 1) return SLA2_EINVAL;
   if (!(p->topk_frac >= 0.0f && p->topk_frac <= 1.0f)) return SLA2_EINVAL;   // also rejects NaN
@@ -102,7 +102,7 @@ static BwdLayout make_bwd_layout(const Shape& s) {
 }
 static size_t bwd_scratch_bytes(const Shape& s) { return make_bwd_layout(s).total; }
 
-static void make_layout(const Shape& s, sla2_ws_layout* L) {
+void make_layout(const Shape& s, sla2_ws_layout* L) {
   size_t off = 0, BH = (size_t)s.BH, d = (size_t)s.d;
   auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
   L->q_sum = take(BH * s.Tm * d * sizeof(double));

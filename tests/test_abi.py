@@ -195,7 +195,7 @@ def _header_enumerators():
     names = []
     for body in re.findall(r"typedef enum \{(.*?)\}", src, flags=re.S):
         names += re.findall(r"\b(SLA2_[A-Z0-9_]+)\b", body)
-    names += re.findall(r"#define (SLA2_FLAG_[A-Z0-9_]+)", src)
+    names += re.findall(r"#define (SLA2_(?:FLAG|STATIC)_[A-Z0-9_]+)", src)
     return names
 
 
