@@ -47,17 +47,28 @@ def parse():
     ap.add_argument("--cpu-heads", type=int, default=12, help="heads of the workload the oracle is timed on")
     ap.add_argument("--event-stride", type=int, default=1,
                     help="bracket the dominant kernel with HIP events on every n-th timed step")
+    ap.add_argument("--block-q", type=int, default=None, choices=[64, 128], help="override the workload's query block size")
+    ap.add_argument("--router-identity", action="store_true",
+                    help="router weights Wq = Wk = I: the pooled-QK router of the Topk-router ablation (Sec. 9.4)")
+    ap.add_argument("--sweep", action="store_true",
+                    help="the sparsity sweep: kept fractions 0.15 ... 0.01 in bf16 and FP8 at N = 75,600 and 75,601 plus the "
+                         "dense kernel on the same inputs; one JSON line per point, written to --sweep-out as well")
+    ap.add_argument("--sweep-out", default="sweep.jsonl")
+    ap.add_argument("--sweep-lengths", default="0,1", help="extra tokens after the 75,600-token grid, comma separated")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 256 MiB device copy (for scaling FETCH_SIZE / WRITE_SIZE under rocprofv3 --pmc)")
     return ap.parse_args()
 
 
+TRAFFIC_FILE = os.path.join("profiles", "attn_mfma_traffic.txt")
+
+
 def measured_traffic(workload, quant):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
-    (profiles/attn_mfma_traffic.txt: lines `workload quant bytes`), or None."""
-    path = os.path.join(ROOT, "profiles", "attn_mfma_traffic.txt")
+    (profiles/attn_mfma_traffic.txt: lines `workload quant bytes`), or None.  It is a stored counter reading
+    of an earlier profiled run of this same command, not a measurement of the present run."""
     try:
-        with open(path) as f:
+        with open(os.path.join(ROOT, TRAFFIC_FILE)) as f:
             for line in f:
                 parts = line.split()
                 if len(parts) >= 3 and not line.startswith("#") and parts[0] == workload and parts[1] == quant:
@@ -65,6 +76,18 @@ def measured_traffic(workload, quant):
     except OSError:
         pass
     return None
+
+
+def traffic_source():
+    """Where `roofline.traffic` comes from: the file and the commit that last changed it."""
+    import subprocess
+    try:
+        rev = subprocess.run(["git", "log", "-1", "--format=%h", "--", TRAFFIC_FILE], cwd=ROOT, capture_output=True,
+                             text=True, timeout=10).stdout.strip()
+    except Exception:
+        rev = ""
+    return "%s%s (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier run of this command; not measured in this run)" % (
+        TRAFFIC_FILE, " @ " + rev if rev else "")
 
 
 def cpu_baseline(inp, heads):
@@ -136,6 +159,72 @@ def backward_timing(api, W, torch, w, inp, dt, qm, tensors, rw, al, stream, ksel
     return res
 
 
+def sweep(args, api, W, torch):
+    """Config 5: B = 2, H = 40, d = 128, N = 75,600 (+ extra tokens), kept fractions 0.15 ... 0.01, bf16 and FP8
+    sparse branch, and the dense bf16 kernel on the same inputs.  One JSON line per point."""
+    stream = torch.cuda.current_stream()
+    lines = []
+    for extra in [int(x) for x in args.sweep_lengths.split(",") if x != ""]:
+        base = W.SWEEP_BASE.replace(extra_tokens=extra)
+        inp = W.generate(base)
+        dt = api.SLA2_BF16
+        sets = []
+        for _ in range(max(1, min(args.input_sets, 2))):
+            q, k, v = (api.to_device(a, dt) for a in (inp.q, inp.k, inp.v))
+            sets.append((q, k, v, torch.empty_like(q)))
+        rw = torch.from_numpy(inp.router_w).cuda()
+        al = torch.from_numpy(inp.alpha).cuda()
+        dense_flops = 4.0 * base.N * base.N * base.d * base.H * base.B
+        pd = api.make_params(base.B, base.H, base.N, base.d, base.block_q, base.block_kv, 1.0, dtype=dt)
+        q, k, v, out = sets[0]
+        api.sla2_dense_forward(pd, q, k, v, out, stream=stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(2):
+            api.sla2_dense_forward(pd, q, k, v, out, stream=stream)
+        torch.cuda.synchronize()
+        dense_ms = (time.perf_counter() - t0) / 2 * 1e3
+        dense = {"ms": round(dense_ms, 2), "TFLOP/s": round(dense_flops / (dense_ms * 1e-3) / 1e12, 1),
+                 "frac_of_bf16_mfma_peak": round(dense_flops / (dense_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS["bf16"], 4)}
+        for quant in ("none", "fp8"):
+            for topk in W.SWEEP_TOPK:
+                w = base.replace(quant=quant, topk_frac=topk)
+                p = api.make_params(w.B, w.H, w.N, w.d, w.block_q, w.block_kv, w.topk_frac, dtype=dt,
+                                    quant_mode=api.QUANT_MODES[quant])
+                ws = api.alloc_workspace(p)
+
+                def step(i):
+                    q, k, v, out = sets[i % len(sets)]
+                    api.sla2_forward(p, q, k, v, rw, al, out, workspace=ws, stream=stream)
+                for i in range(args.warmup):
+                    step(i)
+                api.sla2_profile_begin([n for n in api.STAGES if n != "dense"], args.steps)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for i in range(args.steps):
+                    step(i)
+                torch.cuda.synchronize()
+                ms = (time.perf_counter() - t0) / args.steps * 1e3
+                stages = {name: round(t / n, 4) for name, (t, n) in api.sla2_profile_end().items()}
+                ksel = api.sla2_num_selected(p)
+                line = {"metric": "SLA2 forward, dense-equivalent throughput 4*N^2*d*H*B / t",
+                        "value": round(dense_flops / (ms * 1e-3) / 1e12, 2), "unit": "TFLOP/s", "n_gpus": 1,
+                        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+                        "dtype": "bf16" if quant == "none" else "fp8", "data": "synthetic",
+                        "config": {"workload": "wan14b-sweep", "B": w.B, "H": w.H, "N": w.N, "d": w.d, "block_q": w.block_q,
+                                   "block_kv": w.block_kv, "topk_frac": topk, "k": ksel, "T_n": w.T_n,
+                                   "sparsity": round(1.0 - ksel / w.T_n, 4), "quant": quant, "input_sets": len(sets)},
+                        "stage_ms": stages, "dense_bf16": dense, "speedup_vs_dense_bf16": round(dense_ms / ms, 2)}
+                lines.append(line)
+                print(json.dumps(line), flush=True)
+                del ws
+        del sets, inp
+        torch.cuda.empty_cache()
+    with open(args.sweep_out, "w") as f:
+        for line in lines:
+            f.write(json.dumps(line) + "\n")
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -155,7 +244,13 @@ def main():
         w = w.replace(quant=args.quant)
     if args.topk is not None:
         w = w.replace(topk_frac=args.topk)
+    if args.block_q is not None:
+        w = w.replace(block_q=args.block_q)
+    if args.sweep:
+        return sweep(args, api, W, torch)
     inp = W.generate(w)
+    if args.router_identity:
+        inp.router_w[:] = np.eye(w.d, dtype=np.float32)
     dt = api.SLA2_BF16 if w.dtype == "bf16" else api.SLA2_F32
     qm = api.QUANT_MODES[w.quant]
     strides = {}
@@ -232,6 +327,18 @@ def main():
     torch.cuda.synchronize()
     stages = {name: ms / n for name, (ms, n) in api.sla2_profile_end().items()}
 
+    # the timed loop once more, now that the clocks have had warmup + 2 x steps calls to settle: reported
+    # next to the headline figure, labelled, never as `value`
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    settled_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    settled = {"ms_per_step": round(settled_ms, 4), "TFLOP/s": round(dense_flops / (settled_ms * 1e-3) / 1e12, 2),
+               "steps": args.steps, "calls_before": args.warmup + 2 * args.steps + (5 + max(10, args.steps // 2) if len(sets) > 1 else 0),
+               "note": "the same rotating-input loop as `value`, timed again at the end of the run"}
+
     BH, esz = w.B * w.H, (2 if w.dtype == "bf16" else 4)
     tile_iters = BH * w.T_m * ksel
     qk_flops = tile_iters * 2.0 * w.block_q * w.block_kv * w.d           # Q K^T: 8-bit products in the low-bit modes
@@ -253,7 +360,7 @@ def main():
         note = "peak = dense bf16 MFMA"
     roofline = {"kernel": "attn_mfma (sparse + linear branch + mix)", "bound": "mfma", "achieved": round(achieved, 2),
                 "peak": round(peak, 1), "unit": "TFLOP/s", "frac": round(achieved / peak, 4),
-                "traffic": measured_traffic(w.name, w.quant), "ms": round(attn_ms, 4),
+                "traffic": measured_traffic(w.name, w.quant), "traffic_source": traffic_source(), "ms": round(attn_ms, 4),
                 "launches_timed": prof["attn"][1],
                 "algorithmic_flops": attn_flops, "note": note}
     # the same kernel against the other roof it can hit: bytes it has to gather per (query block, key block)
@@ -289,8 +396,10 @@ def main():
         "config": {"workload": w.name, "B": w.B, "H": w.H, "N": w.N, "d": w.d, "block_q": w.block_q,
                    "block_kv": w.block_kv, "topk_frac": w.topk_frac, "k": ksel, "T_n": w.T_n,
                    "sparsity": round(1.0 - ksel / w.T_n, 4), "quant": w.quant, "input_sets": len(sets),
+                   "router": "identity weights (pooled-QK router)" if args.router_identity else "random projections",
                    "layout": "packed [B,N,3,H,d] -> [B,N,H,d]" if args.packed_qkv else "[B,H,N,d]"},
         "roofline": roofline,
+        "settled": settled,
         "warm_single_input_set": warm,
         "stage_ms": {k_: round(v_, 4) for k_, v_ in stages.items()},
         "hbm_kernels": hbm,

@@ -65,7 +65,14 @@ WAN_14B_97_FP8 = Workload("wan14b-97-fp8", 1, 40, (21, 45, 80), 128, 128, 64, 0.
 SWEEP_BASE = Workload("wan14b-sweep", 2, 40, (21, 45, 80), 128, 128, 64, 0.03, "bf16", "none", 1, True)
 SWEEP_TOPK = (0.15, 0.10, 0.05, 0.03, 0.01)
 
-CONFIGS = {w.name: w for w in (TINY, WAN_1P3B_95, WAN_1P3B_97_FP8, WAN_14B_97_FP8, SWEEP_BASE)}
+# Beyond the five: image-generation-sized inputs (Sec. 1 names image models next to video ones): a 64 x 64
+# latent grid, 4,096 tokens, 90 % sparsity, FP8 sparse branch; d = 128 with 128-row query blocks and d = 64
+# with 64-row query blocks.
+IMAGE_DIT_4K = Workload("image-dit-4k", 2, 24, (1, 64, 64), 128, 128, 64, 0.10, "bf16", "fp8", 2, True)
+IMAGE_DIT_4K_D64 = Workload("image-dit-4k-d64", 2, 16, (1, 64, 64), 64, 64, 64, 0.10, "bf16", "fp8", 2, True)
+
+CONFIGS = {w.name: w for w in (TINY, WAN_1P3B_95, WAN_1P3B_97_FP8, WAN_14B_97_FP8, SWEEP_BASE,
+                               IMAGE_DIT_4K, IMAGE_DIT_4K_D64)}
 
 
 @dataclasses.dataclass

@@ -54,6 +54,30 @@ def rel_l2(a, b):
     return float(np.linalg.norm(a.astype(np.float64) - b) / max(np.linalg.norm(b), 1e-30))
 
 
+# Element-wise parity next to the per-head norm: every compared row within ROW_REL of its reference row
+# (||got - ref|| / ||ref row||) and every element within MAX_ABS_FRAC of the largest reference entry of the
+# compared slice.  The bounds are about three times the largest deviation seen over all forward tests:
+# bf16 / fp32 tensors 7.6e-3 and 4.4e-3, INT8 1.4e-2 and 8.6e-3, FP8 2.5e-2 and 1.0e-2, FP8 with quantised V
+# 2.5e-2 and 1.8e-2.  The low-bit rows are wider because the kernel takes exp2 in float32 with the hardware
+# approximation: a probability next to a rounding boundary of the e4m3 grid lands on the neighbouring code
+# (a 6 % step for that one weight), which no head-wide norm sees.
+ROW_REL = {"none": 2.5e-2, "int8": 4.5e-2, "fp8": 7.5e-2, "fp8v": 7.5e-2}
+MAX_ABS_FRAC = {"none": 1.5e-2, "int8": 2.5e-2, "fp8": 3e-2, "fp8v": 5e-2}
+
+
+def rows_ok(got, ref, quant="none"):
+    """got, ref: [..., rows, d].  Asserts the per-row and per-element bounds above on every row."""
+    d = got.astype(np.float64) - ref
+    rn = np.linalg.norm(ref, axis=-1)
+    dn = np.linalg.norm(d, axis=-1)
+    bad = np.nonzero(dn > ROW_REL[quant] * rn + 1e-6)
+    assert bad[0].size == 0, "rows off by more than %g: first %s, %g of %g" % (
+        ROW_REL[quant], [int(x[0]) for x in bad], float(dn[bad][0]), float(rn[bad][0]))
+    top = float(np.abs(ref).max())
+    worst = float(np.abs(d).max())
+    assert worst <= MAX_ABS_FRAC[quant] * top + 1e-6, "element off by %g (largest reference entry %g)" % (worst, top)
+
+
 def run_forward(api, torch, inp, flags=0, alpha=None, alpha_per_block=0, want_lse=True):
     w = inp.workload
     dt = api.SLA2_BF16 if w.dtype == "bf16" else api.SLA2_F32

@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import sla2_oracle as O
-from helpers import check_mask, oracle_heads, rel_l2, run_dense, run_forward
+from helpers import check_mask, oracle_heads, rel_l2, rows_ok, run_dense, run_forward
 from paper_2602_12675_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -49,6 +49,7 @@ def test_forward_bf16_matches_oracle(w):
         assert rel_l2(h_total[bh], hj.sum(axis=0)) < 5e-3          # K^phi rounded to bf16 before the product
         assert rel_l2(z_total[bh], zj.sum(axis=0)) < 1e-4
         assert rel_l2(r["out"][b, h], o["O"]) <= BF16_REL_L2, (b, h, rel_l2(r["out"][b, h], o["O"]))
+        rows_ok(r["out"][b, h], o["O"])
         fin = np.isfinite(o["L"])
         np.testing.assert_allclose(r["lse"][b, h][fin], o["L"][fin], rtol=0, atol=2e-2)
     assert not np.isnan(r["out"]).any()
@@ -67,6 +68,7 @@ def test_forward_bf16_branches_separately():
         ref = oracle_heads(inp, alpha=al)
         for (b, h), o in ref.items():
             assert rel_l2(r["out"][b, h], o[key]) <= BF16_REL_L2, (key, h)
+            rows_ok(r["out"][b, h], o[key])
 
 
 @pytest.mark.parametrize("frac,alpha", [(0.0, 0.0), (1.0, 1.0), (0.0, 0.6), (1.0, 0.4)])
@@ -80,6 +82,7 @@ def test_forward_bf16_degenerate_branches(frac, alpha):
     ref = oracle_heads(inp, alpha=al)
     for (b, h), o in ref.items():
         assert rel_l2(r["out"][b, h], o["O"]) <= BF16_REL_L2
+        rows_ok(r["out"][b, h], o["O"])
     assert not np.isnan(r["out"]).any()
 
 
@@ -94,6 +97,7 @@ def test_forward_bf16_alpha_per_block_no_smoothing():
     for (b, h), o in ref.items():
         assert check_mask(r["idx"][b, h], o["R"], o["sel"]) == 0
         assert rel_l2(r["out"][b, h], o["O"]) <= BF16_REL_L2
+        rows_ok(r["out"][b, h], o["O"])
 
 
 def test_forward_bf16_large_key_offset():
@@ -110,6 +114,7 @@ def test_forward_bf16_large_key_offset():
     for (b, h), o in ref.items():
         assert check_mask(r["idx"][b, h], o["R"], o["sel"]) == 0
         assert rel_l2(r["out"][b, h], o["O"]) <= BF16_REL_L2
+        rows_ok(r["out"][b, h], o["O"])
 
 
 def test_forward_bf16_deterministic():
@@ -133,3 +138,4 @@ def test_dense_baseline_matches_dense_attention(w):
     ref = oracle_heads(inp, alpha=np.ones((w.H,), np.float32), topk_frac=1.0)
     for (b, h), o in ref.items():
         assert rel_l2(out[b, h], o["O"]) <= BF16_REL_L2
+        rows_ok(out[b, h], o["O"])

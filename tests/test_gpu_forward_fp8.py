@@ -6,7 +6,7 @@ import numpy as np
 import pytest
 
 import sla2_oracle as O
-from helpers import check_mask, oracle_heads, rel_l2, run_forward
+from helpers import check_mask, oracle_heads, rel_l2, rows_ok, run_forward
 from paper_2602_12675_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -58,6 +58,7 @@ def test_forward_fp8_matches_oracle(w):
         assert mism == 0
         assert not codes[bh, w.N:].any()                  # rows past the end are zero
         e = rel_l2(r["out"][b, h], o["O"])
+        rows_ok(r["out"][b, h], o["O"], "fp8")
         worst = max(worst, e)
         assert e <= FP8_REL_L2, (b, h, e)
         fin = np.isfinite(o["L"])
@@ -81,6 +82,7 @@ def test_forward_fp8_sparse_branch_alone_and_vs_unquantised():
     for key in lo:
         b, h = key
         e_kernel = rel_l2(r["out"][b, h], lo[key]["O"])
+        rows_ok(r["out"][b, h], lo[key]["O"], "fp8")
         e_quant = rel_l2(lo[key]["O"], ex[key]["O"])
         assert e_kernel <= FP8_REL_L2
         assert e_kernel < 0.5 * e_quant, (e_kernel, e_quant)
@@ -97,6 +99,7 @@ def test_forward_fp8_degenerate(frac, alpha):
     ref = oracle_heads(inp, alpha=al)
     for (b, h), o in ref.items():
         assert rel_l2(r["out"][b, h], o["O"]) <= FP8_REL_L2
+        rows_ok(r["out"][b, h], o["O"], "fp8")
     assert not np.isnan(r["out"]).any()
 
 
@@ -111,4 +114,5 @@ def test_forward_fp8_zero_query_block():
     ref = oracle_heads(inp)
     for (b, h), o in ref.items():
         assert rel_l2(r["out"][b, h], o["O"]) <= FP8_REL_L2
+        rows_ok(r["out"][b, h], o["O"], "fp8")
     assert not np.isnan(r["out"]).any()

@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import sla2_oracle as O
-from helpers import check_mask, oracle_heads, rel_l2, run_forward
+from helpers import check_mask, oracle_heads, rel_l2, rows_ok, run_forward
 from paper_2602_12675_amd import workloads as W
 from test_gpu_forward_fp8 import e4m3_decode
 
@@ -64,6 +64,7 @@ def test_forward_fp8v_matches_oracle(w):
             assert not by_token[c1 - c0:].any()                         # tokens past the end are zero
         assert mism == 0
         e = rel_l2(r["out"][b, h], o["O"])
+        rows_ok(r["out"][b, h], o["O"], "fp8v")
         worst = max(worst, e)
         assert e <= LOWBIT_REL_L2, (b, h, e)
         fin = np.isfinite(o["L"])
@@ -87,6 +88,7 @@ def test_forward_fp8v_sparse_branch_alone_sees_the_rounded_v():
     for key in lo:
         b, h = key
         e_kernel = rel_l2(r["out"][b, h], lo[key]["O"])
+        rows_ok(r["out"][b, h], lo[key]["O"], "fp8v")
         e_v = rel_l2(lo[key]["O"], f8[key]["O"])
         assert e_kernel <= LOWBIT_REL_L2
         assert e_kernel < 0.5 * e_v, (e_kernel, e_v)
@@ -103,6 +105,7 @@ def test_forward_fp8v_degenerate(frac, alpha):
     ref = oracle_heads(inp, alpha=al)
     for (b, h), o in ref.items():
         assert rel_l2(r["out"][b, h], o["O"]) <= LOWBIT_REL_L2
+        rows_ok(r["out"][b, h], o["O"], "fp8v")
     assert not np.isnan(r["out"]).any()
 
 
@@ -121,4 +124,5 @@ def test_forward_fp8v_blocks_of_very_different_v_scale():
     ref = oracle_heads(inp)
     for (b, h), o in ref.items():
         assert rel_l2(r["out"][b, h], o["O"]) <= LOWBIT_REL_L2
+        rows_ok(r["out"][b, h], o["O"], "fp8v")
     assert not np.isnan(r["out"]).any()

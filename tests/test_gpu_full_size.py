@@ -11,7 +11,7 @@ and, with constant value rows, output rows equal to that constant."""
 import numpy as np
 import pytest
 
-from helpers import check_mask, oracle_heads, rel_l2, run_forward, run_dense
+from helpers import check_mask, oracle_heads, rel_l2, rows_ok, run_forward, run_dense
 from paper_2602_12675_amd import workloads as W
 
 pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
@@ -19,10 +19,11 @@ pytestmark = [pytest.mark.gpu, pytest.mark.timeout(600)]
 TOL = {"none": 2e-2, "fp8": 5e-2, "int8": 5e-2, "fp8v": 5e-2}
 
 
-def sampled_check(w, heads, n_blocks=6, seed=0):
+def sampled_check(w, heads, n_blocks=6, seed=0, inp=None):
     import torch
     from paper_2602_12675_amd import api
-    inp = W.generate(w)
+    if inp is None:
+        inp = W.generate(w)
     r = run_forward(api, torch, inp)
     assert np.isfinite(r["out"]).all()
     rng = np.random.default_rng(seed)
@@ -34,6 +35,7 @@ def sampled_check(w, heads, n_blocks=6, seed=0):
         for i in qb:
             r0, r1 = i * w.block_q, min(w.N, (i + 1) * w.block_q)
             e = rel_l2(r["out"][b, h, r0:r1], o["O"][r0:r1])
+            rows_ok(r["out"][b, h, r0:r1], o["O"][r0:r1], w.quant)
             worst = max(worst, e)
             assert e <= TOL[w.quant], (w.name, b, h, i, e)
             fin = np.isfinite(o["L"][r0:r1])
@@ -62,14 +64,52 @@ def test_wan_14b_fp8_97():
     sampled_check(W.WAN_14B_97_FP8, heads=[(0, 0), (0, 39)], n_blocks=5)
 
 
-@pytest.mark.parametrize("quant,topk", [("none", 0.15), ("fp8", 0.01), ("fp8", 0.10), ("int8", 0.05)])
-def test_sweep_shape_ragged_75601(quant, topk):
-    """B = 2, N = 75,601 (a 17-token last key block and an 81-token last query
-    block); heads reduced to 4 to bound the test's memory and time, the kernels
-    see the same per-head shape and grid mapping as with 40."""
-    w = W.SWEEP_BASE.replace(name="sweep-75601-%s-%g" % (quant, topk), H=4, extra_tokens=1, quant=quant,
-                             topk_frac=topk)
-    sampled_check(w, heads=[(0, 0), (1, 3)], n_blocks=4)
+_SWEEP_INPUTS = {}
+
+
+def sweep_inputs(extra_tokens):
+    """The inputs of the sparsity sweep (B = 2, H = 40, d = 128, N = 75,600 + extra_tokens), drawn once per
+    sequence length and shared by its ten points; only one length is kept at a time (9 GB of host memory)."""
+    if extra_tokens not in _SWEEP_INPUTS:
+        _SWEEP_INPUTS.clear()
+        _SWEEP_INPUTS[extra_tokens] = W.generate(W.SWEEP_BASE.replace(extra_tokens=extra_tokens))
+    return _SWEEP_INPUTS[extra_tokens]
+
+
+@pytest.mark.parametrize("quant", ["none", "fp8"])
+@pytest.mark.parametrize("topk", W.SWEEP_TOPK)
+@pytest.mark.parametrize("extra_tokens", [0, 1])
+def test_sparsity_sweep_as_stated(extra_tokens, topk, quant):
+    """The sparsity sweep at its stated shape: B = 2, H = 40, N = 75,600 and the ragged 75,601 (a 17-token
+    last key block, an 81-token last query block), kept fractions 0.15 ... 0.01 (k = 177 ... 12 of 1182 key
+    blocks), bf16 and FP8 sparse branch.  One head of each batch item, first / middle / last query block:
+    mask of the whole head, output rows and L against the oracle."""
+    import dataclasses
+    base = sweep_inputs(extra_tokens)
+    w = base.workload.replace(name="sweep-%d-%s-%g" % (75600 + extra_tokens, quant, topk), quant=quant, topk_frac=topk)
+    pick = int(round(topk * 200)) + 7 * extra_tokens            # other heads at every point
+    heads = [(0, pick % w.H), (1, (pick * 3 + 11) % w.H)]
+    sampled_check(w, heads=heads, n_blocks=3, seed=pick, inp=dataclasses.replace(base, workload=w))
+
+
+def test_sweep_inputs_are_released():
+    _SWEEP_INPUTS.clear()
+
+
+@pytest.mark.parametrize("quant,d,H", [("none", 128, 12), ("fp8", 128, 12), ("none", 64, 12), ("int8", 64, 12)])
+def test_square_blocks_at_full_length(quant, d, H):
+    """b_q = b_kv = 64 (the other block shape the interface takes) at N = 32,760: 512 query blocks of 512 key
+    blocks, 97 % sparsity, sampled heads and query blocks as above."""
+    w = W.WAN_1P3B_97_FP8.replace(name="wan1.3b-97-bq64-%s-d%d" % (quant, d), block_q=64, d=d, H=H, quant=quant)
+    sampled_check(w, heads=[(0, 1), (0, H - 2)], n_blocks=5, seed=3)
+
+
+@pytest.mark.parametrize("name", ["image-dit-4k", "image-dit-4k-d64"])
+def test_image_sized_workloads(name):
+    """Image-generation-sized inputs (a 64 x 64 latent grid, 4,096 tokens): every head of one batch item in
+    full, mask, output rows and L."""
+    w = W.CONFIGS[name]
+    sampled_check(w, heads=[(0, 0), (w.B - 1, w.H - 1)], n_blocks=w.T_m, seed=4)
 
 
 def test_full_size_constant_values_and_dense_ratio():
@@ -161,6 +201,7 @@ def test_maximum_number_of_key_blocks_forward_and_backward():
     o = oracle_heads(inp, heads=[(0, 0)])[(0, 0)]
     assert check_mask(r["idx"][0, 0], o["R"], o["sel"]) == 0
     assert rel_l2(r["out"][0, 0], o["O"]) <= 2e-2
+    rows_ok(r["out"][0, 0], o["O"])
     np.testing.assert_allclose(r["lse"][0, 0], o["L"], rtol=0, atol=3e-2)
     dout = W.f32_to_bf16_bits(np.random.default_rng(13).normal(size=(w.B, w.H, w.N, w.d)).astype(np.float32))
     alpha = inp.alpha.astype(np.float32)

@@ -5,7 +5,7 @@ left alone."""
 import numpy as np
 import pytest
 
-from helpers import oracle_heads, rel_l2, run_forward
+from helpers import oracle_heads, rel_l2, rows_ok, run_forward
 from paper_2602_12675_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -58,6 +58,7 @@ def test_strided_call_equals_contiguous_call(w):
     assert np.all(guard == 7.0)                            # nothing written between the rows
     o = oracle_heads(inp, heads=[(0, 0)])[(0, 0)]
     assert rel_l2(got[0, 0], o["O"]) <= (5e-2 if w.quant != "none" else 2e-2)
+    rows_ok(got[0, 0], o["O"], w.quant)
 
 
 def test_strided_router_and_dense():
