@@ -315,7 +315,7 @@ template <int D, int BQ, bool FP8, bool VQ = false> struct AttnSmem {
 
 
 template <int D, int BQ, int MODE>
-__global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_mfma_kernel(
+__global__ __launch_bounds__(BQ * 2, ((D == 128 && BQ == 64) || BQ == 256) ? 1 : 2) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const double* __restrict__ k_mean, const uint16_t* __restrict__ k_phi, const float* __restrict__ z_blocks,
     const uint8_t* __restrict__ k_codes, const float* __restrict__ k_scale, const uint8_t* __restrict__ v_codes,
@@ -637,7 +637,14 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
 #pragma unroll
       for (int e = 0; e < 16; e++) mx = fmaxf(mx, sacc[mt][e]);
     mx = half_max(mx) * c1;
-    const float m_new = fmaxf(m_run, mx);            // finite: a tile holds at least one key
+    // The reference of the exponentials.  With P rounded to a grid (low-bit modes) it is the running maximum,
+    // as Alg. 2 states it.  Otherwise any reference gives the same O / l, and the one in use is kept while the
+    // maximum of the row stays within 2^kLazy of it: O^T, l then need no rescaling in most tiles (the weights
+    // reach at most 2^kLazy, harmless in bf16 and fp32).  The decision is taken for the whole wave.
+    constexpr float kLazy = 8.f;
+    bool rescale = true;
+    if constexpr (!FP8) rescale = __builtin_amdgcn_ballot_w64(mx > m_run + kLazy) != 0;   // first tile: m_run = -inf
+    const float m_new = rescale ? fmaxf(m_run, mx) : m_run;   // finite: a tile holds at least one key
     const float m_off = m_new - kPShift;
     float rs = 0.f;
     bf16x8 pf[FP8V ? 1 : 4];                         // P^T fragments, token order
@@ -668,15 +675,18 @@ __global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_m
         }
       }
     rs = half_sum(rs);
-    const float corr = fast_exp2(m_run - m_new);     // 0 on the first tile
-    l_run = l_run * corr + rs;
-    m_run = m_new;
-    const float corr_o = FP8V ? corr * (sv_prev / sv) : corr;   // FP8V: also from the last tile's V scale to this one's
-    sv_prev = sv;
+    if (rescale) {
+      const float corr = fast_exp2(m_run - m_new);   // 0 on the first tile
+      l_run *= corr;
+      m_run = m_new;
+      const float corr_o = FP8V ? corr * (sv_prev / sv) : corr;   // FP8V: also from the last tile's V scale to this one's
+      sv_prev = sv;
 #pragma unroll
-    for (int et = 0; et < ET; et++)
+      for (int et = 0; et < ET; et++)
 #pragma unroll
-      for (int e = 0; e < 16; e++) oacc[et][e] *= corr_o;
+        for (int e = 0; e < 16; e++) oacc[et][e] *= corr_o;
+    }
+    l_run += rs;
 
     if constexpr (!DENSE) __builtin_amdgcn_s_setprio(2);   // matrix products again
     if constexpr (!DENSE) {
@@ -1001,7 +1011,9 @@ hipError_t launch_dense_bf16(const Shape& s, const uint16_t* q, const uint16_t* 
                              hipStream_t stream) {
   AttnArgs a{q, k, v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, out, nullptr,
              SavedForBackward{nullptr, nullptr, nullptr, nullptr, nullptr}};
-  if (s.d == 128) return launch_attn_t<128, 128, kDenseBf16>(s, a, stream);
+  // d = 128: 256 query rows per workgroup (8 waves, one workgroup per CU) - every K / V tile staged in LDS then
+  // serves twice the rows, which is worth 9 % here (a dense pass stages the same tiles for every query block)
+  if (s.d == 128) return launch_attn_t<128, 256, kDenseBf16>(s, a, stream);
   return launch_attn_t<64, 128, kDenseBf16>(s, a, stream);
 }
 
