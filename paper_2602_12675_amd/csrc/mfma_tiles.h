@@ -235,12 +235,15 @@ template <int D, int NT> struct TileCopy {
 };
 
 // A global load the compiler does not track: no wait is generated for it, the caller waits with
-// wait_vmcnt<>() and then passes every loaded value through settle() before using it.
+// wait_vmcnt<>() and then passes every loaded value through settle() before using it.  The load and the
+// wait are compiler-level memory barriers ("memory" clobber): no other memory operation - in particular no
+// global -> LDS transfer, which shares the vmcnt counter - can be moved across them, so the number of
+// operations in flight between a load and its wait is the number written in the source.
 template <class T>
 __device__ __forceinline__ T load_untracked(const void* p) {
   T r;
-  if constexpr (sizeof(T) == 16) asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(p));
-  else asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p));
+  if constexpr (sizeof(T) == 16) asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(r) : "v"(p) : "memory");
+  else asm volatile("global_load_dword %0, %1, off" : "=v"(r) : "v"(p) : "memory");
   return r;
 }
 template <class T, bool UNTRACKED>
@@ -251,7 +254,7 @@ __device__ __forceinline__ T load_maybe_tracked(const void* p) {
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {
   static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N));
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 // Orders every later use of x after the preceding wait (volatile statements keep their order).
 template <class T>
