@@ -35,12 +35,14 @@ independently of itself) live in tests/test_oracle_pins.py:
                              all 256 codes built from the format's definition
   quant_block_int8           codes against a brute-force nearest-integer search;
                              range, symmetry, scale round trip
-  sparse_branch_lowbit       equals sparse_branch when the quantisers are made
-                             exact; small, bounded deviation otherwise.  The
-                             quantisation scheme itself (granularity, scale of
-                             P) is NOT fixed by the paper: parity unpinned for
-                             that choice, it is pinned only to the definition
-                             given in the docstring.
+  sparse_branch_lowbit,      equal sparse_branch when the quantisers are made exact; cases worked by hand
+  absorb_block, smooth_k_f32 (tests/test_oracle_lowbit_pins.py): weights that are powers of two and must
+                             come out exact, weights that need a fourth mantissa bit, a subnormal
+                             and a flushed weight, a maximum that moves between blocks, the
+                             float32 smoothing on inputs where the order of rounding shows; each
+                             of a dozen planted slips fails one of them.  The quantisation
+                             scheme itself (granularity, scale of P) is NOT fixed by the paper:
+                             what is pinned is the definition given in the docstrings.
 """
 from __future__ import annotations
 
@@ -290,75 +292,78 @@ def smooth_k_f32(K: np.ndarray) -> np.ndarray:
     return K.astype(np.float32) - mu32[None, :]
 
 
+def absorb_block(state, S, Vj, v_scale=1.0):
+    """One step of the running softmax of a block of query rows, with the weights rounded for the product.
+
+    `state` = (m, l, A) summarises the key blocks absorbed so far, per query row:
+        m   the largest score seen                                   [rows, 1]
+        l   sum over the keys seen of exp(score - m)                 [rows, 1]
+        A   sum over the keys seen of round(exp(score - m_then)) v, carried forward to the present m:
+            every time m grows to m', what has been added so far is scaled by exp(m - m')   [rows, d]
+    Absorbing a block with scores S [rows, keys] and values Vj [keys, d]:
+        m'  = max(m, largest score of each row of S)
+        w   = exp(S - m')                       the block's weights against the new maximum (<= 1)
+        l'  = exp(m - m') l + rowsum(w)         the un-rounded weights: l is what an exact softmax would have
+        A'  = exp(m - m') A + round(w) Vj v_scale
+    where round(.) puts a weight on the e4m3 grid after scaling by 2^8: round(w) = e4m3_round(w 2^8) / 2^8
+    (weights are at most 1 and 2^8 < 448, so nothing saturates; weights below 2^-18 round to zero).
+    This is the M_c[i, j] = 1 arm of the block loop of Alg. 2 with quant(P); the order of the three updates
+    - maximum, then the sum from the un-rounded weights, then the rounded product - is the algorithm's."""
+    m, l, A = state
+    m_new = np.maximum(m, S.max(axis=1, keepdims=True))
+    w = np.exp(S - m_new)
+    keep = np.exp(m - m_new)                                    # exp(-inf) = 0 for the first block
+    l_new = keep * l + w.sum(axis=1, keepdims=True)
+    w_rounded = e4m3_round((w * 2.0 ** P_SCALE_LOG2).astype(np.float32)).astype(np.float64) / 2.0 ** P_SCALE_LOG2
+    A_new = keep * A + (w_rounded @ Vj) * v_scale
+    return m_new, l_new, A_new
+
+
 def sparse_branch_lowbit(Q, K, V, sel, b_q: int, b_k: int, *, smooth: bool = True,
                          q_blocks=None, quant_block=None, quant_v: bool = False):
-    """Sparse branch with low-bit Q, K and P (Sec. 5), following the block loop
-    of Alg. 2 step by step, because with a rounded P the result depends on the
-    running maximum and therefore on the order of the blocks:
+    """Sparse branch with low-bit Q, K and P (Sec. 5; Alg. 2 with quant / dequant).  With a rounded P the
+    result depends on the running maximum and therefore on the order of the blocks, so it is not a plain
+    closed form: each query block starts from the empty state (m = -inf, l = 0, A = 0) and absorbs its
+    selected key blocks in ascending order through absorb_block, with the scores of block j taken from
+    the 8-bit codes,
+        S = (Qhat_i Khat_j^T) s_Qi s_Kj / sqrt(d)      (exact products of codes, then the two scales),
+    and O_s = A / l, L = m + log l at the end.
 
-      for each selected block j of row block i, ascending j:
-        S      = (Qhat_i Khat_j^T) * s_Qi * s_Kj / sqrt(d)       score
-        m_new  = max(m, rowmax S)                                running max
-        P      = exp(S - m_new)
-        l      = exp(m - m_new) l + rowsum(P)                    running sum
-        Ptilde = e4m3_round(P * 2^8) / 2^8                       quant(P)
-        O      = diag(exp(m - m_new)) O + Ptilde V_j
-      O_s = O / l                                                after the loop
-
-    Readings taken (the paper leaves all four open): FP8 e4m3 with one scale
-    per b_q x d block of Q and per b_k x d block of the smoothed K
-    (quant_block_e4m3); P is rounded with the fixed power-of-two scale 2^8
-    (P <= 1, 2^8 <= 448); l is accumulated from the un-rounded P (Alg. 2
-    updates l before it quantises P); V stays at its input values although Alg. 2
-    also quantises V (the workload definition keeps V in bf16).
+    Readings taken (the paper leaves all four open): FP8 e4m3 with one scale per b_q x d block of Q and per
+    b_k x d block of the smoothed K (quant_block_e4m3); P is rounded with the fixed power-of-two scale 2^8;
+    l is accumulated from the un-rounded P (Alg. 2 updates l before it quantises P); V stays at its input
+    values although Alg. 2 also quantises V (the workload definition keeps V in bf16).
     K is the raw K: smoothing is done here in float32 (smooth_k_f32).
-    `quant_block` is the quantiser of Q and K blocks: quant_block_e4m3 (the
-    default) or quant_block_int8; everything after the codes - the exact
-    product of codes, the two scales, the rounding of P - is the same.
-    `quant_v` takes the second product the way Alg. 2 prints it,
-    dequant(quant(P) quant(V_j)): V_j is quantised like a key block (e4m3, one
-    scale per b_k x d block over its existing tokens, quant_block_e4m3) and
-        O = diag(exp(m - m_new)) O + (Ptilde Vhat_j) s_Vj ;
-    the linear branch keeps the input V (Alg. 2 forms h_j from the unquantised
-    V_j).  Returns (O_s, L) like sparse_branch."""
+    `quant_block` is the quantiser of Q and K blocks: quant_block_e4m3 (the default) or quant_block_int8;
+    everything after the codes is the same.  `quant_v` takes the second product the way Alg. 2 prints it,
+    dequant(quant(P) quant(V_j)): V_j is quantised like a key block (e4m3, one scale per b_k x d block over
+    its existing tokens) and its scale multiplies the block's product; the linear branch keeps the input V
+    (Alg. 2 forms h_j from the unquantised V_j).  Returns (O_s, L) like sparse_branch."""
     if quant_block is None:
         quant_block = quant_block_e4m3
     N, d = Q.shape
     Kin = smooth_k_f32(K) if smooth else K.astype(np.float32)
     T_n = num_blocks(N, b_k)
-    Khat, sK = [], []
-    for j in range(T_n):
-        v, s = quant_block(Kin[j * b_k:min(N, (j + 1) * b_k)])
-        Khat.append(v.astype(np.float64))
-        sK.append(float(s))
+    key_rows = [slice(j * b_k, min(N, (j + 1) * b_k)) for j in range(T_n)]
+    Khat, sK = zip(*[quant_block(Kin[rows]) for rows in key_rows]) if T_n else ((), ())
     O = np.zeros((N, d), dtype=np.float64)
     L = np.full((N,), -np.inf, dtype=np.float64)
-    rscale = 1.0 / math.sqrt(d)
     for i in (range(sel.shape[0]) if q_blocks is None else q_blocks):
-        r0, r1 = i * b_q, min(N, (i + 1) * b_q)
-        Qhat, sQ = quant_block(Q[r0:r1].astype(np.float32))
-        Qhat = Qhat.astype(np.float64)
-        sQ = float(sQ)
-        m = np.full((r1 - r0, 1), -np.inf)
-        l = np.zeros((r1 - r0, 1))
-        acc = np.zeros((r1 - r0, d))
+        rows = slice(i * b_q, min(N, (i + 1) * b_q))
+        n_rows = rows.stop - rows.start
+        Qhat, sQ = quant_block(Q[rows].astype(np.float32))
+        state = (np.full((n_rows, 1), -np.inf), np.zeros((n_rows, 1)), np.zeros((n_rows, d)))
         for j in sel[i]:
-            c0, c1 = j * b_k, min(N, (j + 1) * b_k)
-            S = (Qhat @ Khat[j].T) * (sQ * sK[j]) * rscale
-            m_new = np.maximum(m, S.max(axis=1, keepdims=True))
-            P = np.exp(S - m_new)
-            corr = np.exp(m - m_new)
-            l = corr * l + P.sum(axis=1, keepdims=True)
-            Pt = e4m3_round((P * 2.0 ** P_SCALE_LOG2).astype(np.float32)).astype(np.float64) / 2.0 ** P_SCALE_LOG2
+            S = (Qhat.astype(np.float64) @ Khat[j].astype(np.float64).T) * (float(sQ) * float(sK[j])) / math.sqrt(d)
             if quant_v:
-                Vhat, sV = quant_block_e4m3(V[c0:c1].astype(np.float32))
-                acc = corr * acc + (Pt @ Vhat.astype(np.float64)) * float(sV)
+                Vhat, sV = quant_block_e4m3(V[key_rows[j]].astype(np.float32))
+                state = absorb_block(state, S, Vhat.astype(np.float64), float(sV))
             else:
-                acc = corr * acc + Pt @ V[c0:c1]
-            m = m_new
+                state = absorb_block(state, S, V[key_rows[j]])
         if len(sel[i]):
-            O[r0:r1] = acc / l
-            L[r0:r1] = (m + np.log(l))[:, 0]
+            m, l, A = state
+            O[rows] = A / l
+            L[rows] = (m + np.log(l))[:, 0]
     return O, L
 
 

@@ -197,17 +197,20 @@ def test_lowbit_hand_worked(case):
 SLIPS = {
     "P scaled by 2^7": ("P_SCALE_LOG2 = 8", "P_SCALE_LOG2 = 7"),
     "P scaled by 2^9 (saturates P = 1)": ("P_SCALE_LOG2 = 8", "P_SCALE_LOG2 = 9"),
-    "denominator from the rounded P": ("l = corr * l + P.sum(axis=1, keepdims=True)",
-                                       "l = corr * l + (e4m3_round((P * 256.0).astype(np.float32)).astype(np.float64) / 256.0).sum(axis=1, keepdims=True)"),
+    "denominator from the rounded P": ("l_new = keep * l + w.sum(axis=1, keepdims=True)",
+                                       "l_new = keep * l + (e4m3_round((w * 256.0).astype(np.float32)).astype(np.float64) / 256.0).sum(axis=1, keepdims=True)"),
     "subnormals flushed to zero": ("e = np.maximum(e - 1, -6)", "e = e - 1; a = np.where(a < 2.0 ** -6, 0.0, a)"),
     "no subnormals (normal spacing all the way down)": ("e = np.maximum(e - 1, -6)", "e = e - 1"),
     "P truncated instead of rounded": ("r = np.rint(a / quantum) * quantum", "r = np.floor(a / quantum) * quantum"),
     "smoothing in float64, rounded afterwards": ("return K.astype(np.float32) - mu32[None, :]",
                                                  "return (K - K.mean(axis=0)[None, :]).astype(np.float32)"),
-    "block scale applied once": ("* (sQ * sK[j]) * rscale", "* sK[j] * rscale"),
-    "P rounded against the final maximum": ("Pt = e4m3_round((P * 2.0 ** P_SCALE_LOG2)",
-                                            "Pt = e4m3_round((np.exp(S - _FINAL_M[r0:r1]) * 2.0 ** P_SCALE_LOG2)"),
-    "V scale dropped": ("(Pt @ Vhat.astype(np.float64)) * float(sV)", "(Pt @ Vhat.astype(np.float64))"),
+    "block scale applied once": ("* (float(sQ) * float(sK[j])) / math.sqrt(d)", "* float(sK[j]) / math.sqrt(d)"),
+    "P rounded against the final maximum": ("w_rounded = e4m3_round((w * 2.0 ** P_SCALE_LOG2)",
+                                            "w_rounded = e4m3_round((np.exp(S - _FINAL_M) * 2.0 ** P_SCALE_LOG2)"),
+    "V scale dropped": ("A_new = keep * A + (w_rounded @ Vj) * v_scale", "A_new = keep * A + (w_rounded @ Vj)"),
+    "old sum not carried to the new maximum": ("l_new = keep * l + w.sum(axis=1, keepdims=True)",
+                                               "l_new = l + w.sum(axis=1, keepdims=True)"),
+    "blocks absorbed in descending order": ("for j in sel[i]:", "for j in sel[i][::-1]:"),
 }
 
 
@@ -228,7 +231,7 @@ def test_planted_slip_is_noticed(name):
     mod = _oracle_with(old, new)
     if "_FINAL_M" in new:
         # the row maxima over all selected blocks of case (b): row 0 -> 0, row 1 -> 3
-        mod._FINAL_M = np.array([[0.0], [3.0], [0.0], [0.0], [0.0], [0.0]])
+        mod._FINAL_M = np.array([[0.0], [3.0]])
     failed = []
     for case in ([case_b] if "_FINAL_M" in new else CASES):
         try:
