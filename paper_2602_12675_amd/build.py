@@ -17,7 +17,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsla2.so")
 
-SOURCES = ["sla2_api.cpp", "sla2_pool.hip", "sla2_router.hip", "sla2_router_soft.hip", "sla2_static.hip", "sla2_f32.hip", "sla2_bwd.hip", "sla2_bwd_mfma.hip", "sla2_mfma.hip"]
+SOURCES = ["sla2_api.cpp", "sla2_pool.hip", "sla2_router.hip", "sla2_router_soft.hip", "sla2_static.hip", "sla2_f32.hip", "sla2_bwd.hip", "sla2_bwd_mfma.hip", "sla2_mfma.hip", "sla2_dense.hip"]
 
 # packed-fp32 instructions are switched off on purpose (known-bad forms on this hardware)
 HIPCC_FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-x", "hip",

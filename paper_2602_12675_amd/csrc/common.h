@@ -143,6 +143,8 @@ hipError_t launch_attn_bf16(const Shape& s, const uint16_t* q, const uint16_t* k
                             const float* h_total, const float* z_total,
                             const int32_t* block_idx, const float* alpha, uint16_t* out, float* lse,
                             const SavedForBackward& sv, hipStream_t stream);
+hipError_t launch_dense_pp(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
+                           hipStream_t stream);
 hipError_t launch_dense_bf16(const Shape& s, const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
                              hipStream_t stream);
 

@@ -9,6 +9,8 @@
 // contraction index in that same order: "token order" below is
 //      token(ks, g, kappa) = 16 ks + 8 (kappa / 4) + 4 g + kappa % 4,   kappa = 0..7.
 #pragma once
+#include <type_traits>
+
 #include "common.h"
 
 namespace sla2 {
@@ -42,6 +44,22 @@ template <int D> struct SwizzledLayout {
   static constexpr int kRowElems = D;
   static constexpr int kTileBytes = kTileTokens * D * 2;
   __device__ static __forceinline__ int swz(int row) { return kChunks >= 16 ? 2 * (row & 7) : (row & 7); }
+  __device__ static __forceinline__ int offset(int row, int col) {
+    return row * D + (((col >> 3) ^ swz(row)) << 3) + (col & 7);
+  }
+};
+
+// The same with a permutation that also serves the transposing 8-byte reads without bank conflicts (16 chunks
+// per row only).  The row-wise 16-byte read of 16 consecutive rows needs 16 different chunk positions, so the
+// permutation is a bijection of row % 16; the transposing read touches 4 consecutive rows x 4 consecutive
+// chunks at a time and needs those 16 positions different as well, which the two low row bits provide by
+// moving the chunk by multiples of 4:  position = chunk ^ (4 (row % 4) + (row / 4) % 4).
+template <int D> struct SwizzledLayoutB {
+  static_assert(D == 128, "16 chunks of 16 bytes per row");
+  static constexpr int kChunks = 16;
+  static constexpr int kRowElems = D;
+  static constexpr int kTileBytes = kTileTokens * D * 2;
+  __device__ static __forceinline__ int swz(int row) { return ((row & 3) << 2) | ((row >> 2) & 3); }
   __device__ static __forceinline__ int offset(int row, int col) {
     return row * D + (((col >> 3) ^ swz(row)) << 3) + (col & 7);
   }
@@ -96,13 +114,13 @@ __device__ __forceinline__ bf16x8 row_fragment(const uint16_t* tile, int row, in
 // Completion is counted by vmcnt.  Rows past `valid` (ragged last tile) repeat the last row.  One
 // straight-line sequence for full and ragged tiles alike: the number of transfers in flight is then
 // the same on every path, which lets later waits be counted instead of draining everything.
-template <int D, int NW>
+template <int D, int NW, class L = SwizzledLayout<D>>
 __device__ __forceinline__ void dma_tile(const uint16_t* src /* first row */, int row_stride /* elements */, int valid,
                                          uint16_t* tile, int w, int lane) {
-  typedef SwizzledLayout<D> L;
   constexpr int kRowsPerInstr = 1024 / (D * 2);
   constexpr int kInstrs = kTileTokens / kRowsPerInstr / NW;
-  static_assert((kRowsPerInstr * NW) % 8 == 0, "row swizzle must repeat between the instructions of a wave");
+  static_assert((kRowsPerInstr * NW) % 16 == 0 || (std::is_same<L, SwizzledLayout<D>>::value && (kRowsPerInstr * NW) % 8 == 0),
+                "row swizzle must repeat between the instructions of a wave");
   const int row_w = w * kRowsPerInstr + lane / L::kChunks;           // row of instruction 0
   const unsigned col_bytes = 16u * (unsigned)((lane % L::kChunks) ^ L::swz(row_w));
   const char* base = reinterpret_cast<const char*>(src);

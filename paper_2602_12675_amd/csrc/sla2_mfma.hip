@@ -315,7 +315,7 @@ template <int D, int BQ, bool FP8, bool VQ = false> struct AttnSmem {
 
 
 template <int D, int BQ, int MODE>
-__global__ __launch_bounds__(BQ * 2, ((D == 128 && BQ == 64) || BQ == 256) ? 1 : 2) void attn_mfma_kernel(
+__global__ __launch_bounds__(BQ * 2, (D == 128 && BQ == 64) ? 1 : 2) void attn_mfma_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const double* __restrict__ k_mean, const uint16_t* __restrict__ k_phi, const float* __restrict__ z_blocks,
     const uint8_t* __restrict__ k_codes, const float* __restrict__ k_scale, const uint8_t* __restrict__ v_codes,
@@ -1011,9 +1011,9 @@ hipError_t launch_dense_bf16(const Shape& s, const uint16_t* q, const uint16_t* 
                              hipStream_t stream) {
   AttnArgs a{q, k, v, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, out, nullptr,
              SavedForBackward{nullptr, nullptr, nullptr, nullptr, nullptr}};
-  // d = 128: 256 query rows per workgroup (8 waves, one workgroup per CU) - every K / V tile staged in LDS then
-  // serves twice the rows, which is worth 9 % here (a dense pass stages the same tiles for every query block)
-  if (s.d == 128) return launch_attn_t<128, 256, kDenseBf16>(s, a, stream);
+  // d = 128: the kernel of its own in sla2_dense.hip (256 query rows per workgroup, the two waves of a SIMD
+  // in opposite phases)
+  if (s.d == 128) return launch_dense_pp(s, q, k, v, out, stream);
   return launch_attn_t<64, 128, kDenseBf16>(s, a, stream);
 }
 

@@ -126,8 +126,19 @@ def test_forward_bf16_deterministic():
     assert np.array_equal(a["out"], b["out"]) and np.array_equal(a["lse"], b["lse"])
 
 
-@pytest.mark.parametrize("w", [CASES[0], CASES[1], BASE.replace(name="dense-d64", grid=(3, 11, 31), d=64, block_q=128)],
-                         ids=lambda w: w.name)
+DENSE_CASES = [CASES[0], CASES[1], BASE.replace(name="dense-d64", grid=(3, 11, 31), d=64, block_q=128),
+               # the d = 128 kernel works on 256 query rows and on tiles of 64 keys through three buffers: lengths of one
+               # row, less than a tile, one, two and three tiles with a tail, and a tail of one query row and one key
+               BASE.replace(name="dense-N1", grid=(1, 1, 1), d=128, block_q=128, H=2),
+               BASE.replace(name="dense-N50", grid=(1, 5, 10), d=128, block_q=128, H=2),
+               BASE.replace(name="dense-N64", grid=(1, 8, 8), d=128, block_q=128, H=2),
+               BASE.replace(name="dense-N130", grid=(1, 10, 13), d=128, block_q=128, H=2),
+               BASE.replace(name="dense-N200", grid=(1, 10, 20), d=128, block_q=128, H=2),
+               BASE.replace(name="dense-N769", grid=(1, 1, 769), d=128, block_q=128, B=2, H=3),
+               BASE.replace(name="dense-N2049", grid=(1, 3, 683), d=128, block_q=128, H=2)]
+
+
+@pytest.mark.parametrize("w", DENSE_CASES, ids=lambda w: w.name)
 def test_dense_baseline_matches_dense_attention(w):
     """The in-build comparator against the oracle with every block kept and
     alpha = 1 (= softmax(QK^T/sqrt d)V, pinned to the textbook routine)."""
