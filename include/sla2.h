@@ -182,7 +182,11 @@ int sla2_router_soft(const sla2_params* params, const void* q, const void* k, co
  * per-head total of h_j, z_j minus the selected blocks - and the alpha mix.
  * alpha values are used as given (the caller keeps them in [0,1]).  A query
  * block with no selected block has O_s = 0; one with every block selected has
- * O_l = 0.
+ * O_l = 0.  The subtraction is taken in fp32 on fp32 totals; when all but a few
+ * blocks are selected (k close to T_n) the linear branch is the small difference
+ * of two large sums and carries their rounding (bf16 tensors: the selected blocks'
+ * h_j are rebuilt from bf16 operands) - measured at k = T_n - 1 with a one-token
+ * last block it stays inside the tolerances stated for each precision mode.
  * out:               [B, H, N, d] of params->dtype.
  * block_idx_or_null: if non-null receives the mask as in sla2_router.
  * lse_or_null:       if non-null receives float [B, H, N]: L = m + log l of the
