@@ -135,7 +135,9 @@ DENSE_CASES = [CASES[0], CASES[1], BASE.replace(name="dense-d64", grid=(3, 11, 3
                BASE.replace(name="dense-N130", grid=(1, 10, 13), d=128, block_q=128, H=2),
                BASE.replace(name="dense-N200", grid=(1, 10, 20), d=128, block_q=128, H=2),
                BASE.replace(name="dense-N769", grid=(1, 1, 769), d=128, block_q=128, B=2, H=3),
-               BASE.replace(name="dense-N2049", grid=(1, 3, 683), d=128, block_q=128, H=2)]
+               BASE.replace(name="dense-N2049", grid=(1, 3, 683), d=128, block_q=128, H=2)] + [
+    # around the 256-row workgroup and the three-buffer period
+    BASE.replace(name="dense-N%d" % n, grid=(1, 1, n), d=128, block_q=128, H=2) for n in (191, 255, 256, 257, 385, 513)]
 
 
 @pytest.mark.parametrize("w", DENSE_CASES, ids=lambda w: w.name)
