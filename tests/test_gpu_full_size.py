@@ -104,6 +104,13 @@ def test_square_blocks_at_full_length(quant, d, H):
     sampled_check(w, heads=[(0, 1), (0, H - 2)], n_blocks=5, seed=3)
 
 
+@pytest.mark.parametrize("quant", ["none", "fp8"])
+def test_head_dimension_64_at_full_length(quant):
+    """d = 64 with 128-row query blocks at N = 32,760, 24 heads: the shape whose kernel runs three waves per SIMD."""
+    w = W.WAN_1P3B_97_FP8.replace(name="wan1.3b-97-d64-%s" % quant, d=64, H=24, quant=quant)
+    sampled_check(w, heads=[(0, 0), (0, 23)], n_blocks=5, seed=5)
+
+
 @pytest.mark.parametrize("name", ["image-dit-4k", "image-dit-4k-d64"])
 def test_image_sized_workloads(name):
     """Image-generation-sized inputs (a 64 x 64 latent grid, 4,096 tokens): every head of one batch item in
