@@ -137,6 +137,28 @@ def test_full_size_constant_values_and_dense_ratio():
     assert np.abs(dense - cv).max() <= 3e-2
 
 
+@pytest.mark.parametrize("name", ["wan1.3b-97-fp8", "wan14b-97-fp8"])
+def test_dense_comparator_at_full_length(name):
+    """The dense comparator on the benchmark inputs (512 and 1,182 key tiles per row) against the oracle's sparse
+    branch with every key block kept (= softmax(Q K^T / sqrt d) V): the first query blocks, those around the first
+    256-row workgroup boundaries, a few from the middle, and the ragged last ones."""
+    import torch
+    import sla2_oracle as O
+    from paper_2602_12675_amd import api
+    w = W.CONFIGS[name].replace(H=3)
+    inp = W.generate(w)
+    out = run_dense(api, torch, inp)
+    rng = np.random.default_rng(6)
+    blocks = sorted(set([0, 1, 2, 3, w.T_m - 3, w.T_m - 2, w.T_m - 1] + [int(x) for x in rng.integers(0, w.T_m, 4)]))
+    every = np.tile(np.arange(w.T_n), (w.T_m, 1))
+    for h in (0, 2):
+        Q, K, V = (inp.values(x, 0, h) for x in ("q", "k", "v"))
+        ref, _ = O.sparse_branch(Q, K, V, every, w.block_q, w.block_kv, q_blocks=blocks)
+        rows = np.concatenate([np.arange(i * w.block_q, min(w.N, (i + 1) * w.block_q)) for i in blocks])
+        assert rel_l2(out[0, h][rows], ref[rows]) <= 2e-2
+        rows_ok(out[0, h][rows], ref[rows])
+
+
 @pytest.mark.parametrize("quant", ["fp8", "none"])
 def test_wan_1p3b_backward_full_size(quant):
     """The backward pass at the benchmark size (32,760 tokens, 12 heads, 97 % sparsity), after the forward
