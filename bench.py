@@ -315,15 +315,22 @@ def main():
     torch.cuda.synchronize()
     stride = max(1, args.event_stride)
     api.sla2_profile_begin_sampled(["attn"], (args.steps + stride - 1) // stride, stride)
+    # one event per step boundary (same stream as the kernels): the spread of the K calls, next to their mean
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    marks[0].record()
     for i in range(args.steps):
         step(i)
+        marks[i + 1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     prof = api.sla2_profile_end()
     ms_per_step = elapsed / args.steps * 1e3
     value = dense_flops / (ms_per_step * 1e-3) / 1e12
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+    step_ms = {"median": round(per_step[len(per_step) // 2], 4), "min": round(per_step[0], 4), "max": round(per_step[-1], 4),
+               "note": "GPU time between event marks after each of the K timed calls"}
 
     # The dense comparator, after two untimed calls of its own (the chip is at its sustained clocks by then:
     # a comparator timed cold would flatter the ratio).
@@ -442,6 +449,7 @@ def main():
                    "sparsity": round(1.0 - ksel / w.T_n, 4), "quant": w.quant, "input_sets": len(sets),
                    "router": "identity weights (pooled-QK router)" if args.router_identity else "random projections",
                    "layout": "packed [B,N,3,H,d] -> [B,N,H,d]" if args.packed_qkv else "[B,H,N,d]"},
+        "step_ms": step_ms,
         "roofline": roofline,
         "order": "W warm-up + K timed calls = value; dense comparator; one-input-set pass; per-kernel pass; the K calls again = settled; backward",
         "settled": settled,

@@ -57,4 +57,5 @@ def test_result_line_carries_the_required_objects():
     settled = d["settled"]
     assert settled["steps"] == 4 and settled["ms_per_step"] > 0 and "order" in d and d["order"].startswith("W warm-up + K timed calls = value")
     assert roof["traffic_source"].startswith("profiles/")
+    assert 0 < d["step_ms"]["min"] <= d["step_ms"]["median"] <= d["step_ms"]["max"]
     assert d["dense_bf16"]["ms"] > d["ms_per_step"] and abs(d["speedup_vs_dense_bf16"] - d["dense_bf16"]["ms"] / d["ms_per_step"]) < 0.02 * d["speedup_vs_dense_bf16"]
